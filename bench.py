@@ -1,0 +1,134 @@
+"""Benchmark of the fixed-point inference hot path on one MI355X.
+
+One step = one forward pass of the whole fixed-point ResNet-50 (stride on the 3x3 of the
+bottleneck) over a batch of 256 seeded synthetic 224x224x3 images that already sit in HBM:
+53 dense layers + FC on the int8 matrix cores with the shift/clip epilogue, max pool,
+global pool.  Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 matrix peak, TOP/s
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak, GB/s
+
+
+def cpu_baseline(net, x, threads, images):
+    """The CPU oracle as it stands, on `images` images of the same workload, one image per
+    host thread (the C code itself is single-threaded)."""
+    import numpy as np
+    from oracle import ref
+    xs = np.ascontiguousarray(x[:images])
+    t0 = time.perf_counter()
+    ref.run_network_parallel(net, xs, threads)
+    dt = time.perf_counter() - t0
+    return {"value": images / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of the %d images of the batch, full 224x224 ResNet-50 forward, one image per "
+                      "host thread, %.1f s wall" % (images, x.shape[0], dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+              "(the path shards by batch with no communication; see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2202_05239_amd import binding as f8
+    from paper_2202_05239_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    f8.lib()     # fails loudly if the HIP library is missing
+
+    if args.net == "resnet50":
+        x, net = wl.config4(batch=args.batch)
+    else:
+        x, net = wl.config3(batch=args.batch)
+    B = x.shape[0]
+    xt = torch.from_numpy(x).to("cuda")
+    chain = f8.Chain(net).prepare(B)
+    out = torch.empty((B,) + chain.out_shape, dtype=chain.out_dtype, device="cuda")
+
+    for _ in range(args.warmup):
+        chain.run(xt, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        chain.run(xt, out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    images_per_s = B / (dt / args.steps)
+
+    # Per-kernel device time of the same steps, HIP events on the launch stream.
+    layer_ms = chain.profile(xt, out, repeats=max(1, args.steps))
+    rows, by_kernel = [], {}
+    for i, (L, ms) in enumerate(zip(net.layers, layer_ms)):
+        kname, ops, nbytes = chain.layer_info(i, B)
+        t = ms * 1e-3
+        tops, gbs = ops / t / 1e12, nbytes / t / 1e9
+        t_mfma, t_hbm = ops / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        rows.append({"layer": L.name, "kernel": kname, "us": ms * 1e3, "TOPS": tops,
+                     "pct_mfma_peak": 100 * tops / PEAK_INT8_TOPS, "alg_GBs": gbs,
+                     "pct_hbm_peak": 100 * gbs / PEAK_HBM_GBS,
+                     "binds": "mfma" if t_mfma > t_hbm else "hbm",
+                     "pct_of_roofline": 100 * max(t_mfma, t_hbm) / t})
+        k = by_kernel.setdefault(kname, {"ms": 0.0, "ops": 0.0, "bytes": 0.0, "launches": 0})
+        k["ms"] += ms; k["ops"] += ops; k["bytes"] += nbytes; k["launches"] += 1
+    dom = max(by_kernel, key=lambda n: by_kernel[n]["ms"])
+    d = by_kernel[dom]
+    t_m, t_h = d["ops"] / (PEAK_INT8_TOPS * 1e12), d["bytes"] / (PEAK_HBM_GBS * 1e9)
+    if t_m >= t_h:
+        ach = d["ops"] / (d["ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": ach / PEAK_INT8_TOPS}
+    else:
+        ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    roof.update({"traffic": None, "kernel": dom, "launches_per_step": d["launches"],
+                 "avg_launch_us": d["ms"] * 1e3 / d["launches"],
+                 "alg_ops_per_step": d["ops"], "alg_bytes_per_step": d["bytes"],
+                 "sum_layer_ms": sum(layer_ms)})
+    if args.layers:
+        with open(args.layers, "w") as f:
+            json.dump({"layers": rows, "kernels": by_kernel}, f, indent=1)
+
+    total_ops = sum(2.0 * L.macs_per_image * B for L in net.layers)
+    rec = {
+        "metric": "images/s, fixed-point %s forward (int8 conv on MFMA + shift/clip epilogue), batch %d, 1 GPU"
+                  % ("ResNet-50" if args.net == "resnet50" else "ResNet-18", B),
+        "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[4]: full %s fixed-point forward, batch %d, 224x224x3, seeded FL per layer"
+                               % (net.name, B),
+                   "global_batch": B, "input": "224x224x3 int8", "layers": len(net.layers)},
+        "whole_net_TOPS": total_ops / (dt / args.steps) / 1e12,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        threads = max(1, min(16, os.cpu_count() or 1, 8))
+        rec["cpu_baseline"] = cpu_baseline(net, x, threads, threads)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

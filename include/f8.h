@@ -1,0 +1,195 @@
+/*
+ * f8 — 8-bit fixed-point inference layers for AMD MI355X (gfx950), C ABI.
+ *
+ * What a layer computes (F8Net, arXiv 2202.05239).  An 8-bit integer X with fractional
+ * length FL stands for the real number X * 2^-FL (Sec. 3.1; word length 8 everywhere,
+ * Sec. 4.3).  One layer is Eq. 6:  q_out = fix_quant( sum_j Weff_ij q_j + beff_i ),
+ * fix_quant being Eq. 2 (unsigned, range 0..255, which is also the ReLU) or Eq. 9
+ * (signed, range -127..127).  With q = X 2^-FL_x, Weff = W 2^-FL_w and the effective
+ * bias held as a 32-bit integer B at the accumulator scale FL_x + FL_w this is
+ *
+ *     A      = sum_k X[k] * W[k] + B                      int8 x int8 -> int32
+ *     A     += align(R)                                   optional residual (Sec. 4.3)
+ *     Y      = clip( shift_round(A, s), clip_lo, clip_hi ),   s = FL_x + FL_w - FL_y
+ *
+ *     shift_round(a, s) = floor((a + 2^(s-1)) / 2^s)  for s >= 1   (round half up)
+ *                       = a                           for s == 0
+ *                       = a * 2^-s                    for s <  0
+ *     align(r) = r * 2^d               for d = FL_x + FL_w - FL_res >= 0
+ *              = shift_round(r, -d)    for d < 0
+ *
+ * Rescaling is the shift only: no 32-bit or floating-point multiply (Fig. 1(d), Sec. 1).
+ * The result is one exactly defined integer tensor; the library reproduces it bit for
+ * bit whatever tiling it uses, because integer addition is associative.
+ *
+ * Conventions for every entry point
+ *   - Tensor pointers (x, w, bias, y, q->res, workspace) are DEVICE pointers owned by
+ *     the caller; the struct pointers (q, layer descriptors) are HOST pointers read
+ *     before the call returns.  Activations are NHWC, channel fastest.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously; the library never synchronises.
+ *   - Arguments are validated on the host before anything is launched; a call that
+ *     returns an error has launched nothing.  Errors are status codes, never aborts.
+ *   - Preconditions the library cannot check (they depend on device data): A and
+ *     A + 2^(s-1) fit in int32 (the paper keeps accumulators in 32 bits, Sec. 4.3).
+ *     K <= 65536 is enforced so that sum |X*W| alone cannot overflow.
+ *   - x, w, y must not overlap.  q->res may be any tensor of y's shape except y itself.
+ *   - The single-layer calls keep a small device scratch buffer per stream (the folded
+ *     accumulator start value, 4 bytes per output channel), allocated on first use and
+ *     released by f8_release_scratch() or at process exit.  Calls on different streams
+ *     never share it; calls on one stream are ordered by the stream.
+ */
+#ifndef F8_H
+#define F8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  F8_OK = 0,
+  F8_ERR_NULL = 1,          /* a required pointer is NULL                                  */
+  F8_ERR_SHAPE = 2,         /* a dimension is out of range (negative, K > 65536, ...)      */
+  F8_ERR_FL = 3,            /* shift s outside [-8, 24] or residual shift outside [-24,24] */
+  F8_ERR_CLIP = 4,          /* clip bounds outside the output type's range or lo > hi      */
+  F8_ERR_DTYPE = 5,         /* type code not allowed for that operand                      */
+  F8_ERR_ACC_OVERFLOW = 6,  /* reserved: reported by checkers that can see the data        */
+  F8_ERR_ALIGN = 7,         /* int32 operand (bias, int32 y or residual) not 4-byte aligned */
+  F8_ERR_UNSUPPORTED = 8,   /* valid but not implemented (tensor beyond 2^31-1 bytes, ...) */
+  F8_ERR_DEVICE = 9,        /* the HIP runtime reported an error                           */
+  F8_ERR_STATE = 10         /* chain used before f8_chain_prepare on that workspace        */
+} f8_status;
+
+typedef enum { F8_U8 = 0, F8_S8 = 1, F8_S32 = 2 } f8_dtype;
+
+/* Per-call quantisation parameters (Eq. 2 / Eq. 9 / Eq. 6 in integer form). */
+typedef struct {
+  int32_t fl_x, fl_w, fl_y;   /* fractional lengths of input, weight and output             */
+  int32_t clip_lo, clip_hi;   /* clip bounds in output LSBs (2^-fl_y).                      */
+                              /* U8: 0 <= lo <= hi <= 255.  S8: -127 <= lo <= hi <= 127.    */
+  int32_t x_type;             /* F8_U8 or F8_S8                                             */
+  int32_t y_type;             /* F8_U8, F8_S8, or F8_S32 = write A itself (logits); then    */
+                              /* fl_y and the clip bounds are ignored                       */
+  const void *res;            /* device pointer: residual of y's shape, or NULL             */
+  int32_t res_type;           /* F8_U8, F8_S8 or F8_S32                                     */
+  int32_t fl_res;             /* fractional length of the residual                          */
+} f8_quant;
+
+/* Eq. 6 for a fully connected layer / 1x1 convolution.
+ * x [M][K] 8-bit, w [N][K] int8, bias [N] int32 or NULL, y [M][N] (8-bit or int32). */
+f8_status f8_gemm_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y,
+                        int M, int K, int N, const f8_quant *q, void *stream);
+
+/* Eq. 6 for a convolution, implicit GEMM with M = B*P*Q, K = R*S*Cin, N = Cout.
+ * x NHWC [B][H][W][Cin], w [Cout][R][S][Cin] int8, bias [Cout] or NULL,
+ * y NHWC [B][P][Q][Cout], P = floor((H + 2 pad_h - R) / stride_h) + 1, Q likewise.
+ * Padding is the real value 0. */
+f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y,
+                          int B, int H, int W, int Cin, int Cout, int R, int S,
+                          int stride_h, int stride_w, int pad_h, int pad_w,
+                          const f8_quant *q, void *stream);
+
+/* Eq. 6 for a depthwise convolution (MobileNet V1/V2 layers of Sec. 5): K = R*S taps
+ * per channel, no sum across channels.  x NHWC [B][H][W][C], w [R][S][C] int8,
+ * bias [C] or NULL, y NHWC [B][P][Q][C].  R*S <= 49. */
+f8_status f8_dwconv_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y,
+                          int B, int H, int W, int C, int R, int S,
+                          int stride_h, int stride_w, int pad_h, int pad_w,
+                          const f8_quant *q, void *stream);
+
+/* Max pooling on 8-bit fixed-point activations (ResNet stem, Sec. 5 models).  The
+ * quantiser of Eq. 2 is monotone, so the max of the integers is the quantised max and
+ * the fractional length is unchanged.  Padding never wins; requires pad < window.
+ * x NHWC [B][H][W][C], y NHWC [B][P][Q][C], both of type `dtype` (F8_U8 or F8_S8). */
+f8_status f8_maxpool(const void *x, void *y, int B, int H, int W, int C, int R, int S,
+                     int stride_h, int stride_w, int pad_h, int pad_w, int dtype, void *stream);
+
+/* Global pooling as a fixed-point layer whose weights are all the integer 1 at
+ * fractional length q->fl_w (the real weight 2^-fl_w):  y[b][c] = requant(sum_hw x).
+ * With fl_w = ceil(log2(H*W)) and fl_y = fl_x this is the average up to the factor
+ * 2^fl_w / (H*W), which belongs in the next layer's effective weights the way Eq. 6
+ * absorbs every full-precision scale.  x NHWC [B][H][W][C], y [B][C].  H*W <= 65536.
+ * q->res must be NULL. */
+f8_status f8_global_pool_fixed(const void *x, void *y, int B, int H, int W, int C,
+                               const f8_quant *q, void *stream);
+
+/* ---- layer-chain runner: a whole fixed-point network forward (Sec. 5 models) ---- */
+
+typedef enum { F8_OP_CONV = 0, F8_OP_DWCONV = 1, F8_OP_MAXPOOL = 2, F8_OP_GPOOL = 3 } f8_op;
+
+/* One layer.  Tensors are numbered: 0 is the network input, layer i writes tensor
+ * `dst` (> 0, each id written once, before it is read).  q.res is ignored; the residual
+ * is the tensor `res` (or -1), whose type and fractional length go in q.res_type and
+ * q.fl_res.  w and bias are device pointers that must stay valid while the chain lives. */
+typedef struct {
+  int32_t op;                       /* f8_op                                            */
+  int32_t src, dst, res;            /* tensor ids; res = -1 for none                    */
+  int32_t Cin, Cout, R, S;          /* pools: Cout == Cin; GPOOL ignores R,S            */
+  int32_t stride_h, stride_w, pad_h, pad_w;
+  f8_quant q;
+  const int8_t *w;                  /* CONV [Cout][R][S][Cin]; DWCONV [R][S][C]; else NULL */
+  const int32_t *bias;              /* [Cout] or NULL                                   */
+} f8_layer_desc;
+
+typedef struct f8_chain f8_chain;
+
+/* Checks every layer (shapes, types and fractional lengths must chain), plans which
+ * tensors share memory.  in_type is the type of tensor 0 (F8_U8 / F8_S8). */
+f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, int in_w,
+                          int in_c, int in_type, f8_chain **out);
+/* Bytes of device workspace needed for `batch` images (activations + folded constants). */
+f8_status f8_chain_workspace_bytes(const f8_chain *c, int batch, size_t *bytes);
+/* Writes the folded per-channel constants into the workspace; once per workspace and
+ * batch size, before f8_chain_run. */
+f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream);
+/* Runs all layers on x (tensor 0, NHWC, `batch` images); the last layer's output is
+ * written to `out` (its own type; NHWC).  Must follow f8_chain_prepare with the same
+ * workspace and batch.  Only kernel launches are enqueued, so the call can be captured
+ * into a HIP graph. */
+f8_status f8_chain_run(f8_chain *c, const void *x, void *out, void *workspace, int batch,
+                       void *stream);
+/* Where tensor `id` lives after a run (for per-layer checks): pointer inside the
+ * workspace (or NULL for ids 0 and the last tensor), shape and type.  Tensors whose
+ * memory was reused by a later layer are reported with *live_at_end = 0. */
+f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch, void **ptr,
+                          int *h, int *w, int *ch, int *dtype, int *live_at_end);
+/* With keep_all != 0 no two tensors share memory (bigger workspace, every intermediate
+ * can be inspected).  Call before f8_chain_workspace_bytes. */
+f8_status f8_chain_set_keep_all(f8_chain *c, int keep_all);
+void f8_chain_destroy(f8_chain *c);
+
+/* Measurement aids for the chain (not on the hot path).
+ * f8_chain_layer_info: name of the kernel layer `layer` launches (copied into
+ *   kernel_name, at most name_len bytes with the terminator) and the layer's algorithmic
+ *   work for `batch` images: operations (2 per multiply-accumulate; 0 for pools) and
+ *   bytes (every operand and result touched once).
+ * f8_chain_profile: runs the chain `repeats` times like f8_chain_run with a HIP event
+ *   recorded on `stream` before and after every layer, waits for the stream, and writes
+ *   each layer's mean device time in milliseconds to layer_ms[f8_chain_num_layers]. */
+int f8_chain_num_layers(const f8_chain *c);
+f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *kernel_name,
+                              int name_len, double *alg_ops, double *alg_bytes);
+f8_status f8_chain_profile(f8_chain *c, const void *x, void *out, void *workspace, int batch,
+                           void *stream, int repeats, float *layer_ms);
+
+/* ---- helpers (host side, set-up only) ---- */
+
+/* A PACT clipping level alpha (Eq. 3) expressed in output LSBs for fractional length
+ * fl_y: min(type max, round_half_up(alpha * 2^fl_y)), at least 0.  With the paper's
+ * folding (Eq. 4-6) alpha is absorbed into the effective weights and the bound is the
+ * full range; this helper serves callers that keep an explicit level. */
+int32_t f8_clip_from_alpha(double alpha, int fl_y, int is_signed);
+const char *f8_status_str(f8_status s);
+/* Frees the per-stream scratch buffers of the single-layer calls (after the caller has
+ * synchronised the streams that used them). */
+void f8_release_scratch(void);
+/* Library version, for the binding to check that it loaded what it was built against. */
+int f8_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,38 @@
+// Dense fixed-point convolution / GEMM as an implicit GEMM on the int8 matrix cores.
+#pragma once
+
+#include "f8_device.h"
+
+namespace f8 {
+
+// Everything one launch needs.  x, w, y, res are device pointers; acc0 is the folded
+// start value of the accumulator, one int32 per output channel, padded with zeros to a
+// multiple of 256 channels.
+struct ConvParams {
+  const uint8_t *x;
+  const int8_t *w;
+  const int32_t *acc0;
+  void *y;
+  const void *res;
+  int B, H, W, C, N, R, S, sh, sw, ph, pw, P, Q;
+  int M, K;                 // M = B*P*Q output pixels, K = R*S*C
+  uint32_t xor_mask;        // 0x80808080 for unsigned activations, 0 for signed
+  int shift, lo, hi;        // requantisation
+  int y_type, res_type, res_d;
+  FastDiv fd_pq, fd_q, fd_cpt, fd_s;   // by P*Q, Q, units per tap (C / VEC), S
+};
+
+// Launches the implicit-GEMM kernel.  vec is the widest of 16, 4, 1 bytes that divides C
+// and the alignment of x and w.  Returns a hipError_t as int.
+int launch_conv_igemm(const ConvParams &p, int vec, hipStream_t stream);
+
+// Which tile shape launch_conv_igemm picks for N output channels, and its name.
+int conv_variant(int N);
+const char *conv_variant_name(int variant);
+
+// acc0[n] = bias[n] + rounding addend + (unsigned x ? 128 * sum_k w[n][k] : 0), zero for
+// N <= n < n_pad.
+int launch_fold_acc0(const int8_t *w, const int32_t *bias, int32_t *acc0, int N, int n_pad, int K,
+                     int x_unsigned, int rnd, hipStream_t stream);
+
+}  // namespace f8

@@ -1,0 +1,33 @@
+// Depthwise convolution, max pooling and global pooling launchers (gfx950).
+#pragma once
+
+#include "f8_device.h"
+
+namespace f8 {
+
+// Depthwise layer / global pool parameters.  rnd is the rounding addend 2^(shift-1)
+// (0 when shift <= 0 or the output is raw int32).
+struct DwParams {
+  const uint8_t *x;
+  const int8_t *w;          // [R][S][C]; unused by the global pool
+  const int32_t *bias;      // [C] or nullptr
+  void *y;
+  const void *res;
+  int B, H, W, C, R, S, sh, sw, ph, pw, P, Q;
+  int x_type, y_type, res_type, res_d;
+  int shift, rnd, lo, hi;
+};
+
+struct PoolParams {
+  const uint8_t *x;
+  uint8_t *y;
+  int B, H, W, C, R, S, sh, sw, ph, pw, P, Q;
+  int type;
+};
+
+// vec4: C % 4 == 0 and every pointer is 4-byte aligned.
+int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream);
+int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream);
+int launch_gpool(const DwParams &p, bool vec4, hipStream_t stream);
+
+}  // namespace f8

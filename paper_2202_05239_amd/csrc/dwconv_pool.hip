@@ -1,0 +1,177 @@
+// Depthwise fixed-point convolution and the two pooling layers for gfx950.
+// These are bandwidth-bound: no matrix cores, NHWC with consecutive lanes on consecutive
+// channels so that every wave access is a run of contiguous bytes.
+#include "dwconv_pool.h"
+
+namespace f8 {
+
+namespace {
+
+constexpr int NT = 256;
+
+// Generic depthwise layer (F8Net Eq. 6 with one input channel per output channel):
+// one thread = CV consecutive channels (CV = 4: one dword, or 1) of one output pixel.
+template <int CV>
+__global__ __launch_bounds__(NT) void dwconv_generic_kernel(const DwParams p, const long long total) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int cgroups = p.C / CV;
+  const int cg = (int)(gid % cgroups);
+  const long long pix = gid / cgroups;
+  const int q = (int)(pix % p.Q);
+  const long long t = pix / p.Q;
+  const int pp = (int)(t % p.P);
+  const int b = (int)(t / p.P);
+  const int c = cg * CV;
+  const bool xs = p.x_type == T_S8;
+
+  int acc[CV];
+#pragma unroll
+  for (int i = 0; i < CV; ++i) acc[i] = p.rnd + (p.bias ? p.bias[c + i] : 0);
+  for (int r = 0; r < p.R; ++r) {
+    const int ih = pp * p.sh - p.ph + r;
+    if ((unsigned)ih >= (unsigned)p.H) continue;
+    for (int s = 0; s < p.S; ++s) {
+      const int iw = q * p.sw - p.pw + s;
+      if ((unsigned)iw >= (unsigned)p.W) continue;
+      const size_t xi = (((size_t)b * p.H + ih) * p.W + iw) * p.C + c;
+      const size_t wi = ((size_t)r * p.S + s) * p.C + c;
+      if (CV == 4) {
+        const uint32_t xv = *reinterpret_cast<const uint32_t *>(p.x + xi);
+        const uint32_t wv = *reinterpret_cast<const uint32_t *>(p.w + wi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] += byte_of(xv, i, xs) * byte_of(wv, i, true);
+      } else {
+        acc[0] += (xs ? (int)(int8_t)p.x[xi] : (int)p.x[xi]) * (int)p.w[wi];
+      }
+    }
+  }
+  const size_t o = (size_t)pix * p.C + c;
+  if (p.res) {
+#pragma unroll
+    for (int i = 0; i < CV; ++i) {
+      int r;
+      if (p.res_type == T_S32) r = reinterpret_cast<const int32_t *>(p.res)[o + i];
+      else if (p.res_type == T_S8) r = reinterpret_cast<const int8_t *>(p.res)[o + i];
+      else r = reinterpret_cast<const uint8_t *>(p.res)[o + i];
+      acc[i] += align_res(r, p.res_d);
+    }
+  }
+  if (p.y_type == T_S32) {
+#pragma unroll
+    for (int i = 0; i < CV; ++i) reinterpret_cast<int32_t *>(p.y)[o + i] = acc[i];
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < CV; ++i)
+    acc[i] = p.shift >= 0 ? requant<false>(acc[i], p.shift, p.lo, p.hi) : requant<true>(acc[i], p.shift, p.lo, p.hi);
+  uint8_t *yp = reinterpret_cast<uint8_t *>(p.y) + o;
+  if (CV == 4) *reinterpret_cast<uint32_t *>(yp) = pack4(acc[0], acc[1], acc[2], acc[3]);
+  else yp[0] = (uint8_t)acc[0];
+}
+
+// Max pooling: one thread = CV consecutive channels of one output pixel; out-of-image
+// taps are skipped, so padding never wins.
+template <int CV>
+__global__ __launch_bounds__(NT) void maxpool_kernel(const PoolParams p, const long long total) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int cgroups = p.C / CV;
+  const int cg = (int)(gid % cgroups);
+  const long long pix = gid / cgroups;
+  const int q = (int)(pix % p.Q);
+  const long long t = pix / p.Q;
+  const int pp = (int)(t % p.P);
+  const int b = (int)(t / p.P);
+  const int c = cg * CV;
+  const bool sgn = p.type == T_S8;
+  int best[CV];
+#pragma unroll
+  for (int i = 0; i < CV; ++i) best[i] = -1024;
+  for (int r = 0; r < p.R; ++r) {
+    const int ih = pp * p.sh - p.ph + r;
+    if ((unsigned)ih >= (unsigned)p.H) continue;
+    for (int s = 0; s < p.S; ++s) {
+      const int iw = q * p.sw - p.pw + s;
+      if ((unsigned)iw >= (unsigned)p.W) continue;
+      const size_t xi = (((size_t)b * p.H + ih) * p.W + iw) * p.C + c;
+      if (CV == 4) {
+        const uint32_t xv = *reinterpret_cast<const uint32_t *>(p.x + xi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) best[i] = max(best[i], byte_of(xv, i, sgn));
+      } else {
+        best[0] = max(best[0], sgn ? (int)(int8_t)p.x[xi] : (int)p.x[xi]);
+      }
+    }
+  }
+  uint8_t *yp = p.y + (size_t)pix * p.C + c;
+  if (CV == 4) *reinterpret_cast<uint32_t *>(yp) = pack4(best[0], best[1], best[2], best[3]);
+  else yp[0] = (uint8_t)best[0];
+}
+
+// Global sum pool + requantisation: one thread = CV channels of one image.
+template <int CV>
+__global__ __launch_bounds__(NT) void gpool_kernel(const DwParams p, const long long total) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int cgroups = p.C / CV;
+  const int cg = (int)(gid % cgroups);
+  const int b = (int)(gid / cgroups);
+  const int c = cg * CV;
+  const bool xs = p.x_type == T_S8;
+  int acc[CV];
+#pragma unroll
+  for (int i = 0; i < CV; ++i) acc[i] = p.rnd;
+  const uint8_t *xp = p.x + (size_t)b * p.H * p.W * p.C + c;
+  for (int i = 0; i < p.H * p.W; ++i) {
+    if (CV == 4) {
+      const uint32_t xv = *reinterpret_cast<const uint32_t *>(xp + (size_t)i * p.C);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += byte_of(xv, j, xs);
+    } else {
+      acc[0] += xs ? (int)(int8_t)xp[(size_t)i * p.C] : (int)xp[(size_t)i * p.C];
+    }
+  }
+  const size_t o = (size_t)b * p.C + c;
+  if (p.y_type == T_S32) {
+#pragma unroll
+    for (int i = 0; i < CV; ++i) reinterpret_cast<int32_t *>(p.y)[o + i] = acc[i];
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < CV; ++i)
+    acc[i] = p.shift >= 0 ? requant<false>(acc[i], p.shift, p.lo, p.hi) : requant<true>(acc[i], p.shift, p.lo, p.hi);
+  uint8_t *yp = reinterpret_cast<uint8_t *>(p.y) + o;
+  if (CV == 4) *reinterpret_cast<uint32_t *>(yp) = pack4(acc[0], acc[1], acc[2], acc[3]);
+  else yp[0] = (uint8_t)acc[0];
+}
+
+inline unsigned blocks_for(long long total) { return (unsigned)((total + NT - 1) / NT); }
+
+}  // namespace
+
+int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
+  const long long total = (long long)p.B * p.P * p.Q * (p.C / (vec4 ? 4 : 1));
+  if (total <= 0) return 0;
+  if (vec4) hipLaunchKernelGGL(dwconv_generic_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  else hipLaunchKernelGGL(dwconv_generic_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  return (int)hipGetLastError();
+}
+
+int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream) {
+  const long long total = (long long)p.B * p.P * p.Q * (p.C / (vec4 ? 4 : 1));
+  if (total <= 0) return 0;
+  if (vec4) hipLaunchKernelGGL(maxpool_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  else hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  return (int)hipGetLastError();
+}
+
+int launch_gpool(const DwParams &p, bool vec4, hipStream_t stream) {
+  const long long total = (long long)p.B * (p.C / (vec4 ? 4 : 1));
+  if (total <= 0) return 0;
+  if (vec4) hipLaunchKernelGGL(gpool_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  else hipLaunchKernelGGL(gpool_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  return (int)hipGetLastError();
+}
+
+}  // namespace f8

@@ -1,0 +1,277 @@
+// C-ABI entry points of the single-layer calls: validation on the host, then launches.
+#include <mutex>
+#include <unordered_map>
+
+#include "f8_host.h"
+
+namespace f8 {
+
+f8_status check_quant(const f8_quant *q, bool allow_res) {
+  if (!q) return F8_ERR_NULL;
+  if (q->x_type != F8_U8 && q->x_type != F8_S8) return F8_ERR_DTYPE;
+  if (q->y_type != F8_U8 && q->y_type != F8_S8 && q->y_type != F8_S32) return F8_ERR_DTYPE;
+  if (q->res) {
+    if (!allow_res) return F8_ERR_UNSUPPORTED;
+    if (q->res_type != F8_U8 && q->res_type != F8_S8 && q->res_type != F8_S32) return F8_ERR_DTYPE;
+    const int d = q->fl_x + q->fl_w - q->fl_res;
+    if (d < -24 || d > 24) return F8_ERR_FL;
+  }
+  if (q->y_type != F8_S32) {
+    const int s = q->fl_x + q->fl_w - q->fl_y;
+    if (s < -8 || s > 24) return F8_ERR_FL;
+    if (q->clip_lo > q->clip_hi) return F8_ERR_CLIP;
+    if (q->y_type == F8_U8 && (q->clip_lo < 0 || q->clip_hi > 255)) return F8_ERR_CLIP;
+    if (q->y_type == F8_S8 && (q->clip_lo < -127 || q->clip_hi > 127)) return F8_ERR_CLIP;
+  }
+  return F8_OK;
+}
+
+f8_status check_geom(Geom &g, bool depthwise) {
+  if (g.B < 0 || g.H < 1 || g.W < 1 || g.Cin < 1 || g.Cout < 0 || g.R < 1 || g.S < 1 || g.sh < 1 ||
+      g.sw < 1 || g.ph < 0 || g.pw < 0)
+    return F8_ERR_SHAPE;
+  if (depthwise && g.Cout != g.Cin) return F8_ERR_SHAPE;
+  const long long K = (long long)g.R * g.S * (depthwise ? 1 : g.Cin);
+  if (K > 65536) return F8_ERR_SHAPE;
+  g.P = out_extent(g.H, g.ph, g.R, g.sh);
+  g.Q = out_extent(g.W, g.pw, g.S, g.sw);
+  const long long lim = 0x7fffffffLL;
+  const long long xb = (long long)g.B * g.H * g.W;
+  const long long yb = (long long)g.B * g.P * g.Q;
+  if (xb > lim || xb * g.Cin > lim || yb > lim || yb * g.Cout > lim) return F8_ERR_UNSUPPORTED;
+  return F8_OK;
+}
+
+f8_status check_align(const int32_t *bias, const void *y, const f8_quant &q, const void *res) {
+  if (reinterpret_cast<uintptr_t>(bias) & 3) return F8_ERR_ALIGN;
+  if (q.y_type == F8_S32 && (reinterpret_cast<uintptr_t>(y) & 3)) return F8_ERR_ALIGN;
+  if (res && q.res_type == F8_S32 && (reinterpret_cast<uintptr_t>(res) & 3)) return F8_ERR_ALIGN;
+  return F8_OK;
+}
+
+static int widest_vec(int C, const void *a, const void *b) {
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | (uintptr_t)C;
+  if ((bits & 15) == 0) return 16;
+  if ((bits & 3) == 0) return 4;
+  return 1;
+}
+
+f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void *y, const void *res,
+                       const Geom &g, const f8_quant &q, hipStream_t stream) {
+  ConvParams p;
+  p.x = static_cast<const uint8_t *>(x);
+  p.w = w;
+  p.acc0 = acc0;
+  p.y = y;
+  p.res = res;
+  p.B = g.B; p.H = g.H; p.W = g.W; p.C = g.Cin; p.N = g.Cout; p.R = g.R; p.S = g.S;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.P = g.P; p.Q = g.Q;
+  p.M = g.B * g.P * g.Q;
+  p.K = g.R * g.S * g.Cin;
+  p.xor_mask = q.x_type == F8_U8 ? 0x80808080u : 0u;
+  p.shift = q.y_type == F8_S32 ? 0 : q.fl_x + q.fl_w - q.fl_y;
+  p.lo = q.clip_lo; p.hi = q.clip_hi;
+  p.y_type = q.y_type;
+  p.res_type = q.res_type;
+  p.res_d = q.fl_x + q.fl_w - q.fl_res;
+  const int vec = widest_vec(g.Cin, x, w);
+  p.fd_pq = FastDiv((uint32_t)(g.P * g.Q));
+  p.fd_q = FastDiv((uint32_t)g.Q);
+  p.fd_cpt = FastDiv((uint32_t)(g.Cin / vec));
+  p.fd_s = FastDiv((uint32_t)g.S);
+  if (p.M == 0 || p.N == 0) return F8_OK;
+  return launch_conv_igemm(p, vec, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+f8_status enqueue_fold(const int8_t *w, const int32_t *bias, int32_t *acc0, const Geom &g,
+                       const f8_quant &q, hipStream_t stream) {
+  const int rc = launch_fold_acc0(w, bias, acc0, g.Cout, (int)acc0_padded(g.Cout), g.R * g.S * g.Cin,
+                                  q.x_type == F8_U8, rounding_addend(q), stream);
+  return rc == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+static DwParams dw_params(const void *x, const int8_t *w, const int32_t *bias, void *y, const void *res,
+                          const Geom &g, const f8_quant &q) {
+  DwParams p;
+  p.x = static_cast<const uint8_t *>(x);
+  p.w = w; p.bias = bias; p.y = y; p.res = res;
+  p.B = g.B; p.H = g.H; p.W = g.W; p.C = g.Cin; p.R = g.R; p.S = g.S;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.P = g.P; p.Q = g.Q;
+  p.x_type = q.x_type; p.y_type = q.y_type; p.res_type = q.res_type;
+  p.res_d = q.fl_x + q.fl_w - q.fl_res;
+  p.shift = q.y_type == F8_S32 ? 0 : q.fl_x + q.fl_w - q.fl_y;
+  p.rnd = rounding_addend(q);
+  p.lo = q.clip_lo; p.hi = q.clip_hi;
+  return p;
+}
+
+f8_status enqueue_dwconv(const void *x, const int8_t *w, const int32_t *bias, void *y, const void *res,
+                         const Geom &g, const f8_quant &q, hipStream_t stream) {
+  const DwParams p = dw_params(x, w, bias, y, res, g, q);
+  uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) |
+                   reinterpret_cast<uintptr_t>(y) | (uintptr_t)g.Cin;
+  if (res && q.res_type != F8_S32) bits |= reinterpret_cast<uintptr_t>(res);
+  return launch_dwconv(p, (bits & 3) == 0, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+f8_status enqueue_maxpool(const void *x, void *y, const Geom &g, int dtype, hipStream_t stream) {
+  PoolParams p;
+  p.x = static_cast<const uint8_t *>(x);
+  p.y = static_cast<uint8_t *>(y);
+  p.B = g.B; p.H = g.H; p.W = g.W; p.C = g.Cin; p.R = g.R; p.S = g.S;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.P = g.P; p.Q = g.Q;
+  p.type = dtype;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | (uintptr_t)g.Cin;
+  return launch_maxpool(p, (bits & 3) == 0, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+f8_status enqueue_gpool(const void *x, void *y, const Geom &g, const f8_quant &q, hipStream_t stream) {
+  const DwParams p = dw_params(x, nullptr, nullptr, y, nullptr, g, q);
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | (uintptr_t)g.Cin;
+  return launch_gpool(p, (bits & 3) == 0, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+// ---- per-stream scratch for the folded accumulator start values ------------------------
+namespace {
+struct Scratch { int32_t *ptr; size_t ints; };
+std::mutex g_mu;
+std::unordered_map<uint64_t, Scratch> g_scratch;   // key: device id, stream handle
+
+int32_t *scratch_for(hipStream_t stream, size_t ints) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  const uint64_t key = (reinterpret_cast<uint64_t>(stream) << 4) ^ (uint64_t)dev;
+  std::lock_guard<std::mutex> lock(g_mu);
+  Scratch &s = g_scratch[key];
+  if (s.ints < ints) {
+    // Growing: work already queued on this stream may still read the old buffer.
+    if (s.ptr) {
+      if (hipStreamSynchronize(stream) != hipSuccess) return nullptr;
+      (void)hipFree(s.ptr);
+      s.ptr = nullptr; s.ints = 0;
+    }
+    size_t want = ints < 16384 ? 16384 : ints;
+    if (hipMalloc(reinterpret_cast<void **>(&s.ptr), want * sizeof(int32_t)) != hipSuccess) {
+      s.ptr = nullptr;
+      return nullptr;
+    }
+    s.ints = want;
+  }
+  return s.ptr;
+}
+}  // namespace
+
+}  // namespace f8
+
+using namespace f8;
+
+extern "C" {
+
+f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int B, int H, int W,
+                          int Cin, int Cout, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                          const f8_quant *q, void *stream) {
+  if (!x || !w || !y) return F8_ERR_NULL;
+  f8_status st = check_quant(q, true);
+  if (st != F8_OK) return st;
+  Geom g{B, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  st = check_geom(g, false);
+  if (st != F8_OK) return st;
+  st = check_align(bias, y, *q, q->res);
+  if (st != F8_OK) return st;
+  if (q->res == y) return F8_ERR_UNSUPPORTED;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t *acc0 = scratch_for(s, acc0_padded(Cout));
+  if (!acc0) return F8_ERR_DEVICE;
+  st = enqueue_fold(w, bias, acc0, g, *q, s);
+  if (st != F8_OK) return st;
+  return enqueue_conv(x, w, acc0, y, q->res, g, *q, s);
+}
+
+f8_status f8_gemm_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int M, int K, int N,
+                        const f8_quant *q, void *stream) {
+  if (M < 0 || K < 1 || N < 0) return (x && w && y) ? F8_ERR_SHAPE : F8_ERR_NULL;
+  // A GEMM is the 1x1 convolution of a 1 x M image with K channels.
+  return f8_conv2d_fixed(x, w, bias, y, 1, 1, M > 0 ? M : 1, K, M > 0 ? N : 0, 1, 1, 1, 1, 0, 0, q, stream);
+}
+
+f8_status f8_dwconv_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int B, int H, int W,
+                          int C, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                          const f8_quant *q, void *stream) {
+  if (!x || !w || !y) return F8_ERR_NULL;
+  f8_status st = check_quant(q, true);
+  if (st != F8_OK) return st;
+  Geom g{B, H, W, C, C, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  st = check_geom(g, true);
+  if (st != F8_OK) return st;
+  st = check_align(bias, y, *q, q->res);
+  if (st != F8_OK) return st;
+  if (q->res == y) return F8_ERR_UNSUPPORTED;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  return enqueue_dwconv(x, w, bias, y, q->res, g, *q, static_cast<hipStream_t>(stream));
+}
+
+f8_status f8_maxpool(const void *x, void *y, int B, int H, int W, int C, int R, int S, int stride_h,
+                     int stride_w, int pad_h, int pad_w, int dtype, void *stream) {
+  if (!x || !y) return F8_ERR_NULL;
+  if (dtype != F8_U8 && dtype != F8_S8) return F8_ERR_DTYPE;
+  Geom g{B, H, W, C, C, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  f8_status st = check_geom(g, true);
+  if (st != F8_OK) return st;
+  if (pad_h >= R || pad_w >= S) return F8_ERR_SHAPE;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  return enqueue_maxpool(x, y, g, dtype, static_cast<hipStream_t>(stream));
+}
+
+f8_status f8_global_pool_fixed(const void *x, void *y, int B, int H, int W, int C, const f8_quant *q,
+                               void *stream) {
+  if (!x || !y) return F8_ERR_NULL;
+  f8_status st = check_quant(q, false);
+  if (st != F8_OK) return st;
+  if (B < 0 || H < 1 || W < 1 || C < 1 || (long long)H * W > 65536) return F8_ERR_SHAPE;
+  Geom g{B, H, W, C, C, H, W, 1, 1, 0, 0, 1, 1};
+  if ((long long)B * H * W * C > 0x7fffffffLL) return F8_ERR_UNSUPPORTED;
+  st = check_align(nullptr, y, *q, nullptr);
+  if (st != F8_OK) return st;
+  if (B == 0) return F8_OK;
+  return enqueue_gpool(x, y, g, *q, static_cast<hipStream_t>(stream));
+}
+
+int32_t f8_clip_from_alpha(double alpha, int fl_y, int is_signed) {
+  const int top = is_signed ? 127 : 255;
+  if (!(alpha > 0.0)) return 0;
+  double v = alpha;
+  for (int i = 0; i < fl_y; ++i) v *= 2.0;
+  for (int i = 0; i > fl_y; --i) v *= 0.5;
+  if (v >= (double)top) return top;
+  const int32_t r = (int32_t)(v + 0.5);    // v >= 0: truncation of v + 1/2 is round half up
+  return r > top ? top : r;
+}
+
+const char *f8_status_str(f8_status s) {
+  switch (s) {
+    case F8_OK: return "ok";
+    case F8_ERR_NULL: return "null pointer";
+    case F8_ERR_SHAPE: return "bad shape";
+    case F8_ERR_FL: return "fractional lengths give a shift outside the supported range";
+    case F8_ERR_CLIP: return "clip bounds outside the output type's range";
+    case F8_ERR_DTYPE: return "type code not allowed for this operand";
+    case F8_ERR_ACC_OVERFLOW: return "accumulator overflow";
+    case F8_ERR_ALIGN: return "int32 operand is not 4-byte aligned";
+    case F8_ERR_UNSUPPORTED: return "unsupported configuration";
+    case F8_ERR_DEVICE: return "HIP runtime error";
+    case F8_ERR_STATE: return "chain not prepared for this workspace";
+  }
+  return "unknown status";
+}
+
+void f8_release_scratch(void) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  for (auto &kv : g_scratch)
+    if (kv.second.ptr) (void)hipFree(kv.second.ptr);
+  g_scratch.clear();
+}
+
+int f8_abi_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,396 @@
+// Layer-chain runner: a whole fixed-point network forward as a fixed sequence of launches.
+//
+// The chain owns only host-side book-keeping.  Activations and the folded per-channel
+// constants live in a caller-provided device workspace whose layout is
+//   [ constants: acc0 vector of every dense layer ][ activation arena ]
+// Every tensor's size is linear in the batch, so the arena is planned once per image
+// (first-fit over tensor lifetimes, offsets in multiples of 256 bytes) and scaled by the
+// batch at run time.
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "f8_host.h"
+
+using namespace f8;
+
+namespace {
+
+struct Tensor {
+  int h = 0, w = 0, c = 0;
+  int type = -1;
+  int fl = 0;
+  bool fl_known = false;
+  int producer = -2;        // -2: not defined, -1: network input, else layer index
+  int last_use = -1;        // last layer index that reads it
+  size_t bytes_per_image = 0;
+  size_t offset_per_image = 0;
+  bool external = false;    // input x or final output
+};
+
+size_t elem_size(int type) { return type == F8_S32 ? 4 : 1; }
+size_t round256(size_t v) { return (v + 255) / 256 * 256; }
+
+}  // namespace
+
+struct f8_chain {
+  std::vector<f8_layer_desc> layers;
+  std::vector<Geom> geom;              // per layer, B filled at run time
+  std::vector<Tensor> tensors;
+  std::vector<size_t> acc0_off;        // per layer: byte offset in the constants region
+  size_t const_bytes = 0;
+  size_t arena_per_image = 0;
+  bool keep_all = false;
+  bool planned = false;
+  int last_tensor = 0;
+  void *prepared_ws = nullptr;
+  int prepared_batch = -1;
+
+  void plan() {
+    struct Block { size_t off, size; };
+    std::vector<Block> free_list;      // sorted by offset
+    size_t top = 0;
+    auto alloc = [&](size_t size) -> size_t {
+      for (size_t i = 0; i < free_list.size(); ++i) {
+        if (free_list[i].size >= size) {
+          const size_t off = free_list[i].off;
+          free_list[i].off += size;
+          free_list[i].size -= size;
+          if (free_list[i].size == 0) free_list.erase(free_list.begin() + i);
+          return off;
+        }
+      }
+      // extend the arena, reusing a free tail if there is one
+      if (!free_list.empty() && free_list.back().off + free_list.back().size == top) {
+        const size_t off = free_list.back().off;
+        free_list.pop_back();
+        top = off + size;
+        return off;
+      }
+      const size_t off = top;
+      top += size;
+      return off;
+    };
+    auto release = [&](size_t off, size_t size) {
+      Block b{off, size};
+      auto it = std::lower_bound(free_list.begin(), free_list.end(), b,
+                                 [](const Block &a, const Block &c) { return a.off < c.off; });
+      it = free_list.insert(it, b);
+      const size_t i = it - free_list.begin();
+      if (i + 1 < free_list.size() && free_list[i].off + free_list[i].size == free_list[i + 1].off) {
+        free_list[i].size += free_list[i + 1].size;
+        free_list.erase(free_list.begin() + i + 1);
+      }
+      if (i > 0 && free_list[i - 1].off + free_list[i - 1].size == free_list[i].off) {
+        free_list[i - 1].size += free_list[i].size;
+        free_list.erase(free_list.begin() + i);
+      }
+    };
+    for (size_t li = 0; li < layers.size(); ++li) {
+      Tensor &d = tensors[layers[li].dst];
+      if (!d.external) d.offset_per_image = alloc(round256(d.bytes_per_image));
+      if (keep_all) continue;
+      const int ids[2] = {layers[li].src, layers[li].res};
+      for (int k = 0; k < 2; ++k) {
+        if (ids[k] < 0) continue;
+        if (k == 1 && ids[1] == ids[0]) continue;
+        Tensor &t = tensors[ids[k]];
+        if (!t.external && t.last_use == (int)li) release(t.offset_per_image, round256(t.bytes_per_image));
+      }
+    }
+    arena_per_image = top;
+    planned = true;
+  }
+};
+
+extern "C" {
+
+f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, int in_w, int in_c,
+                          int in_type, f8_chain **out) {
+  if (!layers || !out) return F8_ERR_NULL;
+  *out = nullptr;
+  if (n_layers < 1 || in_h < 1 || in_w < 1 || in_c < 1) return F8_ERR_SHAPE;
+  if (in_type != F8_U8 && in_type != F8_S8) return F8_ERR_DTYPE;
+  f8_chain *c = new (std::nothrow) f8_chain();
+  if (!c) return F8_ERR_DEVICE;
+  f8_status st = F8_OK;
+  int max_id = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    if (layers[i].dst < 1 || layers[i].src < 0 || layers[i].res < -1) { st = F8_ERR_SHAPE; break; }
+    max_id = std::max(max_id, std::max(layers[i].dst, std::max(layers[i].src, layers[i].res)));
+  }
+  if (st == F8_OK && max_id > 16 * n_layers + 16) st = F8_ERR_SHAPE;
+  if (st != F8_OK) { delete c; return st; }
+  c->tensors.resize(max_id + 1);
+  Tensor &t0 = c->tensors[0];
+  t0.h = in_h; t0.w = in_w; t0.c = in_c; t0.type = in_type; t0.producer = -1; t0.external = true;
+  t0.bytes_per_image = (size_t)in_h * in_w * in_c;
+
+  for (int i = 0; i < n_layers && st == F8_OK; ++i) {
+    f8_layer_desc L = layers[i];
+    L.q.res = nullptr;
+    Tensor &s = c->tensors[L.src];
+    if (s.producer == -2) { st = F8_ERR_SHAPE; break; }           // read before written
+    if (c->tensors[L.dst].producer != -2) { st = F8_ERR_SHAPE; break; }   // written twice
+    if (L.op < F8_OP_CONV || L.op > F8_OP_GPOOL) { st = F8_ERR_UNSUPPORTED; break; }
+    if (L.Cin != s.c || L.q.x_type != s.type) { st = F8_ERR_SHAPE; break; }
+    if (s.fl_known && s.fl != L.q.fl_x) { st = F8_ERR_FL; break; }
+    s.fl = L.q.fl_x; s.fl_known = true;
+    Geom g{1, s.h, s.w, L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, 0, 0};
+    Tensor d;
+    d.producer = i;
+    if (L.op == F8_OP_MAXPOOL) {
+      if (L.Cout != L.Cin || L.res >= 0) { st = F8_ERR_SHAPE; break; }
+      st = check_geom(g, true);
+      if (st != F8_OK) break;
+      if (L.pad_h >= L.R || L.pad_w >= L.S) { st = F8_ERR_SHAPE; break; }
+      d.type = s.type; d.fl = s.fl; d.fl_known = true;
+    } else {
+      if (L.op == F8_OP_GPOOL) {
+        if (L.Cout != L.Cin || L.res >= 0 || (long long)s.h * s.w > 65536) { st = F8_ERR_SHAPE; break; }
+        g.R = s.h; g.S = s.w; g.sh = g.sw = 1; g.ph = g.pw = 0; g.P = g.Q = 1;
+        L.R = s.h; L.S = s.w;
+      } else {
+        if (!L.w) { st = F8_ERR_NULL; break; }
+        st = check_geom(g, L.op == F8_OP_DWCONV);
+        if (st != F8_OK) break;
+      }
+      // a dummy non-null residual pointer lets check_quant vet the residual fields
+      f8_quant qq = L.q;
+      if (L.res >= 0) qq.res = &qq;
+      st = check_quant(&qq, L.op != F8_OP_GPOOL);
+      if (st != F8_OK) break;
+      if (reinterpret_cast<uintptr_t>(L.bias) & 3) { st = F8_ERR_ALIGN; break; }
+      d.type = L.q.y_type;
+      d.fl = L.q.y_type == F8_S32 ? L.q.fl_x + L.q.fl_w : L.q.fl_y;
+      d.fl_known = true;
+    }
+    if (g.P < 1 || g.Q < 1) { st = F8_ERR_SHAPE; break; }
+    d.h = g.P; d.w = g.Q; d.c = L.Cout;
+    d.bytes_per_image = (size_t)d.h * d.w * d.c * elem_size(d.type);
+    if (L.res >= 0) {
+      const Tensor &r = c->tensors[L.res];
+      if (r.producer == -2 || L.res == L.dst) { st = F8_ERR_SHAPE; break; }
+      if (r.h != d.h || r.w != d.w || r.c != d.c || r.type != L.q.res_type) { st = F8_ERR_SHAPE; break; }
+      if (r.fl_known && r.fl != L.q.fl_res) { st = F8_ERR_FL; break; }
+      c->tensors[L.res].fl = L.q.fl_res; c->tensors[L.res].fl_known = true;
+      c->tensors[L.res].last_use = i;
+    }
+    s.last_use = i;
+    c->tensors[L.dst] = d;
+    c->layers.push_back(L);
+    c->geom.push_back(g);
+    c->acc0_off.push_back(c->const_bytes);
+    if (L.op == F8_OP_CONV) c->const_bytes += acc0_padded(L.Cout) * sizeof(int32_t);
+  }
+  if (st != F8_OK) { delete c; return st; }
+  c->last_tensor = c->layers.back().dst;
+  c->tensors[c->last_tensor].external = true;
+  c->const_bytes = round256(c->const_bytes);
+  *out = c;
+  return F8_OK;
+}
+
+f8_status f8_chain_set_keep_all(f8_chain *c, int keep_all) {
+  if (!c) return F8_ERR_NULL;
+  c->keep_all = keep_all != 0;
+  c->planned = false;
+  c->prepared_ws = nullptr;
+  return F8_OK;
+}
+
+f8_status f8_chain_workspace_bytes(const f8_chain *cc, int batch, size_t *bytes) {
+  if (!cc || !bytes) return F8_ERR_NULL;
+  if (batch < 0) return F8_ERR_SHAPE;
+  f8_chain *c = const_cast<f8_chain *>(cc);
+  if (!c->planned) c->plan();
+  // every tensor must stay addressable with 32-bit element counts
+  for (const Tensor &t : c->tensors)
+    if (t.producer != -2 && (long long)t.bytes_per_image / (long long)elem_size(t.type) * batch > 0x7fffffffLL)
+      return F8_ERR_UNSUPPORTED;
+  *bytes = c->const_bytes + c->arena_per_image * (size_t)batch + 256;
+  return F8_OK;
+}
+
+f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream) {
+  if (!c || !workspace) return F8_ERR_NULL;
+  if (batch < 0) return F8_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return F8_ERR_ALIGN;
+  if (!c->planned) c->plan();
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  for (size_t i = 0; i < c->layers.size(); ++i) {
+    const f8_layer_desc &L = c->layers[i];
+    if (L.op != F8_OP_CONV) continue;
+    int32_t *acc0 = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
+    const f8_status st = enqueue_fold(L.w, L.bias, acc0, c->geom[i], L.q, s);
+    if (st != F8_OK) return st;
+  }
+  c->prepared_ws = workspace;
+  c->prepared_batch = batch;
+  return F8_OK;
+}
+
+static void *tensor_ptr(const f8_chain *c, int id, const void *x, void *out, void *workspace, int batch) {
+  if (id == 0) return const_cast<void *>(x);
+  if (id == c->last_tensor) return out;
+  return static_cast<uint8_t *>(workspace) + c->const_bytes + c->tensors[id].offset_per_image * (size_t)batch;
+}
+
+f8_status f8_chain_run(f8_chain *c, const void *x, void *out, void *workspace, int batch, void *stream) {
+  if (!c || !x || !out || !workspace) return F8_ERR_NULL;
+  if (batch < 0) return F8_ERR_SHAPE;
+  if (c->prepared_ws != workspace || c->prepared_batch != batch) return F8_ERR_STATE;
+  if (c->tensors[c->last_tensor].type == F8_S32 && (reinterpret_cast<uintptr_t>(out) & 3)) return F8_ERR_ALIGN;
+  if (batch == 0) return F8_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  for (size_t i = 0; i < c->layers.size(); ++i) {
+    const f8_layer_desc &L = c->layers[i];
+    Geom g = c->geom[i];
+    g.B = batch;
+    const void *src = tensor_ptr(c, L.src, x, out, workspace, batch);
+    void *dst = tensor_ptr(c, L.dst, x, out, workspace, batch);
+    const void *res = L.res >= 0 ? tensor_ptr(c, L.res, x, out, workspace, batch) : nullptr;
+    f8_status st;
+    switch (L.op) {
+      case F8_OP_CONV: {
+        const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
+        st = enqueue_conv(src, L.w, acc0, dst, res, g, L.q, s);
+        break;
+      }
+      case F8_OP_DWCONV: st = enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s); break;
+      case F8_OP_MAXPOOL: st = enqueue_maxpool(src, dst, g, L.q.x_type, s); break;
+      default: st = enqueue_gpool(src, dst, g, L.q, s); break;
+    }
+    if (st != F8_OK) return st;
+  }
+  return F8_OK;
+}
+
+f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch, void **ptr, int *h, int *w,
+                          int *ch, int *dtype, int *live_at_end) {
+  if (!c) return F8_ERR_NULL;
+  if (id < 0 || id >= (int)c->tensors.size() || c->tensors[id].producer == -2) return F8_ERR_SHAPE;
+  if (!c->planned) const_cast<f8_chain *>(c)->plan();
+  const Tensor &t = c->tensors[id];
+  if (ptr) *ptr = (t.external || !workspace) ? nullptr : tensor_ptr(c, id, nullptr, nullptr, workspace, batch);
+  if (h) *h = t.h;
+  if (w) *w = t.w;
+  if (ch) *ch = t.c;
+  if (dtype) *dtype = t.type;
+  if (live_at_end) {
+    int live = 1;
+    if (!c->keep_all && !t.external) {
+      // overwritten if a tensor produced after this one's last use overlaps it
+      for (size_t j = 0; j < c->tensors.size() && live; ++j) {
+        const Tensor &o = c->tensors[j];
+        if ((int)j == id || o.external || o.producer == -2 || o.producer <= t.last_use ||
+            o.producer <= t.producer)
+          continue;
+        const size_t a0 = t.offset_per_image, a1 = a0 + round256(t.bytes_per_image);
+        const size_t b0 = o.offset_per_image, b1 = b0 + round256(o.bytes_per_image);
+        if (a0 < b1 && b0 < a1) live = 0;
+      }
+    }
+    *live_at_end = live;
+  }
+  return F8_OK;
+}
+
+void f8_chain_destroy(f8_chain *c) { delete c; }
+
+}  // extern "C"
+
+// ---- measurement aids ---------------------------------------------------------------------
+
+extern "C" {
+
+int f8_chain_num_layers(const f8_chain *c) { return c ? (int)c->layers.size() : 0; }
+
+f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *kernel_name, int name_len,
+                              double *alg_ops, double *alg_bytes) {
+  if (!c) return F8_ERR_NULL;
+  if (layer < 0 || layer >= (int)c->layers.size() || batch < 0) return F8_ERR_SHAPE;
+  const f8_layer_desc &L = c->layers[layer];
+  const Geom &g = c->geom[layer];
+  const char *name = "?";
+  double ops = 0.0;
+  const double M = (double)batch * g.P * g.Q;
+  // input pixels a strided window actually touches
+  const double rows = g.sh >= g.R ? (double)g.P * g.R : (double)std::min(g.H, (g.P - 1) * g.sh + g.R);
+  const double cols = g.sw >= g.S ? (double)g.Q * g.S : (double)std::min(g.W, (g.Q - 1) * g.sw + g.S);
+  double bytes = (double)batch * rows * cols * g.Cin + M * g.Cout * (double)elem_size(c->tensors[L.dst].type);
+  if (L.res >= 0) bytes += M * g.Cout * (double)elem_size(c->tensors[L.res].type);
+  switch (L.op) {
+    case F8_OP_CONV:
+      name = conv_variant_name(conv_variant(g.Cout));
+      ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
+      bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
+      break;
+    case F8_OP_DWCONV:
+      name = "dwconv";
+      ops = 2.0 * M * g.R * g.S * g.Cout;
+      bytes += (double)g.R * g.S * g.Cout + 4.0 * g.Cout;
+      break;
+    case F8_OP_MAXPOOL: name = "maxpool"; break;
+    default: name = "gpool"; break;
+  }
+  if (kernel_name && name_len > 0) {
+    int i = 0;
+    for (; name[i] && i < name_len - 1; ++i) kernel_name[i] = name[i];
+    kernel_name[i] = 0;
+  }
+  if (alg_ops) *alg_ops = ops;
+  if (alg_bytes) *alg_bytes = bytes;
+  return F8_OK;
+}
+
+f8_status f8_chain_profile(f8_chain *c, const void *x, void *out, void *workspace, int batch, void *stream,
+                           int repeats, float *layer_ms) {
+  if (!c || !x || !out || !workspace || !layer_ms) return F8_ERR_NULL;
+  if (batch < 1 || repeats < 1) return F8_ERR_SHAPE;
+  if (c->prepared_ws != workspace || c->prepared_batch != batch) return F8_ERR_STATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = c->layers.size();
+  std::vector<hipEvent_t> ev(repeats * (n + 1));
+  for (auto &e : ev)
+    if (hipEventCreate(&e) != hipSuccess) return F8_ERR_DEVICE;
+  f8_status st = F8_OK;
+  for (int r = 0; r < repeats && st == F8_OK; ++r) {
+    hipEvent_t *e = &ev[r * (n + 1)];
+    (void)hipEventRecord(e[0], s);
+    for (size_t i = 0; i < n && st == F8_OK; ++i) {
+      const f8_layer_desc &L = c->layers[i];
+      Geom g = c->geom[i];
+      g.B = batch;
+      const void *src = tensor_ptr(c, L.src, x, out, workspace, batch);
+      void *dst = tensor_ptr(c, L.dst, x, out, workspace, batch);
+      const void *res = L.res >= 0 ? tensor_ptr(c, L.res, x, out, workspace, batch) : nullptr;
+      switch (L.op) {
+        case F8_OP_CONV:
+          st = enqueue_conv(src, L.w, reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]),
+                            dst, res, g, L.q, s);
+          break;
+        case F8_OP_DWCONV: st = enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s); break;
+        case F8_OP_MAXPOOL: st = enqueue_maxpool(src, dst, g, L.q.x_type, s); break;
+        default: st = enqueue_gpool(src, dst, g, L.q, s); break;
+      }
+      (void)hipEventRecord(e[i + 1], s);
+    }
+  }
+  if (hipStreamSynchronize(s) != hipSuccess) st = F8_ERR_DEVICE;
+  if (st == F8_OK) {
+    for (size_t i = 0; i < n; ++i) {
+      double sum = 0.0;
+      for (int r = 0; r < repeats; ++r) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, ev[r * (n + 1) + i], ev[r * (n + 1) + i + 1]);
+        sum += ms;
+      }
+      layer_ms[i] = (float)(sum / repeats);
+    }
+  }
+  for (auto &e : ev) (void)hipEventDestroy(e);
+  return st;
+}
+
+}  // extern "C"

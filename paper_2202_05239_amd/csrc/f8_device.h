@@ -1,0 +1,80 @@
+// Device-side helpers shared by the gfx950 kernels: requantisation epilogue pieces
+// (rounding shift, clip, pack; F8Net Eq. 2 / Eq. 9 in integer form), division by
+// run-time constants, and the XCD-aware block-index permutation.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace f8 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+enum { T_U8 = 0, T_S8 = 1, T_S32 = 2 };
+
+// Division of a non-negative 32-bit integer by a fixed divisor d >= 1, as a multiply-high
+// and a shift.  (Address arithmetic only: the layer arithmetic itself has no multiply
+// besides the 8-bit products.)
+struct FastDiv {
+  uint32_t mul;
+  uint32_t shr;
+  uint32_t d;
+  __host__ FastDiv() : mul(0), shr(0), d(1) {}
+  __host__ explicit FastDiv(uint32_t div) : d(div) {
+    if (div <= 1) { mul = 0; shr = 0; d = 1; return; }
+    uint32_t l = 0;
+    while ((1ull << l) < div) ++l;                        // l = ceil(log2(div))
+    uint64_t m = ((1ull << 32) * ((1ull << l) - div)) / div + 1;
+    mul = (uint32_t)m;
+    shr = l;
+  }
+  __device__ __forceinline__ uint32_t div(uint32_t n) const {
+    if (d == 1) return n;
+    uint32_t t = __umulhi(n, mul);
+    return (t + ((n - t) >> 1)) >> (shr - 1);
+  }
+};
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id.  Give every XCD a
+// contiguous range of logical tiles so that neighbouring tiles share one L2.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks) {
+  const uint32_t per = nblocks >> 3, rem = nblocks & 7;
+  const uint32_t xcd = bid & 7, idx = bid >> 3;
+  return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+// Rounding shift + clip.  `a` already contains the rounding addend 2^(s-1) (it is folded
+// into the accumulator's start value), so s >= 0 is one arithmetic shift.  For s < 0 the
+// value is scaled up; clamping first keeps the product inside 32 bits and cannot change
+// the clipped result because |clip bounds| <= 255.
+template <bool NEG>
+__device__ __forceinline__ int requant(int a, int s, int lo, int hi) {
+  int v;
+  if (NEG) {
+    a = min(max(a, -65536), 65536);
+    v = a << (-s);
+  } else {
+    v = a >> s;
+  }
+  return min(max(v, lo), hi);
+}
+
+// Four 8-bit results (already clipped into their type's range) into one dword.
+__device__ __forceinline__ uint32_t pack4(int v0, int v1, int v2, int v3) {
+  const uint32_t lo = __builtin_amdgcn_perm((uint32_t)v1, (uint32_t)v0, 0x0c0c0400u);  // bytes: v0.b0, v1.b0
+  const uint32_t hi = __builtin_amdgcn_perm((uint32_t)v3, (uint32_t)v2, 0x04000c0cu);  // bytes 2,3: v2.b0, v3.b0
+  return lo | hi;
+}
+
+// Residual operand brought to the accumulator scale (F8Net Sec. 4.3: sibling tensors
+// differ only by a power of two).  d >= 0: exact left shift; d < 0: rounding shift.
+__device__ __forceinline__ int align_res(int r, int d) {
+  return d >= 0 ? (r << d) : ((r + (1 << (-d - 1))) >> (-d));
+}
+
+__device__ __forceinline__ int byte_of(uint32_t v, int i, bool is_signed) {
+  return is_signed ? (int)(int8_t)(v >> (8 * i)) : (int)((v >> (8 * i)) & 0xffu);
+}
+
+}  // namespace f8

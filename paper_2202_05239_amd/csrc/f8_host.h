@@ -1,0 +1,51 @@
+// Host-side pieces shared by the single-layer entry points and the chain runner:
+// argument validation and the translation of a validated call into launch parameters.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/f8.h"
+#include "conv_igemm.h"
+#include "dwconv_pool.h"
+
+namespace f8 {
+
+// Geometry of a convolution-like layer.
+struct Geom {
+  int B, H, W, Cin, Cout, R, S, sh, sw, ph, pw;
+  int P, Q;
+};
+
+inline int out_extent(int in, int pad, int k, int stride) {
+  const long long span = (long long)in + 2LL * pad - k;
+  return span < 0 ? 0 : (int)(span / stride + 1);
+}
+
+inline int rounding_addend(const f8_quant &q) {
+  if (q.y_type == F8_S32) return 0;
+  const int s = q.fl_x + q.fl_w - q.fl_y;
+  return s > 0 ? (1 << (s - 1)) : 0;
+}
+
+inline size_t acc0_padded(int N) { return ((size_t)N + 255) / 256 * 256; }
+
+// Checks of the quantisation record that need no device data.
+f8_status check_quant(const f8_quant *q, bool allow_res);
+// Shape / size checks; fills P and Q.  depthwise: Cout must equal Cin.
+f8_status check_geom(Geom &g, bool depthwise);
+// Pointer alignment the int32 operands need.
+f8_status check_align(const int32_t *bias, const void *y, const f8_quant &q, const void *res);
+
+// Enqueue the dense layer with a ready acc0 vector (device, acc0_padded(Cout) ints).
+f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void *y, const void *res,
+                       const Geom &g, const f8_quant &q, hipStream_t stream);
+// Enqueue the fold of (w, bias, rounding addend, sign correction) into acc0.
+f8_status enqueue_fold(const int8_t *w, const int32_t *bias, int32_t *acc0, const Geom &g,
+                       const f8_quant &q, hipStream_t stream);
+f8_status enqueue_dwconv(const void *x, const int8_t *w, const int32_t *bias, void *y, const void *res,
+                         const Geom &g, const f8_quant &q, hipStream_t stream);
+f8_status enqueue_maxpool(const void *x, void *y, const Geom &g, int dtype, hipStream_t stream);
+f8_status enqueue_gpool(const void *x, void *y, const Geom &g, const f8_quant &q, hipStream_t stream);
+
+}  // namespace f8

@@ -334,8 +334,13 @@ def random_conv_case(rng, B, H, W, Cin, Cout, R, S, stride, pad, x_type="u8", y_
     fl_w = int(rng.integers(0, 9))
     s = int(rng.integers(0, 13)) if shift is None else shift
     fl_y = fl_x + fl_w - s
-    x = draw_u8(rng, (B, H, W, Cin)) if x_type == "u8" else \
-        rng.integers(-128, 128, size=(B, H, W, Cin), dtype=np.int8)
+    if s <= 0:
+        # no down-shift: keep operands tiny so that results do not all saturate
+        x = rng.integers(0, 4, size=(B, H, W, Cin), dtype=np.uint8) if x_type == "u8" else \
+            rng.integers(-3, 4, size=(B, H, W, Cin), dtype=np.int8)
+    else:
+        x = draw_u8(rng, (B, H, W, Cin)) if x_type == "u8" else \
+            rng.integers(-128, 128, size=(B, H, W, Cin), dtype=np.int8)
     if w_std is None:
         # accumulator spread of a few hundred output LSBs
         w_std = min(40.0, max(0.6, 2.0 ** s * 60.0 / (74.0 * np.sqrt(K))))

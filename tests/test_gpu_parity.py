@@ -1,0 +1,293 @@
+"""Bit-exact parity of the gfx950 library (through its C ABI) with the CPU oracle.
+
+Every case draws seeded operands, runs the oracle on the host and the library on the
+GPU, and compares element by element: integer work, so the bar is equality.
+"""
+import os
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2202_05239_amd import binding as f8
+from paper_2202_05239_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+NP_DTYPE = {"u8": np.uint8, "s8": np.int8, "s32": np.int32}
+
+
+def host_threads():
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def gpu_layer(L, x, res=None, offset=0):
+    """Run one layer description through the C ABI.  offset > 0 places x at an address
+    that is only 1- or 4-byte aligned, to reach the narrow gather paths."""
+    if offset:
+        buf = torch.empty(x.size + 64, dtype=torch.uint8, device=DEV)
+        xt = buf[offset:offset + x.size].view(f8.TORCH_DTYPE[L.x_type]).view(*x.shape)
+        xt.copy_(torch.from_numpy(x))
+    else:
+        xt = torch.from_numpy(x).to(DEV)
+    wt = torch.from_numpy(L.w).to(DEV) if L.w is not None else None
+    bt = torch.from_numpy(L.bias).to(DEV) if L.bias is not None else None
+    rt = torch.from_numpy(res).to(DEV) if res is not None else None
+    B = x.shape[0]
+    P, Q = L.out_hw
+    if L.op == "gpool":
+        y = torch.empty((B, L.Cout), dtype=f8.TORCH_DTYPE[L.y_type], device=DEV)
+        f8.f8_global_pool_fixed(xt, y, L)
+    elif L.op == "maxpool":
+        y = torch.empty((B, P, Q, L.Cout), dtype=f8.TORCH_DTYPE[L.x_type], device=DEV)
+        f8.f8_maxpool(xt, y, L.x_type, (L.R, L.S), (L.stride, L.stride), (L.pad, L.pad))
+    else:
+        y = torch.full((B, P, Q, L.Cout), 77, dtype=f8.TORCH_DTYPE[L.y_type], device=DEV)
+        fn = f8.f8_conv2d_fixed if L.op == "conv" else f8.f8_dwconv_fixed
+        fn(xt, wt, bt, y, L, (L.stride, L.stride), (L.pad, L.pad), rt)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def assert_same(got, want, what=""):
+    assert got.shape == want.shape and got.dtype == want.dtype, (what, got.shape, want.shape, got.dtype, want.dtype)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        i = tuple(bad[0])
+        raise AssertionError("%s: %d of %d differ; first at %s: gpu %d oracle %d" %
+                             (what, len(bad), got.size, i, int(got[i]), int(want[i])))
+
+
+# ------------------------------------------------------------------------- configs 0, 1, 2
+
+def test_config0_gemm(oracle):
+    x, L = wl.config0()
+    want = oracle.gemm_fixed(x, L.w.reshape(64, 64), L.bias, L)
+    xt, wt, bt = (torch.from_numpy(a).to(DEV) for a in (x, L.w.reshape(64, 64), L.bias))
+    y = torch.empty((256, 64), dtype=torch.uint8, device=DEV)
+    f8.f8_gemm_fixed(xt, wt, bt, y, L)
+    torch.cuda.synchronize()
+    assert_same(y.cpu().numpy(), want, "config0")
+    assert 0.3 < (want == 0).mean() < 0.7 and want.max() > 100     # not a degenerate draw
+
+
+def test_config1_conv3x3(oracle):
+    x, L = wl.config1()                                             # full batch 32
+    got = gpu_layer(L, x)
+    parts = np.array_split(np.arange(x.shape[0]), host_threads())
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(host_threads()) as ex:
+        outs = list(ex.map(lambda idx: oracle.conv2d_fixed(x[idx], L.w, L.bias, L, (1, 1), (1, 1)),
+                           [p for p in parts if len(p)]))
+    want = np.concatenate(outs)
+    assert_same(got, want, "config1")
+    assert (want == 192).mean() > 0.01 and want.max() == 192        # the clip level is exercised
+
+
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_config2_mbv2_block(oracle, with_residual):
+    x, net = wl.config2(with_residual=with_residual)                # batch 64
+    want = oracle.run_network_parallel(net, x, host_threads(), keep_all=True)
+    t = {0: x}
+    for L in net.layers:                                            # single-layer entry points
+        t[L.dst] = gpu_layer(L, t[L.src], t[L.res] if L.res >= 0 else None)
+        assert_same(t[L.dst], want[L.dst], "config2 " + L.name)
+    chain = f8.Chain(net, keep_all=True).prepare(x.shape[0])        # and the chain runner
+    out = chain.run(torch.from_numpy(x).to(DEV))
+    torch.cuda.synchronize()
+    assert_same(out.cpu().numpy(), want[net.layers[-1].dst], "config2 chain")
+    for L in net.layers[:-1]:
+        assert_same(chain.tensor(L.dst).cpu().numpy(), want[L.dst], "config2 chain " + L.name)
+
+
+# ------------------------------------------------------------------------- whole networks
+
+def check_network(oracle, x, net, oracle_images, what):
+    """GPU runs the full batch; the oracle runs the listed images (images are independent)."""
+    xt = torch.from_numpy(x).to(DEV)
+    chain = f8.Chain(net, keep_all=True).prepare(x.shape[0])
+    out = chain.run(xt)
+    torch.cuda.synchronize()
+    idx = np.asarray(oracle_images)
+    want = oracle.run_network_parallel(net, np.ascontiguousarray(x[idx]), host_threads(), keep_all=True)
+    for L in net.layers[:-1]:
+        got = chain.tensor(L.dst).cpu().numpy()[idx]
+        assert_same(got, want[L.dst], "%s layer %s" % (what, L.name))
+    assert_same(out.cpu().numpy()[idx], want[net.layers[-1].dst], what + " logits")
+    # the memory-reusing plan gives the same logits, and repeated runs are identical
+    lean = f8.Chain(net).prepare(x.shape[0])
+    a = lean.run(xt).clone()
+    b = lean.run(xt)
+    torch.cuda.synchronize()
+    assert torch.equal(a, out) and torch.equal(b, out), what + " lean plan / rerun"
+    assert lean.workspace_bytes(x.shape[0]) < chain.workspace_bytes(x.shape[0])
+    return out
+
+
+def test_config3_resnet18(oracle):
+    x, net = wl.config3()                                           # batch 64, 224x224x3
+    out = check_network(oracle, x, net, list(range(0, 64, 4)), "config3")
+    assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
+
+
+def test_config4_resnet50(oracle):
+    x, net = wl.config4()                                           # batch 256, 224x224x3
+    imgs = [0, 1, 2, 3, 100, 101, 254, 255]
+    out = check_network(oracle, x, net, imgs, "config4")
+    assert out.shape == (256, 1, 1, 1000)
+
+
+def test_small_networks_full_compare(oracle):
+    for cfg, batch in ((wl.config3, 5), (wl.config4, 3)):
+        x, net = cfg(batch=batch, hw=64)
+        check_network(oracle, x, net, list(range(batch)), net.name + " 64x64")
+
+
+# ------------------------------------------------------------------------- layer sweeps
+
+DENSE_CASES = [
+    # B   H   W  Cin Cout R  S st pd  x     y     res    align-offset
+    (2, 19, 23, 64, 64, 3, 3, 1, 1, "u8", "u8", None, 0),        # several 256-pixel tiles + ragged tail
+    (3, 17, 17, 32, 160, 3, 3, 1, 1, "u8", "u8", "u8", 0),       # two N tiles, ragged N
+    (2, 30, 14, 128, 128, 1, 1, 1, 0, "u8", "s8", "s8", 0),
+    (2, 29, 31, 16, 24, 3, 3, 2, 1, "s8", "u8", None, 0),        # stride 2, N = 24
+    (2, 33, 33, 64, 256, 1, 1, 2, 0, "u8", "s8", None, 0),       # downsample shortcut
+    (1, 40, 40, 4, 64, 7, 7, 2, 3, "s8", "u8", None, 0),         # 4-byte gather path
+    (2, 21, 21, 3, 32, 7, 7, 2, 3, "s8", "u8", None, 0),         # 1-byte gather path (C = 3)
+    (1, 12, 13, 20, 10, 3, 3, 1, 1, "u8", "u8", "u8", 0),        # C % 4 == 0, N % 4 != 0
+    (1, 9, 9, 7, 5, 3, 3, 1, 1, "u8", "s8", "s32", 0),           # odd everything
+    (2, 10, 10, 48, 48, 3, 3, 1, 1, "u8", "u8", None, 4),        # x only 4-byte aligned
+    (2, 10, 10, 48, 48, 3, 3, 1, 1, "u8", "u8", None, 1),        # x only 1-byte aligned
+    (1, 1, 300, 512, 1000, 1, 1, 1, 0, "u8", "s32", None, 0),    # FC-like: int32 logits
+    (1, 1, 7, 2048, 1000, 1, 1, 1, 0, "u8", "s32", "s32", 0),
+    (1, 7, 7, 512, 512, 3, 3, 1, 1, "u8", "u8", "u8", 0),        # K = 4608
+    (1, 5, 5, 8, 8, 5, 5, 1, 4, "u8", "u8", None, 0),            # padding wider than the image edge
+    (1, 1, 1, 16, 16, 1, 1, 1, 0, "u8", "u8", None, 0),          # single pixel
+    (1, 6, 6, 1, 1, 3, 3, 1, 1, "u8", "u8", None, 0),            # single channel in and out
+    (4, 14, 14, 256, 64, 1, 1, 1, 0, "u8", "u8", "u8", 0),
+]
+
+
+@pytest.mark.parametrize("case", DENSE_CASES)
+def test_dense_layer_sweep(oracle, case):
+    B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt, off = case
+    rng = np.random.default_rng(zlib.crc32(repr(case).encode()))
+    for trial in range(3):
+        shift = [None, 0, -2][trial] if yt != "s32" else None
+        x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt, shift=shift)
+        if trial == 1 and yt != "s32":
+            L.clip_lo, L.clip_hi = (10, 100) if yt == "u8" else (-50, 60)
+        want = oracle.conv2d_fixed(x, L.w, L.bias, L, (st, st), (pd, pd), res)
+        got = gpu_layer(L, x, res, off)
+        assert_same(got, want, "dense %s trial %d" % (str(case), trial))
+
+
+def test_residual_shift_directions(oracle):
+    """Residual finer than, equal to and coarser than the accumulator scale."""
+    rng = np.random.default_rng(77)
+    for fl_res in (0, 5, 9, 12, 14):
+        x, L, res = wl.random_conv_case(rng, 2, 12, 12, 32, 32, 3, 3, 1, 1, "u8", "u8", "s8", shift=6)
+        L.fl_x, L.fl_w, L.fl_y, L.fl_res = 4, 5, 3, fl_res
+        want = oracle.conv2d_fixed(x, L.w, L.bias, L, (1, 1), (1, 1), res)
+        assert_same(gpu_layer(L, x, res), want, "fl_res %d" % fl_res)
+
+
+def test_shift_extremes(oracle):
+    rng = np.random.default_rng(78)
+    for shift, fl in ((24, (12, 12, 0)), (-8, (0, 0, 8)), (1, (1, 0, 0))):
+        x, L, _ = wl.random_conv_case(rng, 1, 8, 8, 64, 32, 3, 3, 1, 1, "u8", "u8", shift=shift,
+                                      w_std=30.0 if shift > 8 else 0.7)
+        L.fl_x, L.fl_w, L.fl_y = fl
+        if shift == 24:
+            L.bias = rng.integers(0, 2 ** 30, L.Cout).astype(np.int32)
+        want = oracle.conv2d_fixed(x, L.w, L.bias, L, (1, 1), (1, 1))
+        assert_same(gpu_layer(L, x), want, "shift %d" % shift)
+        assert len(np.unique(want)) > (1 if shift < 0 else 2)
+
+
+def test_degenerate_inputs(oracle):
+    rng = np.random.default_rng(79)
+    x, L, _ = wl.random_conv_case(rng, 1, 8, 8, 16, 16, 3, 3, 1, 1)
+    L.w[:] = 0                                                  # output = fix_quant(bias)
+    assert_same(gpu_layer(L, x), oracle.conv2d_fixed(x, L.w, L.bias, L, (1, 1), (1, 1)), "zero weights")
+    x, L, _ = wl.random_conv_case(rng, 1, 8, 8, 16, 16, 3, 3, 1, 1)
+    L.clip_lo = L.clip_hi = 9                                   # degenerate clip
+    assert (gpu_layer(L, x) == 9).all()
+    x, L, _ = wl.random_conv_case(rng, 1, 8, 8, 16, 16, 1, 1, 1, 0, x_type="s8")
+    x[:] = -128                                                 # -128 is accepted on input
+    L.bias = None
+    assert_same(gpu_layer(L, x), oracle.conv2d_fixed(x, L.w, None, L), "minus 128 input, no bias")
+    x, L, _ = wl.random_conv_case(rng, 1, 8, 8, 16, 16, 1, 1, 1, 0)
+    x[:] = 255
+    L.w[:] = 127                                                # largest products
+    assert_same(gpu_layer(L, x), oracle.conv2d_fixed(x, L.w, L.bias, L), "max magnitude")
+    # empty batch: nothing launched, nothing written
+    import ctypes
+    y = torch.full((1, 8, 8, 16), 5, dtype=torch.uint8, device=DEV)
+    xt, wt = torch.from_numpy(x).to(DEV), torch.from_numpy(L.w).to(DEV)
+    q = f8.make_quant(L)
+    rc = f8.lib().f8_conv2d_fixed(xt.data_ptr(), wt.data_ptr(), None, y.data_ptr(), 0, 8, 8, 16, 16, 1, 1,
+                                  1, 1, 0, 0, ctypes.byref(q), None)
+    torch.cuda.synchronize()
+    assert rc == 0 and (y == 5).all()
+
+
+DW_CASES = [
+    (2, 19, 23, 144, 3, 3, 1, 1, "u8", "u8", None),
+    (2, 20, 21, 96, 3, 3, 2, 1, "u8", "u8", None),
+    (1, 15, 15, 32, 5, 5, 1, 2, "s8", "s8", "s8"),
+    (1, 9, 11, 7, 3, 3, 1, 1, "u8", "u8", "u8"),           # channels not a multiple of 4
+    (1, 8, 8, 24, 3, 3, 1, 0, "u8", "s32", None),
+    (3, 7, 7, 576, 3, 3, 1, 1, "u8", "u8", None),
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_depthwise_sweep(oracle, case):
+    B, H, W, C, R, S, st, pd, xt, yt, rt = case
+    rng = np.random.default_rng(zlib.crc32(repr(case).encode()))
+    for trial in range(3):
+        shift = [None, 0, -1][trial] if yt != "s32" else None
+        x, L, res = wl.random_conv_case(rng, B, H, W, C, C, R, S, st, pd, xt, yt, rt, shift=shift, depthwise=True)
+        want = oracle.dwconv_fixed(x, L.w, L.bias, L, (st, st), (pd, pd), res)
+        assert_same(gpu_layer(L, x, res), want, "dw %s trial %d" % (str(case), trial))
+
+
+def test_pools(oracle):
+    rng = np.random.default_rng(80)
+    for kind, shape, k, st, pd in (("u8", (2, 31, 29, 64), 3, 2, 1), ("s8", (1, 10, 10, 6), 2, 2, 0),
+                                   ("u8", (1, 7, 9, 5), 3, 1, 1)):
+        x = wl.draw_u8(rng, shape) if kind == "u8" else rng.integers(-128, 0, shape, dtype=np.int8)
+        want = oracle.maxpool(x, kind, (k, k), (st, st), (pd, pd))
+        L = wl.LayerSpec(op="maxpool", Cin=shape[3], Cout=shape[3], R=k, S=k, stride=st, pad=pd,
+                         x_type=kind, y_type=kind, out_hw=want.shape[1:3])
+        assert_same(gpu_layer(L, x), want, "maxpool " + kind)
+    for shape, fl_w in (((3, 7, 7, 512), 6), ((2, 5, 6, 10), 5), ((1, 2, 2, 3), 0)):
+        x = wl.draw_u8(rng, shape)
+        L = wl.LayerSpec(op="gpool", Cin=shape[3], Cout=shape[3], fl_x=4, fl_w=fl_w, fl_y=4, clip_lo=0,
+                         clip_hi=255, x_type="u8", y_type="u8")
+        assert_same(gpu_layer(L, x), oracle.global_pool_fixed(x, L), "gpool")
+
+
+def test_repeatable_and_streams(oracle):
+    """Same inputs, three runs, two streams: identical bits (the race detector)."""
+    x, L = wl.config1(batch=4)
+    xt, wt, bt = (torch.from_numpy(a).to(DEV) for a in (x, L.w, L.bias))
+    want = oracle.conv2d_fixed(x, L.w, L.bias, L, (1, 1), (1, 1))
+    outs = []
+    s2 = torch.cuda.Stream()
+    for i in range(3):
+        y = torch.empty((4, 56, 56, 64), dtype=torch.uint8, device=DEV)
+        if i == 1:
+            s2.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s2):
+                f8.f8_conv2d_fixed(xt, wt, bt, y, L, (1, 1), (1, 1))
+            s2.synchronize()
+        else:
+            f8.f8_conv2d_fixed(xt, wt, bt, y, L, (1, 1), (1, 1))
+        torch.cuda.synchronize()
+        outs.append(y.cpu().numpy())
+    for o in outs:
+        assert_same(o, want, "repeat")

@@ -1,0 +1,157 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, rejects bad arguments before launching anything, and the chain
+planner's book-keeping."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2202_05239_amd import binding as f8
+from paper_2202_05239_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)        # never dereferenced: every call below fails validation first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "f8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(f8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = f8.lib()
+    names = declared_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(f8.EXPORTS) == names
+    assert L.f8_abi_version() == 1
+
+
+def quant(**kw):
+    q = f8.f8_quant()
+    q.fl_x, q.fl_w, q.fl_y, q.clip_lo, q.clip_hi = 4, 4, 4, 0, 255
+    q.x_type, q.y_type, q.res, q.res_type, q.fl_res = f8.F8_U8, f8.F8_U8, None, 0, 0
+    for k, v in kw.items():
+        setattr(q, k, v)
+    return q
+
+
+def conv(q, x=FAKE, w=FAKE, bias=None, y=FAKE, B=1, H=8, W=8, Cin=16, Cout=16, R=3, S=3, sh=1, sw=1, ph=1, pw=1):
+    return f8.lib().f8_conv2d_fixed(x, w, bias, y, B, H, W, Cin, Cout, R, S, sh, sw, ph, pw,
+                                    ctypes.byref(q) if q is not None else None, None)
+
+
+def test_conv_argument_validation():
+    assert conv(quant(), x=None) == 1
+    assert conv(quant(), w=None) == 1
+    assert conv(quant(), y=None) == 1
+    assert conv(None) == 1
+    assert conv(quant(), H=0) == 2
+    assert conv(quant(), sh=0) == 2
+    assert conv(quant(), ph=-1) == 2
+    assert conv(quant(), Cin=8192, R=3, S=3) == 2                 # K = 73728 > 65536
+    assert conv(quant(fl_y=17)) == 3                               # shift -9
+    assert conv(quant(fl_x=12, fl_w=13, fl_y=0)) == 3              # shift 25
+    assert conv(quant(clip_lo=3, clip_hi=2)) == 4
+    assert conv(quant(clip_hi=256)) == 4
+    assert conv(quant(y_type=f8.F8_S8, clip_lo=-128, clip_hi=127)) == 4
+    assert conv(quant(x_type=f8.F8_S32)) == 5
+    assert conv(quant(y_type=7)) == 5
+    assert conv(quant(res=0x2000, res_type=9)) == 5
+    assert conv(quant(res=0x2000, res_type=f8.F8_U8, fl_res=40)) == 3
+    assert conv(quant(), bias=ctypes.c_void_p(0x1002)) == 7
+    assert conv(quant(y_type=f8.F8_S32), y=ctypes.c_void_p(0x1001)) == 7
+    assert conv(quant(res=0x1000, res_type=f8.F8_U8, fl_res=4), y=ctypes.c_void_p(0x1000)) == 8
+    assert conv(quant(), B=70000, H=256, W=256, Cin=16) == 8      # beyond 2^31-1 bytes
+    # empty problems are fine and launch nothing
+    assert conv(quant(), B=0) == 0
+    assert conv(quant(), Cout=0) == 0
+    assert conv(quant(), H=1, W=1, R=3, S=3, ph=0, pw=0) == 0     # window larger than image: P = Q = 0
+
+
+def test_other_entry_points_validate():
+    L = f8.lib()
+    q = quant()
+    assert L.f8_gemm_fixed(FAKE, FAKE, None, FAKE, -1, 8, 8, ctypes.byref(q), None) == 2
+    assert L.f8_gemm_fixed(FAKE, FAKE, None, FAKE, 8, 0, 8, ctypes.byref(q), None) == 2
+    assert L.f8_gemm_fixed(None, FAKE, None, FAKE, 8, 8, 8, ctypes.byref(q), None) == 1
+    assert L.f8_gemm_fixed(FAKE, FAKE, None, FAKE, 0, 8, 8, ctypes.byref(q), None) == 0
+    assert L.f8_dwconv_fixed(FAKE, FAKE, None, FAKE, 1, 8, 8, 0, 3, 3, 1, 1, 1, 1, ctypes.byref(q), None) == 2
+    assert L.f8_dwconv_fixed(FAKE, None, None, FAKE, 1, 8, 8, 4, 3, 3, 1, 1, 1, 1, ctypes.byref(q), None) == 1
+    assert L.f8_maxpool(FAKE, FAKE, 1, 8, 8, 4, 3, 3, 2, 2, 3, 1, f8.F8_U8, None) == 2   # pad >= window
+    assert L.f8_maxpool(FAKE, FAKE, 1, 8, 8, 4, 3, 3, 2, 2, 1, 1, f8.F8_S32, None) == 5
+    assert L.f8_global_pool_fixed(FAKE, FAKE, 1, 300, 300, 4, ctypes.byref(q), None) == 2
+    qr = quant(res=0x3000)
+    assert L.f8_global_pool_fixed(FAKE, FAKE, 1, 7, 7, 4, ctypes.byref(qr), None) == 8
+    assert L.f8_status_str(3).decode().startswith("fractional")
+
+
+def test_clip_from_alpha():
+    assert f8.f8_clip_from_alpha(6.0, 5) == 192                    # 6.0 * 2^5
+    assert f8.f8_clip_from_alpha(6.0, 6) == 255                    # saturates at the type's top
+    assert f8.f8_clip_from_alpha(1.0, 7, True) == 127
+    assert f8.f8_clip_from_alpha(0.7, 3) == 6                      # 5.6 -> 6
+    assert f8.f8_clip_from_alpha(0.3125, 3) == 3                   # 2.5 -> 3 (half up)
+    assert f8.f8_clip_from_alpha(-1.0, 3) == 0
+    assert f8.f8_clip_from_alpha(3.0, 0) == 3
+
+
+def make_descs(net):
+    descs = (f8.f8_layer_desc * len(net.layers))()
+    for d, S in zip(descs, net.layers):
+        d.op = {"conv": 0, "dwconv": 1, "maxpool": 2, "gpool": 3}[S.op]
+        d.src, d.dst, d.res = S.src, S.dst, S.res
+        d.Cin, d.Cout, d.R, d.S = S.Cin, S.Cout, S.R, S.S
+        d.stride_h = d.stride_w = S.stride
+        d.pad_h = d.pad_w = S.pad
+        d.q = f8.make_quant(S)
+        if S.res >= 0:
+            d.q.res_type, d.q.fl_res = {"u8": 0, "s8": 1, "s32": 2}[S.res_type], S.fl_res
+        d.w = 0x10000 if S.w is not None else None
+        d.bias = 0x20000 if S.bias is not None else None
+    return descs
+
+
+def test_chain_planner_host_side():
+    L = f8.lib()
+    _, net = wl.config4(batch=1, hw=64)
+    descs = make_descs(net)
+    h = ctypes.c_void_p()
+    assert L.f8_chain_create(descs, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 0
+    n1, n8, nk = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    assert L.f8_chain_workspace_bytes(h, 1, ctypes.byref(n1)) == 0
+    assert L.f8_chain_workspace_bytes(h, 8, ctypes.byref(n8)) == 0
+    total = sum(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers[:-1])
+    biggest = max(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers[:-1])
+    # reuse: the arena is far smaller than the sum of all tensors, yet holds the largest few
+    consts = sum((l.Cout + 255) // 256 * 256 * 4 for l in net.layers if l.op == "conv")
+    assert biggest <= n1.value - consts < total / 4
+    assert n8.value - n1.value == 7 * (n1.value - consts - 256 - (-consts % 256))
+    # run before prepare is refused; so is a wrong batch
+    assert L.f8_chain_run(h, FAKE, FAKE, ctypes.c_void_p(0x100000), 1, None) == 10
+    assert L.f8_chain_set_keep_all(h, 1) == 0
+    assert L.f8_chain_workspace_bytes(h, 1, ctypes.byref(nk)) == 0
+    assert nk.value - consts >= total
+    L.f8_chain_destroy(h)
+    # inconsistent chains are rejected
+    bad = make_descs(net)
+    bad[3].q.fl_x += 1
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 3
+    bad = make_descs(net)
+    bad[2].Cin += 1
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 2
+    bad = make_descs(net)
+    bad[5].src = 40
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 2
+    assert L.f8_chain_create(make_descs(net), len(net.layers), 64, 64, 3, f8.F8_U8, ctypes.byref(h)) == 2
+
+
+def test_binding_refuses_to_run_without_library(monkeypatch):
+    monkeypatch.setattr(f8, "_lib", None)
+    monkeypatch.setattr(f8, "LIB_PATH", "/nonexistent/libf8.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        f8.lib()
