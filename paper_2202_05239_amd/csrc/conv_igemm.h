@@ -30,6 +30,13 @@ int launch_conv_igemm(const ConvParams &p, int vec, hipStream_t stream);
 int conv_variant(int N);
 const char *conv_variant_name(int variant);
 
+// Fast path (conv_fast.hip): Cin % 16 == 0, 8-bit output and residual, Cout % 4 == 0,
+// 16-byte aligned x and w.  conv_fast_variant picks the tile shape.
+bool conv_fast_applicable(const ConvParams &p);
+int conv_fast_variant(const ConvParams &p);
+const char *conv_fast_variant_name(int variant);
+int launch_conv_fast(const ConvParams &p, hipStream_t stream);
+
 // acc0[n] = bias[n] + rounding addend + (unsigned x ? 128 * sum_k w[n][k] : 0), zero for
 // N <= n < n_pad.
 int launch_fold_acc0(const int8_t *w, const int32_t *bias, int32_t *acc0, int N, int n_pad, int K,

@@ -80,7 +80,16 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void
   p.fd_cpt = FastDiv((uint32_t)(g.Cin / vec));
   p.fd_s = FastDiv((uint32_t)g.S);
   if (p.M == 0 || p.N == 0) return F8_OK;
+  if (conv_fast_applicable(p)) return launch_conv_fast(p, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
   return launch_conv_igemm(p, vec, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+}
+
+const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
+  ConvParams p;
+  p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
+  p.C = g.Cin; p.N = g.Cout; p.y_type = q.y_type; p.res_type = q.res_type;
+  if (conv_fast_applicable(p)) return conv_fast_variant_name(conv_fast_variant(p));
+  return conv_variant_name(conv_variant(g.Cout));
 }
 
 f8_status enqueue_fold(const int8_t *w, const int32_t *bias, int32_t *acc0, const Geom &g,

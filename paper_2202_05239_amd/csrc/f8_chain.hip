@@ -322,7 +322,7 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
   if (L.res >= 0) bytes += M * g.Cout * (double)elem_size(c->tensors[L.res].type);
   switch (L.op) {
     case F8_OP_CONV:
-      name = conv_variant_name(conv_variant(g.Cout));
+      name = conv_kernel_name(g, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       break;
