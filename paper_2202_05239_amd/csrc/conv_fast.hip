@@ -111,11 +111,14 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
   auto issue_loads = [&](int kstep, int stage) {
     const uint32_t u = (uint32_t)(kstep * 4 + cl);            // 16-byte unit index along K
     const bool kvalid = (int)(u * 16) < p.K;
-    const uint32_t tap = p.fd_cpt.div(u);
-    const uint32_t cu = u - tap * p.fd_cpt.d;
+    // A unit is 16 channels of one tap (C % 16 == 0) or 16 / C whole taps of one window
+    // row (C < 16, windows never clipped): either way 16 contiguous bytes starting at
+    // (r, s, c0), and only that first tap needs the bounds check.
+    const uint32_t tap = p.fd_c.div(u * 16);
+    const uint32_t c0 = u * 16 - tap * p.fd_c.d;
     const uint32_t r = p.fd_s.div(tap);
     const int s = (int)(tap - r * p.S);
-    const int toff = ((int)r * p.W + s) * p.C + (int)cu * 16;
+    const int toff = ((int)r * p.W + s) * p.C + (int)c0;
     uint8_t *base = lds + stage * STAGE + wave * 1024;
 #pragma unroll
     for (int i = 0; i < XR; ++i) {
@@ -306,7 +309,13 @@ int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
 
 bool conv_fast_applicable(const ConvParams &p) {
   const uintptr_t bits = reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w);
-  if ((p.C & 15) || (bits & 15)) return false;
+  if (bits & 15) return false;
+  // 16-byte units: 16 channels of one tap, or (small C) whole taps of one window row when
+  // no window is ever clipped by the image border.
+  const bool wide = (p.C & 15) == 0;
+  const bool packed = p.C < 16 && 16 % p.C == 0 && ((p.S * p.C) & 15) == 0 && p.ph == 0 && p.pw == 0 &&
+                      (p.P - 1) * p.sh + p.R <= p.H && (p.Q - 1) * p.sw + p.S <= p.W;
+  if (!wide && !packed) return false;
   if (p.y_type == T_S32 || (p.res && p.res_type == T_S32)) return false;
   if (p.N & 3) return false;
   uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res);

@@ -19,7 +19,7 @@ struct ConvParams {
   uint32_t xor_mask;        // 0x80808080 for unsigned activations, 0 for signed
   int shift, lo, hi;        // requantisation
   int y_type, res_type, res_d;
-  FastDiv fd_pq, fd_q, fd_cpt, fd_s;   // by P*Q, Q, units per tap (C / VEC), S
+  FastDiv fd_pq, fd_q, fd_c, fd_s;     // by P*Q, Q, C, S
 };
 
 // Launches the implicit-GEMM kernel.  vec is the widest of 16, 4, 1 bytes that divides C

@@ -33,12 +33,13 @@ template <int VEC>
 __device__ __forceinline__ TapRef decode_unit(const ConvParams &p, uint32_t u) {
   TapRef t;
   t.kvalid = (int)(u * VEC) < p.K;
-  const uint32_t tap = p.fd_cpt.div(u);
-  const uint32_t cu = u - tap * p.fd_cpt.d;
+  const uint32_t k0 = u * VEC;                       // position along K = (r, s, c)
+  const uint32_t tap = p.fd_c.div(k0);
+  const uint32_t c0 = k0 - tap * p.fd_c.d;
   const uint32_t r = p.fd_s.div(tap);
   t.r = (int)r;
   t.s = (int)(tap - r * p.S);
-  t.off = (t.r * p.W + t.s) * p.C + (int)cu * VEC;
+  t.off = (t.r * p.W + t.s) * p.C + (int)c0;
   return t;
 }
 

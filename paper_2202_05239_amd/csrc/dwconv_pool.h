@@ -30,4 +30,10 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream);
 int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream);
 int launch_gpool(const DwParams &p, bool vec4, hipStream_t stream);
 
+// Stem re-layout for convolutions with C <= 4 input channels: explicit zero border and
+// channels padded to 4 (input), window rows padded to Sp taps of 4 channels (weights).
+int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp, int Wp, int ph, int pw,
+                     hipStream_t stream);
+int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C, int Sp, hipStream_t stream);
+
 }  // namespace f8

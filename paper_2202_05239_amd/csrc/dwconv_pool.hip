@@ -146,6 +146,44 @@ __global__ __launch_bounds__(NT) void gpool_kernel(const DwParams p, const long 
   else yp[0] = (uint8_t)acc[0];
 }
 
+// Stem re-layout (exact, values unchanged): x [B][H][W][C] -> xp [B][Hp][Wp][4] with the
+// image at offset (ph, pw), zeros elsewhere and in channels C..3.  One thread per output
+// pixel (one dword).  Turns a clipped-window, odd-channel convolution into one whose
+// windows are never clipped and whose taps are whole dwords.
+__global__ __launch_bounds__(NT) void pad_input_kernel(const uint8_t *x, uint32_t *xp, int B, int H, int W, int C,
+                                                       int Hp, int Wp, int ph, int pw, long long total) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int j = (int)(gid % Wp);
+  const long long t = gid / Wp;
+  const int i = (int)(t % Hp);
+  const int b = (int)(t / Hp);
+  const int ih = i - ph, iw = j - pw;
+  uint32_t v = 0;
+  if ((unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W) {
+    const uint8_t *src = x + (((size_t)b * H + ih) * W + iw) * C;
+    for (int c = 0; c < C; ++c) v |= (uint32_t)src[c] << (8 * c);
+  }
+  xp[gid] = v;
+}
+
+// w [N][R][S][C] -> wp [N][R][Sp][4], zeros in taps S..Sp-1 and channels C..3.
+__global__ __launch_bounds__(NT) void repack_weights_kernel(const int8_t *w, uint32_t *wp, int N, int R, int S, int C,
+                                                            int Sp, long long total) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int s = (int)(gid % Sp);
+  const long long t = gid / Sp;
+  const int r = (int)(t % R);
+  const int n = (int)(t / R);
+  uint32_t v = 0;
+  if (s < S) {
+    const int8_t *src = w + (((size_t)n * R + r) * S + s) * C;
+    for (int c = 0; c < C; ++c) v |= (uint32_t)(uint8_t)src[c] << (8 * c);
+  }
+  wp[gid] = v;
+}
+
 inline unsigned blocks_for(long long total) { return (unsigned)((total + NT - 1) / NT); }
 
 }  // namespace
@@ -163,6 +201,23 @@ int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream) {
   if (total <= 0) return 0;
   if (vec4) hipLaunchKernelGGL(maxpool_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
   else hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
+  return (int)hipGetLastError();
+}
+
+int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp, int Wp, int ph, int pw,
+                     hipStream_t stream) {
+  const long long total = (long long)B * Hp * Wp;
+  if (total <= 0) return 0;
+  hipLaunchKernelGGL(pad_input_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, static_cast<const uint8_t *>(x),
+                     static_cast<uint32_t *>(xp), B, H, W, C, Hp, Wp, ph, pw, total);
+  return (int)hipGetLastError();
+}
+
+int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C, int Sp, hipStream_t stream) {
+  const long long total = (long long)N * R * Sp;
+  if (total <= 0) return 0;
+  hipLaunchKernelGGL(repack_weights_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, w,
+                     static_cast<uint32_t *>(wp), N, R, S, C, Sp, total);
   return (int)hipGetLastError();
 }
 

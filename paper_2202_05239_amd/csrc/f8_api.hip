@@ -77,7 +77,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void
   const int vec = widest_vec(g.Cin, x, w);
   p.fd_pq = FastDiv((uint32_t)(g.P * g.Q));
   p.fd_q = FastDiv((uint32_t)g.Q);
-  p.fd_cpt = FastDiv((uint32_t)(g.Cin / vec));
+  p.fd_c = FastDiv((uint32_t)g.Cin);
   p.fd_s = FastDiv((uint32_t)g.S);
   if (p.M == 0 || p.N == 0) return F8_OK;
   if (conv_fast_applicable(p)) return launch_conv_fast(p, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
@@ -88,6 +88,8 @@ const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
   p.C = g.Cin; p.N = g.Cout; p.y_type = q.y_type; p.res_type = q.res_type;
+  p.H = g.H; p.W = g.W; p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+  p.P = g.P; p.Q = g.Q;
   if (conv_fast_applicable(p)) return conv_fast_variant_name(conv_fast_variant(p));
   return conv_variant_name(conv_variant(g.Cout));
 }

@@ -1,11 +1,17 @@
 // Layer-chain runner: a whole fixed-point network forward as a fixed sequence of launches.
 //
-// The chain owns only host-side book-keeping.  Activations and the folded per-channel
-// constants live in a caller-provided device workspace whose layout is
-//   [ constants: acc0 vector of every dense layer ][ activation arena ]
+// The chain owns only host-side book-keeping.  Activations and the per-layer constants
+// live in a caller-provided device workspace whose layout is
+//   [ constants: acc0 vector (and re-laid-out stem weights) of every dense layer ][ arena ]
 // Every tensor's size is linear in the batch, so the arena is planned once per image
 // (first-fit over tensor lifetimes, offsets in multiples of 256 bytes) and scaled by the
 // batch at run time.
+//
+// Stem re-layout.  A dense layer with at most 4 input channels (the 7x7/2 ImageNet stem)
+// is run on a re-laid-out copy of its operands: the input gets an explicit zero border
+// and 4 channels, each window row is padded to a multiple of 4 taps with zero weights.
+// The sums are unchanged (only zero products are added), windows are never clipped, and
+// 16 contiguous bytes hold four whole taps, which is what the fast kernel's loads need.
 #include <algorithm>
 #include <new>
 #include <vector>
@@ -28,6 +34,14 @@ struct Tensor {
   bool external = false;    // input x or final output
 };
 
+struct Stem {
+  bool on = false;
+  int Sp = 0, Hp = 0, Wp = 0;       // padded window width, padded image extent (4 channels)
+  size_t w_off = 0;                 // re-laid-out weights: byte offset in the constants region
+  size_t x_off_per_image = 0;       // re-laid-out input: arena offset per image
+  size_t x_bytes_per_image = 0;
+};
+
 size_t elem_size(int type) { return type == F8_S32 ? 4 : 1; }
 size_t round256(size_t v) { return (v + 255) / 256 * 256; }
 
@@ -36,6 +50,7 @@ size_t round256(size_t v) { return (v + 255) / 256 * 256; }
 struct f8_chain {
   std::vector<f8_layer_desc> layers;
   std::vector<Geom> geom;              // per layer, B filled at run time
+  std::vector<Stem> stem;              // per layer
   std::vector<Tensor> tensors;
   std::vector<size_t> acc0_off;        // per layer: byte offset in the constants region
   size_t const_bytes = 0;
@@ -87,9 +102,11 @@ struct f8_chain {
       }
     };
     for (size_t li = 0; li < layers.size(); ++li) {
+      if (stem[li].on) stem[li].x_off_per_image = alloc(round256(stem[li].x_bytes_per_image));
       Tensor &d = tensors[layers[li].dst];
       if (!d.external) d.offset_per_image = alloc(round256(d.bytes_per_image));
       if (keep_all) continue;
+      if (stem[li].on) release(stem[li].x_off_per_image, round256(stem[li].x_bytes_per_image));
       const int ids[2] = {layers[li].src, layers[li].res};
       for (int k = 0; k < 2; ++k) {
         if (ids[k] < 0) continue;
@@ -100,6 +117,52 @@ struct f8_chain {
     }
     arena_per_image = top;
     planned = true;
+  }
+
+  uint8_t *arena(void *workspace) const { return static_cast<uint8_t *>(workspace) + const_bytes; }
+
+  void *tensor_ptr(int id, const void *x, void *out, void *workspace, int batch) const {
+    if (id == 0) return const_cast<void *>(x);
+    if (id == last_tensor) return out;
+    return arena(workspace) + tensors[id].offset_per_image * (size_t)batch;
+  }
+
+  // Geometry and operands of dense layer i as the kernel sees them (after the stem re-layout).
+  Geom conv_geom(size_t i, int batch) const {
+    Geom g = geom[i];
+    g.B = batch;
+    if (stem[i].on) {
+      g.H = stem[i].Hp; g.W = stem[i].Wp; g.Cin = 4; g.S = stem[i].Sp; g.ph = 0; g.pw = 0;
+    }
+    return g;
+  }
+  const int8_t *conv_weights(size_t i, void *workspace) const {
+    if (!stem[i].on) return layers[i].w;
+    return reinterpret_cast<const int8_t *>(static_cast<uint8_t *>(workspace) + stem[i].w_off);
+  }
+
+  f8_status launch_layer(size_t i, const void *x, void *out, void *workspace, int batch, hipStream_t s) const {
+    const f8_layer_desc &L = layers[i];
+    Geom g = geom[i];
+    g.B = batch;
+    const void *src = tensor_ptr(L.src, x, out, workspace, batch);
+    void *dst = tensor_ptr(L.dst, x, out, workspace, batch);
+    const void *res = L.res >= 0 ? tensor_ptr(L.res, x, out, workspace, batch) : nullptr;
+    switch (L.op) {
+      case F8_OP_CONV: {
+        const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
+        if (stem[i].on) {
+          void *xp = arena(workspace) + stem[i].x_off_per_image * (size_t)batch;
+          if (launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s) != 0)
+            return F8_ERR_DEVICE;
+          src = xp;
+        }
+        return enqueue_conv(src, conv_weights(i, workspace), acc0, dst, res, conv_geom(i, batch), L.q, s);
+      }
+      case F8_OP_DWCONV: return enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s);
+      case F8_OP_MAXPOOL: return enqueue_maxpool(src, dst, g, L.q.x_type, s);
+      default: return enqueue_gpool(src, dst, g, L.q, s);
+    }
   }
 };
 
@@ -181,7 +244,20 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     c->layers.push_back(L);
     c->geom.push_back(g);
     c->acc0_off.push_back(c->const_bytes);
-    if (L.op == F8_OP_CONV) c->const_bytes += acc0_padded(L.Cout) * sizeof(int32_t);
+    Stem sm;
+    if (L.op == F8_OP_CONV) {
+      c->const_bytes += acc0_padded(L.Cout) * sizeof(int32_t);
+      if (L.Cin <= 4 && L.q.y_type != F8_S32 && (L.Cout & 3) == 0) {
+        sm.on = true;
+        sm.Sp = (L.S + 3) / 4 * 4;
+        sm.Hp = (g.P - 1) * g.sh + g.R;
+        sm.Wp = (g.Q - 1) * g.sw + sm.Sp;
+        sm.x_bytes_per_image = (size_t)sm.Hp * sm.Wp * 4;
+        sm.w_off = c->const_bytes;
+        c->const_bytes += round256((size_t)L.Cout * g.R * sm.Sp * 4);
+      }
+    }
+    c->stem.push_back(sm);
   }
   if (st != F8_OK) { delete c; return st; }
   c->last_tensor = c->layers.back().dst;
@@ -208,6 +284,8 @@ f8_status f8_chain_workspace_bytes(const f8_chain *cc, int batch, size_t *bytes)
   for (const Tensor &t : c->tensors)
     if (t.producer != -2 && (long long)t.bytes_per_image / (long long)elem_size(t.type) * batch > 0x7fffffffLL)
       return F8_ERR_UNSUPPORTED;
+  for (const Stem &sm : c->stem)
+    if (sm.on && (long long)sm.x_bytes_per_image * batch > 0x7fffffffLL) return F8_ERR_UNSUPPORTED;
   *bytes = c->const_bytes + c->arena_per_image * (size_t)batch + 256;
   return F8_OK;
 }
@@ -221,19 +299,17 @@ f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream
   for (size_t i = 0; i < c->layers.size(); ++i) {
     const f8_layer_desc &L = c->layers[i];
     if (L.op != F8_OP_CONV) continue;
+    if (c->stem[i].on) {
+      void *wp = static_cast<uint8_t *>(workspace) + c->stem[i].w_off;
+      if (launch_repack_weights(L.w, wp, L.Cout, L.R, L.S, L.Cin, c->stem[i].Sp, s) != 0) return F8_ERR_DEVICE;
+    }
     int32_t *acc0 = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
-    const f8_status st = enqueue_fold(L.w, L.bias, acc0, c->geom[i], L.q, s);
+    const f8_status st = enqueue_fold(c->conv_weights(i, workspace), L.bias, acc0, c->conv_geom(i, 1), L.q, s);
     if (st != F8_OK) return st;
   }
   c->prepared_ws = workspace;
   c->prepared_batch = batch;
   return F8_OK;
-}
-
-static void *tensor_ptr(const f8_chain *c, int id, const void *x, void *out, void *workspace, int batch) {
-  if (id == 0) return const_cast<void *>(x);
-  if (id == c->last_tensor) return out;
-  return static_cast<uint8_t *>(workspace) + c->const_bytes + c->tensors[id].offset_per_image * (size_t)batch;
 }
 
 f8_status f8_chain_run(f8_chain *c, const void *x, void *out, void *workspace, int batch, void *stream) {
@@ -244,23 +320,7 @@ f8_status f8_chain_run(f8_chain *c, const void *x, void *out, void *workspace, i
   if (batch == 0) return F8_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   for (size_t i = 0; i < c->layers.size(); ++i) {
-    const f8_layer_desc &L = c->layers[i];
-    Geom g = c->geom[i];
-    g.B = batch;
-    const void *src = tensor_ptr(c, L.src, x, out, workspace, batch);
-    void *dst = tensor_ptr(c, L.dst, x, out, workspace, batch);
-    const void *res = L.res >= 0 ? tensor_ptr(c, L.res, x, out, workspace, batch) : nullptr;
-    f8_status st;
-    switch (L.op) {
-      case F8_OP_CONV: {
-        const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
-        st = enqueue_conv(src, L.w, acc0, dst, res, g, L.q, s);
-        break;
-      }
-      case F8_OP_DWCONV: st = enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s); break;
-      case F8_OP_MAXPOOL: st = enqueue_maxpool(src, dst, g, L.q.x_type, s); break;
-      default: st = enqueue_gpool(src, dst, g, L.q, s); break;
-    }
+    const f8_status st = c->launch_layer(i, x, out, workspace, batch, s);
     if (st != F8_OK) return st;
   }
   return F8_OK;
@@ -272,7 +332,7 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
   if (id < 0 || id >= (int)c->tensors.size() || c->tensors[id].producer == -2) return F8_ERR_SHAPE;
   if (!c->planned) const_cast<f8_chain *>(c)->plan();
   const Tensor &t = c->tensors[id];
-  if (ptr) *ptr = (t.external || !workspace) ? nullptr : tensor_ptr(c, id, nullptr, nullptr, workspace, batch);
+  if (ptr) *ptr = (t.external || !workspace) ? nullptr : c->tensor_ptr(id, nullptr, nullptr, workspace, batch);
   if (h) *h = t.h;
   if (w) *w = t.w;
   if (ch) *ch = t.c;
@@ -280,14 +340,20 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
   if (live_at_end) {
     int live = 1;
     if (!c->keep_all && !t.external) {
-      // overwritten if a tensor produced after this one's last use overlaps it
+      // overwritten if something allocated after this tensor's last use overlaps it
+      const size_t a0 = t.offset_per_image, a1 = a0 + round256(t.bytes_per_image);
       for (size_t j = 0; j < c->tensors.size() && live; ++j) {
         const Tensor &o = c->tensors[j];
         if ((int)j == id || o.external || o.producer == -2 || o.producer <= t.last_use ||
             o.producer <= t.producer)
           continue;
-        const size_t a0 = t.offset_per_image, a1 = a0 + round256(t.bytes_per_image);
         const size_t b0 = o.offset_per_image, b1 = b0 + round256(o.bytes_per_image);
+        if (a0 < b1 && b0 < a1) live = 0;
+      }
+      for (size_t j = 0; j < c->stem.size() && live; ++j) {
+        const Stem &sm = c->stem[j];
+        if (!sm.on || (int)j <= t.last_use || (int)j <= t.producer) continue;
+        const size_t b0 = sm.x_off_per_image, b1 = b0 + round256(sm.x_bytes_per_image);
         if (a0 < b1 && b0 < a1) live = 0;
       }
     }
@@ -298,11 +364,7 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
 
 void f8_chain_destroy(f8_chain *c) { delete c; }
 
-}  // extern "C"
-
 // ---- measurement aids ---------------------------------------------------------------------
-
-extern "C" {
 
 int f8_chain_num_layers(const f8_chain *c) { return c ? (int)c->layers.size() : 0; }
 
@@ -321,11 +383,14 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
   double bytes = (double)batch * rows * cols * g.Cin + M * g.Cout * (double)elem_size(c->tensors[L.dst].type);
   if (L.res >= 0) bytes += M * g.Cout * (double)elem_size(c->tensors[L.res].type);
   switch (L.op) {
-    case F8_OP_CONV:
-      name = conv_kernel_name(g, L.q, L.res >= 0);
+    case F8_OP_CONV: {
+      Geom gk = c->conv_geom(layer, batch);
+      gk.P = g.P; gk.Q = g.Q;
+      name = conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       break;
+    }
     case F8_OP_DWCONV:
       name = "dwconv";
       ops = 2.0 * M * g.R * g.S * g.Cout;
@@ -359,21 +424,7 @@ f8_status f8_chain_profile(f8_chain *c, const void *x, void *out, void *workspac
     hipEvent_t *e = &ev[r * (n + 1)];
     (void)hipEventRecord(e[0], s);
     for (size_t i = 0; i < n && st == F8_OK; ++i) {
-      const f8_layer_desc &L = c->layers[i];
-      Geom g = c->geom[i];
-      g.B = batch;
-      const void *src = tensor_ptr(c, L.src, x, out, workspace, batch);
-      void *dst = tensor_ptr(c, L.dst, x, out, workspace, batch);
-      const void *res = L.res >= 0 ? tensor_ptr(c, L.res, x, out, workspace, batch) : nullptr;
-      switch (L.op) {
-        case F8_OP_CONV:
-          st = enqueue_conv(src, L.w, reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]),
-                            dst, res, g, L.q, s);
-          break;
-        case F8_OP_DWCONV: st = enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s); break;
-        case F8_OP_MAXPOOL: st = enqueue_maxpool(src, dst, g, L.q.x_type, s); break;
-        default: st = enqueue_gpool(src, dst, g, L.q, s); break;
-      }
+      st = c->launch_layer(i, x, out, workspace, batch, s);
       (void)hipEventRecord(e[i + 1], s);
     }
   }

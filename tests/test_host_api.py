@@ -122,15 +122,19 @@ def test_chain_planner_host_side():
     descs = make_descs(net)
     h = ctypes.c_void_p()
     assert L.f8_chain_create(descs, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 0
-    n1, n8, nk = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    n1, n2, n8, nk = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
     assert L.f8_chain_workspace_bytes(h, 1, ctypes.byref(n1)) == 0
+    assert L.f8_chain_workspace_bytes(h, 2, ctypes.byref(n2)) == 0
     assert L.f8_chain_workspace_bytes(h, 8, ctypes.byref(n8)) == 0
     total = sum(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers[:-1])
     biggest = max(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers[:-1])
-    # reuse: the arena is far smaller than the sum of all tensors, yet holds the largest few
-    consts = sum((l.Cout + 255) // 256 * 256 * 4 for l in net.layers if l.op == "conv")
-    assert biggest <= n1.value - consts < total / 4
-    assert n8.value - n1.value == 7 * (n1.value - consts - 256 - (-consts % 256))
+    # reuse: the per-image arena is far smaller than the sum of all tensors, yet holds the
+    # largest few; it scales linearly with the batch, the constants do not
+    arena = n2.value - n1.value
+    consts = n1.value - arena
+    assert biggest <= arena < total / 4
+    assert n8.value - n1.value == 7 * arena
+    assert consts >= sum((l.Cout + 255) // 256 * 256 * 4 for l in net.layers if l.op == "conv")
     # run before prepare is refused; so is a wrong batch
     assert L.f8_chain_run(h, FAKE, FAKE, ctypes.c_void_p(0x100000), 1, None) == 10
     assert L.f8_chain_set_keep_all(h, 1) == 0
