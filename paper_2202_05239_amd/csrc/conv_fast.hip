@@ -1,7 +1,7 @@
 // Fast path of the dense fixed-point convolution / GEMM (F8Net Eq. 6 in integer form) for
 // gfx950, for layers whose input channel count is a multiple of 16 (every layer of the
-// ResNet / MobileNet bodies).  Same arithmetic and operand conventions as the generic
-// kernel in conv_igemm.hip; what differs is how the data moves:
+// ResNet / MobileNet bodies) and for the re-laid-out stem.  Same arithmetic and operand
+// conventions as the generic kernel in conv_igemm.hip; what differs is how the data moves:
 //
 //  * v_mfma_i32_32x32x32_i8 (the full-rate int8 matrix instruction on this chip; the
 //    16x16x64 form issues at half that rate), weights as the row operand, im2col rows as
@@ -9,15 +9,21 @@
 //  * Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
 //    register staging) through a ring of NSTAGE K-steps, so several K-steps of loads are
 //    in flight while the matrix cores work.  Out-of-image taps and rows past the tensor
-//    read a 16-byte page of zeros instead.  The xor with 0x80 that turns unsigned
-//    activations into the signed operand the instruction wants is applied to the
-//    fragment after it is read from LDS.
-//  * LDS rows are 64 bytes (one K-step) with the four 16-byte chunks of a row permuted by
-//    (row / 4) % 4, which makes the ds_read_b128 fragment reads bank-conflict free
-//    without padding (padding is impossible: a wave's LDS-direct load writes 1 KiB of
-//    consecutive bytes).
+//    read a page of zeros instead.  The xor with 0x80 that turns unsigned activations
+//    into the signed operand the instruction wants is applied to the fragment after it
+//    is read from LDS.
+//  * A K-step is BK = 64 or 128 bytes of K per row.  The vector L1 works on 128-byte
+//    lines, so BK = 128 (whole lines) nearly doubles what the L2 -> LDS path delivers;
+//    BK = 64 serves layers whose channel count is not a multiple of 128.
+//  * LDS rows are BK bytes with their 16-byte chunks permuted by a function of the row
+//    index, which makes the ds_read_b128 fragment reads bank-conflict free without
+//    padding (padding is impossible: a wave's LDS-direct load writes 1 KiB of consecutive
+//    bytes).
 //  * The epilogue (residual, rounding shift, clip, pack) exchanges the tile through LDS
 //    so that residual reads and output stores are whole 16-byte pieces of NHWC rows.
+#include <cstdlib>
+#include <type_traits>
+
 #include "conv_igemm.h"
 
 namespace f8 {
@@ -27,9 +33,6 @@ namespace {
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int NT = 256;
-
-// 16 bytes of zeros that stand in for padding taps and for rows outside the tensor.
-__device__ __attribute__((aligned(64))) uint8_t g_zero_page[64];
 
 // One LDS-direct load per call, whatever the predicate: the source address is selected as
 // data (the empty asm keeps the compiler from turning the select into two loads under
@@ -43,6 +46,8 @@ __device__ __forceinline__ void lds_direct_16(bool ok, const void *real, const v
                                    (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
+// Fragment reads are inline asm so that the compiler does not see them as LDS accesses that
+// might alias the LDS-direct loads in flight (it would wait for all of them every time).
 __device__ __forceinline__ v4i lds_read_frag(uint32_t addr, const int imm) {
   v4i v;
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
@@ -54,17 +59,45 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EV>
-__global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, const int tiles_n,
-                                                          const int ntiles) {
+template <int N>
+__device__ __forceinline__ void wait_lgkm() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Wait until at most `ahead` K-steps of LPS loads each are still in flight (ahead <= MAXA).
+template <int MAXA, int LPS>
+__device__ __forceinline__ void wait_ahead(int ahead) {
+  if constexpr (MAXA <= 0) {
+    wait_vm<0>();
+  } else {
+    if (ahead >= MAXA) wait_vm<(MAXA * LPS < 63 ? MAXA * LPS : 63)>();
+    else wait_ahead<MAXA - 1, LPS>(ahead);
+  }
+}
+
+// Chunk permutation of an LDS row: 4 chunks (BK 64) or 8 chunks (BK 128).
+template <int BK>
+__device__ __forceinline__ int row_swizzle(int row) {
+  return BK == 64 ? (row >> 2) & 3 : (row >> 1) & 7;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>
+__global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p, const int tiles_n,
+                                                             const int ntiles) {
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
-  static_assert(BM % 64 == 0 && BN % 64 == 0, "tiles are loaded 64 rows at a time");
+  static_assert(BK == 64 || BK == 128, "K step of 64 or 128 bytes");
+  constexpr int CH = BK / 16;                     // 16-byte chunks per row
+  constexpr int RPG = NT / CH;                    // rows covered by one load of the whole workgroup
+  static_assert(BM % RPG == 0 && BN % RPG == 0, "tiles are loaded RPG rows at a time");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
-  constexpr int XR = BM / 64, WR = BN / 64;       // LDS-direct loads per thread and K step
+  constexpr int XR = BM / RPG, WR = BN / RPG;     // LDS-direct loads per thread and K step
   constexpr int LPS = XR + WR;
-  constexpr int STAGE = (BM + BN) * 64;
+  constexpr int STAGE = (BM + BN) * BK;
+  constexpr int KS = BK / 32;                     // matrix instructions along K per step
+  constexpr int BLK = 32 * BK;                    // bytes of a 32-row block in LDS
   constexpr int PITCH = BN + 16;                  // epilogue tile row pitch
+  static_assert(NB + MB <= 15, "fragment reads of half a step must fit lgkmcnt");
 
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
@@ -72,18 +105,26 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const uint32_t tile = xcd_remap(blockIdx.x, (uint32_t)ntiles);
+  const uint32_t tile = p.remap ? xcd_remap(blockIdx.x, (uint32_t)ntiles) : blockIdx.x;
   const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
 
-  // ---- loader role: LDS slot tid + 256 i  <->  row (tid / 4) + 64 i, physical chunk tid % 4
-  const int lrow = tid >> 2;
-  const int cl = (tid & 3) ^ ((lrow >> 2) & 3);   // logical 16-byte chunk of K this thread fetches
+  // ---- loader role: LDS slot tid + 256 i  <->  row tid / CH + RPG i, physical chunk tid % CH
+  const int lrow = tid / CH;
+  const int cl = (tid % CH) ^ row_swizzle<BK>(lrow);   // logical 16-byte chunk of the K step this thread fetches
+
+  // Two ways to form the load addresses.  UT ("uniform tap": C % BK == 0, at most 32 taps,
+  // x and the page of zeros within 2 GiB of p.lo_base): one K step is BK channels of a single
+  // tap, so the tap is decoded on the scalar unit, a row's validity is one bit of a per-row
+  // tap mask, and addresses are 32-bit offsets from a scalar base.  Otherwise the tap is
+  // decoded per thread and addresses are 64-bit.
   int x_ih0[XR], x_iw0[XR], x_off[XR];
+  uint32_t x_mask[XR];
 #pragma unroll
   for (int i = 0; i < XR; ++i) {
-    const int m = m0 + lrow + i * 64;
+    const int m = m0 + lrow + i * RPG;
+    x_mask[i] = 0;
     if (m < p.M) {
       const uint32_t b = p.fd_pq.div((uint32_t)m);
       const uint32_t rem = (uint32_t)m - b * p.fd_pq.d;
@@ -92,6 +133,13 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
       x_ih0[i] = (int)pp * p.sh - p.ph;
       x_iw0[i] = (int)qq * p.sw - p.pw;
       x_off[i] = ((int)b * p.H + x_ih0[i]) * p.W * p.C + x_iw0[i] * p.C;
+      if (UT) {
+        for (int r = 0; r < p.R; ++r)
+          for (int s2 = 0; s2 < p.S; ++s2)
+            if ((unsigned)(x_ih0[i] + r) < (unsigned)p.H && (unsigned)(x_iw0[i] + s2) < (unsigned)p.W)
+              x_mask[i] |= 1u << (r * p.S + s2);
+        x_off[i] += (int)p.x_delta + cl * 16;
+      }
     } else {
       x_ih0[i] = -(1 << 28);
       x_iw0[i] = 0;
@@ -100,36 +148,85 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
   }
   const int8_t *w_row[WR];
   bool w_ok[WR];
+  int w_inc[WR];
 #pragma unroll
   for (int i = 0; i < WR; ++i) {
-    const int n = n0 + lrow + i * 64;
+    const int n = n0 + lrow + i * RPG;
     w_ok[i] = n < p.N;
     w_row[i] = p.w + (size_t)(w_ok[i] ? n : 0) * p.K + cl * 16;
+    w_inc[i] = BK;
+    if (UT && !w_ok[i]) { w_row[i] = reinterpret_cast<const int8_t *>(p.zero); w_inc[i] = 0; }
   }
-  const uint8_t *zero = g_zero_page;
+  const uint8_t *zero = p.zero;
 
-  auto issue_loads = [&](int kstep, int stage) {
-    const uint32_t u = (uint32_t)(kstep * 4 + cl);            // 16-byte unit index along K
-    const bool kvalid = (int)(u * 16) < p.K;
-    // A unit is 16 channels of one tap (C % 16 == 0) or 16 / C whole taps of one window
-    // row (C < 16, windows never clipped): either way 16 contiguous bytes starting at
-    // (r, s, c0), and only that first tap needs the bounds check.
-    const uint32_t tap = p.fd_c.div(u * 16);
-    const uint32_t c0 = u * 16 - tap * p.fd_c.d;
-    const uint32_t r = p.fd_s.div(tap);
-    const int s = (int)(tap - r * p.S);
-    const int toff = ((int)r * p.W + s) * p.C + (int)c0;
-    uint8_t *base = lds + stage * STAGE + wave * 1024;
+  // Loads of one K step, one LDS-direct load per call of issue_one so that the main loop can
+  // spread them between matrix instructions.  K-steps are issued strictly in order (the UT
+  // weight pointers advance by one step per call).
+  struct StepCtx {
+    uint8_t *base;     // this wave's 1 KiB slice of the stage
+    int kstep;
+    int toff;          // offset of the step's tap / channel slice inside a window
+    uint32_t tap;      // UT: tap index (scalar)
+    int r, s;          // per-thread tap coordinates (non-UT)
+    bool kvalid;
+  };
+  auto decode_step = [&](int kstep, int stage) {
+    StepCtx c;
+    c.base = lds + stage * STAGE + wave * 1024;
+    c.kstep = kstep;
+    if (UT) {
+      // scalar: which tap and which BK-channel slice this K step is
+      const FastDiv &fd_cpt = BK == 64 ? p.fd_cpt : p.fd_cpt2;
+      c.tap = fd_cpt.div((uint32_t)kstep);
+      const uint32_t cs = (uint32_t)kstep - c.tap * fd_cpt.d;
+      const uint32_t r = p.fd_s.div(c.tap);
+      const uint32_t s2 = c.tap - r * p.S;
+      c.toff = ((int)r * p.W + (int)s2) * p.C + (int)cs * BK;
+      c.r = c.s = 0;
+      c.kvalid = true;
+    } else {
+      // A unit is 16 channels of one tap (C % 16 == 0) or 16 / C whole taps of one window
+      // row (C < 16, windows never clipped): either way 16 contiguous bytes starting at
+      // (r, s, c0), and only that first tap needs the bounds check.
+      const uint32_t u = (uint32_t)(kstep * CH + cl);            // 16-byte unit index along K
+      c.kvalid = (int)(u * 16) < p.K;
+      c.tap = p.fd_c.div(u * 16);
+      const uint32_t c0 = u * 16 - c.tap * p.fd_c.d;
+      const uint32_t r = p.fd_s.div(c.tap);
+      c.r = (int)r;
+      c.s = (int)(c.tap - r * p.S);
+      c.toff = (c.r * p.W + c.s) * p.C + (int)c0;
+    }
+    return c;
+  };
+  auto issue_one = [&](const StepCtx &c, int j) {
 #pragma unroll
     for (int i = 0; i < XR; ++i) {
-      const bool ok = kvalid && (unsigned)(x_ih0[i] + (int)r) < (unsigned)p.H &&
-                      (unsigned)(x_iw0[i] + s) < (unsigned)p.W;
-      lds_direct_16(ok, p.x + (x_off[i] + toff), zero, base + i * 4096);
+      if (i != j) continue;
+      if (UT) {
+        const bool ok = (x_mask[i] >> c.tap) & 1u;
+        uint32_t off = ok ? (uint32_t)(x_off[i] + c.toff) : p.z_delta;
+        asm volatile("" : "+v"(off));
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(p.lo_base + (size_t)off),
+            (__attribute__((address_space(3))) void *)(c.base + i * 4096), 16, 0, 0);
+      } else {
+        const bool ok = c.kvalid && (unsigned)(x_ih0[i] + c.r) < (unsigned)p.H &&
+                        (unsigned)(x_iw0[i] + c.s) < (unsigned)p.W;
+        lds_direct_16(ok, p.x + (x_off[i] + c.toff), zero, c.base + i * 4096);
+      }
     }
 #pragma unroll
     for (int i = 0; i < WR; ++i) {
-      const bool ok = kvalid && w_ok[i];
-      lds_direct_16(ok, w_row[i] + kstep * 64, zero, base + BM * 64 + i * 4096);
+      if (i + XR != j) continue;
+      if (UT) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)w_row[i],
+                                         (__attribute__((address_space(3))) void *)(c.base + BM * BK + i * 4096),
+                                         16, 0, 0);
+        w_row[i] += w_inc[i];
+      } else {
+        lds_direct_16(c.kvalid && w_ok[i], w_row[i] + c.kstep * BK, zero, c.base + BM * BK + i * 4096);
+      }
     }
   };
 
@@ -148,78 +245,102 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
     }
   }
 
-  // fragment read offsets inside a stage: row l32 of a 32-row block, chunk (2 ks + half)
-  const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t *)lds);   // byte offset of the dynamic segment inside LDS
-  const int swz = (l32 >> 2) & 3;
-  const uint32_t foff0 = (uint32_t)(l32 * 64 + ((half ^ swz) * 16));
-  const uint32_t foff1 = (uint32_t)(l32 * 64 + (((2 + half) ^ swz) * 16));
+  // fragment read offsets inside a stage: row l32 of a 32-row block, chunk 2 ks + half
+  const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t *)lds);
+  uint32_t foff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    foff[ks] = (uint32_t)(l32 * BK + (((2 * ks + half) ^ row_swizzle<BK>(l32)) * 16));
   const int xmask = (int)p.xor_mask;
 
-  const int ksteps = (p.K + 63) >> 6;
+  const int ksteps = (p.K + BK - 1) / BK;
+  constexpr int NMF = NB * MB;                    // matrix instructions per 32 bytes of K
+  constexpr int LPM = (LPS + NMF - 1) / NMF;      // loads issued after each of them
   __builtin_amdgcn_sched_barrier(0);   // acc0 is read before the first operand loads are queued
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < ksteps) issue_loads(s, s);
+  for (int s = 0; s < NSTAGE; ++s) {
+    if (s < ksteps) {
+      const StepCtx c = decode_step(s, s);
+#pragma unroll
+      for (int j = 0; j < LPS; ++j) issue_one(c, j);
+    }
+  }
+  auto read_frags = [&](int stage, int ks, v4i (&fa)[NB], v4i (&fb)[MB]) {
+    const uint32_t xs = lds_base + (uint32_t)(stage * STAGE + wm0 * BK);
+    const uint32_t ws = lds_base + (uint32_t)(stage * STAGE + BM * BK + wn0 * BK);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) fa[nb] = lds_read_frag(ws + foff[ks], nb * BLK);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) fb[mb] = lds_read_frag(xs + foff[ks], mb * BLK);
+  };
+  // fragments are usable once the LDS counter has drained; the xor makes activations signed
+  auto land_frags = [&](v4i (&fa)[NB], v4i (&fb)[MB]) {
+    wait_lgkm<0>();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(fa[nb]));
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      asm volatile("" : "+v"(fb[mb]));
+      fb[mb].x ^= xmask; fb[mb].y ^= xmask; fb[mb].z ^= xmask; fb[mb].w ^= xmask;
+    }
+  };
 
+  // The loop is software-pipelined at the granularity of one matrix instruction along K
+  // (a slice of 32 bytes): while the instructions of one slice run, the fragments of the
+  // next slice are read from LDS into the other of two fragment sets, and at the last
+  // slice of a K step the step's stage, which no wave reads any more once the barrier is
+  // passed, is refilled with the loads of K step t + NSTAGE, spread between the matrix
+  // instructions.  Three instances of the step body: with refill, without, and the last
+  // step (nothing follows).
+  wait_ahead<NSTAGE - 1, LPS>(min(NSTAGE - 1, ksteps - 1));
+  __syncthreads();
+  v4i fa[2][NB], fb[2][MB];
+  read_frags(0, 0, fa[0], fb[0]);
+  land_frags(fa[0], fb[0]);
   int stage = 0;
-  for (int t = 0; t < ksteps; ++t) {
-    // loads of K-steps t+1 .. t+NSTAGE-2 may stay in flight; K-step t must have landed
-    const int ahead = min(NSTAGE - 2, ksteps - 1 - t);
-    if (NSTAGE >= 4 && ahead >= 2) wait_vm<2 * LPS>();
-    else if (NSTAGE >= 3 && ahead >= 1) wait_vm<LPS>();
-    else wait_vm<0>();
-    __syncthreads();
-    {
-      const int tn = t + NSTAGE - 1;
-      int sn = stage + NSTAGE - 1;
-      if (sn >= NSTAGE) sn -= NSTAGE;
-      if (tn < ksteps) issue_loads(tn, sn);
+  auto kstep_body = [&](int t, auto refill_tag, auto next_tag) {
+    constexpr bool REFILL = decltype(refill_tag)::value;
+    constexpr bool NEXT = decltype(next_tag)::value;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      constexpr int DUMMY = 0;
+      (void)DUMMY;
+      const int cur = ks & 1, nxt = cur ^ 1;
+      const bool last_slice = ks == KS - 1;
+      StepCtx c{};
+      bool reads = true;
+      if (!last_slice) {
+        read_frags(stage, ks + 1, fa[nxt], fb[nxt]);
+      } else if (NEXT) {
+        // K step t+1 must have landed; steps t+2 .. t+NSTAGE-1 may stay in flight
+        wait_ahead<NSTAGE - 2, LPS>(min(NSTAGE - 2, ksteps - 2 - t));
+        __syncthreads();
+        read_frags(stage + 1 == NSTAGE ? 0 : stage + 1, 0, fa[nxt], fb[nxt]);
+        if (REFILL) c = decode_step(t + NSTAGE, stage);
+      } else {
+        reads = false;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < NMF; ++q) {
+        const int nb = q / MB, mb = q % MB;
+        if (q == NMF - 1 && reads) land_frags(fa[nxt], fb[nxt]);
+        acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (last_slice && REFILL) {
+#pragma unroll
+          for (int j = q * LPM; j < (q + 1) * LPM && j < LPS; ++j) issue_one(c, j);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
-    const uint32_t xs = lds_base + (uint32_t)(stage * STAGE + wm0 * 64);
-    const uint32_t ws = lds_base + (uint32_t)(stage * STAGE + BM * 64 + wn0 * 64);
-    v4i a0[NB], b0[MB], a1[NB], b1[MB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) a0[nb] = lds_read_frag(ws + foff0, nb * 2048);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) b0[mb] = lds_read_frag(xs + foff0, mb * 2048);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) a1[nb] = lds_read_frag(ws + foff1, nb * 2048);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) b1[mb] = lds_read_frag(xs + foff1, mb * 2048);
-    // first half of the K step: wait for its NB + MB fragments only
-    if (NB == 2 && MB == 4) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(a0[0]), "+v"(a0[1]), "+v"(b0[0]), "+v"(b0[1]), "+v"(b0[MB > 2 ? 2 : 0]), "+v"(b0[MB > 3 ? 3 : 0]));
-    else if (NB == 2 && MB == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(a0[0]), "+v"(a0[1]), "+v"(b0[0]), "+v"(b0[1]));
-    else {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(a0[nb]));
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(b0[mb]));
-    }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) { b0[mb].x ^= xmask; b0[mb].y ^= xmask; b0[mb].z ^= xmask; b0[mb].w ^= xmask; }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-        acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[nb], b0[mb], acc[nb][mb], 0, 0, 0);
-    if (NB == 2 && MB == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a1[0]), "+v"(a1[1]), "+v"(b1[0]), "+v"(b1[1]), "+v"(b1[MB > 2 ? 2 : 0]), "+v"(b1[MB > 3 ? 3 : 0]));
-    else if (NB == 2 && MB == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a1[0]), "+v"(a1[1]), "+v"(b1[0]), "+v"(b1[1]));
-    else {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(a1[nb]));
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(b1[mb]));
-    }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) { b1[mb].x ^= xmask; b1[mb].y ^= xmask; b1[mb].z ^= xmask; b1[mb].w ^= xmask; }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-        acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[nb], b1[mb], acc[nb][mb], 0, 0, 0);
     if (++stage == NSTAGE) stage = 0;
+  };
+  {
+    int t = 0;
+    for (; t + NSTAGE < ksteps; ++t) kstep_body(t, std::true_type{}, std::true_type{});
+    for (; t + 1 < ksteps; ++t) kstep_body(t, std::false_type{}, std::true_type{});
+    kstep_body(t, std::false_type{}, std::false_type{});
   }
   wait_vm<0>();
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
@@ -281,28 +402,46 @@ __global__ __launch_bounds__(NT, 2) void conv_fast_kernel(const ConvParams p, co
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE>
-int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>
+int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const long long ntiles = (long long)tiles_m * tiles_n;
   if (ntiles > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-  constexpr int stage_bytes = NSTAGE * (BM + BN) * 64;
+  constexpr int stage_bytes = NSTAGE * (BM + BN) * BK;
   constexpr int epi_bytes = BM * (BN + 16);
   constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
-  dim3 grid((unsigned)ntiles), block(NT);
-  hipError_t e;
-  if (ev == 16) {
-    auto k = conv_fast_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, 16>;
-    static bool once = false;   // raising the dynamic LDS limit is idempotent; racing callers set the same value
-    if (!once) { e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, smem); if (e != hipSuccess) return (int)e; once = true; }
-    hipLaunchKernelGGL(k, grid, block, smem, stream, p, tiles_n, (int)ntiles);
-  } else {
-    auto k = conv_fast_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, 4>;
-    static bool once = false;
-    if (!once) { e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, smem); if (e != hipSuccess) return (int)e; once = true; }
-    hipLaunchKernelGGL(k, grid, block, smem, stream, p, tiles_n, (int)ntiles);
+  auto k = conv_fast_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, EV, UT>;
+  static bool once = false;   // raising the dynamic LDS limit is idempotent; racing callers set the same value
+  if (!once) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return (int)e;
+    once = true;
   }
+  hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(NT), smem, stream, p, tiles_n, (int)ntiles);
   return (int)hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB>
+int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
+  const bool ut = p.C % BK == 0 && p.R * p.S <= 32 && p.near;
+  if (ut) {
+    if (ev == 16) return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 16, true>(p, stream);
+    return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 4, true>(p, stream);
+  }
+  if (ev == 16) return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 16, false>(p, stream);
+  return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 4, false>(p, stream);
+}
+
+constexpr int N_VARIANTS = 8;
+const char *const kVariantNames[N_VARIANTS] = {
+    "conv_fast<256x128,k64,s3>", "conv_fast<256x64,k64,s3>",  "conv_fast<128x128,k64,s2>",
+    "conv_fast<128x64,k64,s2>",  "conv_fast<128x128,k128,s2>", "conv_fast<256x128,k128,s2>",
+    "conv_fast<128x128,k128,s3>", "conv_fast<128x64,k128,s2>"};
+
+int forced_variant() {
+  static const int v = [] { const char *e = getenv("F8_CONV_VARIANT"); return e ? atoi(e) : -1; }();
+  return v;
 }
 
 }  // namespace
@@ -323,18 +462,32 @@ bool conv_fast_applicable(const ConvParams &p) {
   return true;
 }
 
-int conv_fast_variant(const ConvParams &p) { return p.N > 64 ? 0 : 1; }
-
-const char *conv_fast_variant_name(int v) {
-  static const char *names[] = {"conv_fast<256x128>", "conv_fast<256x64>"};
-  return v >= 0 && v < 2 ? names[v] : "?";
+int conv_fast_variant(const ConvParams &p) {
+  const int f = forced_variant();
+  if (f >= 0 && f < N_VARIANTS) return f;
+  // Measured on MI355X over the ResNet-50 layer shapes: short-K and narrow layers are bound
+  // by memory latency and want many small workgroups per CU; long-K layers want whole
+  // 128-byte lines per row.
+  if (p.N <= 64 || p.K <= 128) return 3;
+  if (p.K >= 2048 && (p.C & 127) == 0) return 4;
+  return 2;
 }
+
+const char *conv_fast_variant_name(int v) { return v >= 0 && v < N_VARIANTS ? kVariantNames[v] : "?"; }
 
 int launch_conv_fast(const ConvParams &p, hipStream_t stream) {
   const uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res);
   const int ev = ((p.N & 15) == 0 && (ybits & 15) == 0) ? 16 : 4;
-  if (conv_fast_variant(p) == 0) return launch_fast_tile<256, 128, 2, 2, 3>(p, ev, stream);
-  return launch_fast_tile<256, 64, 4, 1, 3>(p, ev, stream);
+  switch (conv_fast_variant(p)) {
+    case 0: return launch_fast_tile<256, 128, 2, 2, 64, 3, 2>(p, ev, stream);
+    case 1: return launch_fast_tile<256, 64, 4, 1, 64, 3, 2>(p, ev, stream);
+    case 2: return launch_fast_tile<128, 128, 2, 2, 64, 2, 3>(p, ev, stream);
+    case 3: return launch_fast_tile<128, 64, 2, 2, 64, 2, 4>(p, ev, stream);
+    case 4: return launch_fast_tile<128, 128, 2, 2, 128, 2, 2>(p, ev, stream);
+    case 5: return launch_fast_tile<256, 128, 2, 2, 128, 2, 1>(p, ev, stream);
+    case 6: return launch_fast_tile<128, 128, 2, 2, 128, 3, 1>(p, ev, stream);
+    default: return launch_fast_tile<128, 64, 2, 2, 128, 2, 3>(p, ev, stream);
+  }
 }
 
 }  // namespace f8

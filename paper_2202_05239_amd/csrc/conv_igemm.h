@@ -19,7 +19,15 @@ struct ConvParams {
   uint32_t xor_mask;        // 0x80808080 for unsigned activations, 0 for signed
   int shift, lo, hi;        // requantisation
   int y_type, res_type, res_d;
-  FastDiv fd_pq, fd_q, fd_c, fd_s;     // by P*Q, Q, C, S
+  int remap;                // 1: XCD-aware tile order
+  // 64 bytes of zeros in device memory that stand in for padding taps and rows outside the
+  // tensor (fast path).  If x and zero both lie within 4 GiB above lo_base, near = 1 and
+  // x_delta / z_delta are their offsets from it.
+  const uint8_t *zero;
+  const uint8_t *lo_base;
+  uint32_t x_delta, z_delta;
+  int near;
+  FastDiv fd_pq, fd_q, fd_c, fd_s, fd_cpt, fd_cpt2;   // by P*Q, Q, C, S, C / 64, C / 128
 };
 
 // Launches the implicit-GEMM kernel.  vec is the widest of 16, 4, 1 bytes that divides C

@@ -1,4 +1,5 @@
 // C-ABI entry points of the single-layer calls: validation on the host, then launches.
+#include <cstdlib>
 #include <mutex>
 #include <unordered_map>
 
@@ -56,9 +57,19 @@ static int widest_vec(int C, const void *a, const void *b) {
   return 1;
 }
 
-f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void *y, const void *res,
-                       const Geom &g, const f8_quant &q, hipStream_t stream) {
+f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
+                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream) {
   ConvParams p;
+  p.zero = static_cast<const uint8_t *>(zero);
+  {
+    const uintptr_t xa = reinterpret_cast<uintptr_t>(x), za = reinterpret_cast<uintptr_t>(zero);
+    const uintptr_t lo = xa < za ? xa : za;
+    const unsigned long long xbytes = (unsigned long long)g.B * g.H * g.W * g.Cin;
+    p.lo_base = reinterpret_cast<const uint8_t *>(lo);
+    p.x_delta = (uint32_t)(xa - lo);
+    p.z_delta = (uint32_t)(za - lo);
+    p.near = (xa - lo) + xbytes + 64 < 0x7fffffffULL && (za - lo) + 64 < 0x7fffffffULL;
+  }
   p.x = static_cast<const uint8_t *>(x);
   p.w = w;
   p.acc0 = acc0;
@@ -78,6 +89,9 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void
   p.fd_pq = FastDiv((uint32_t)(g.P * g.Q));
   p.fd_q = FastDiv((uint32_t)g.Q);
   p.fd_c = FastDiv((uint32_t)g.Cin);
+  p.fd_cpt = FastDiv((uint32_t)((g.Cin & 63) == 0 ? g.Cin / 64 : 1));
+  p.fd_cpt2 = FastDiv((uint32_t)((g.Cin & 127) == 0 ? g.Cin / 128 : 1));
+  { static const int rm = [] { const char *e = getenv("F8_XCD_REMAP"); return e ? atoi(e) : 1; }(); p.remap = rm != 0; }
   p.fd_s = FastDiv((uint32_t)g.S);
   if (p.M == 0 || p.N == 0) return F8_OK;
   if (conv_fast_applicable(p)) return launch_conv_fast(p, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
@@ -87,6 +101,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
+  p.near = 1;
   p.C = g.Cin; p.N = g.Cout; p.y_type = q.y_type; p.res_type = q.res_type;
   p.H = g.H; p.W = g.W; p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
   p.P = g.P; p.Q = g.Q;
@@ -166,6 +181,12 @@ int32_t *scratch_for(hipStream_t stream, size_t ints) {
       s.ptr = nullptr;
       return nullptr;
     }
+    // the first 64 ints stay zero for the life of the buffer (the kernels' page of zeros)
+    if (hipMemset(s.ptr, 0, 64 * sizeof(int32_t)) != hipSuccess) {
+      (void)hipFree(s.ptr);
+      s.ptr = nullptr;
+      return nullptr;
+    }
     s.ints = want;
   }
   return s.ptr;
@@ -192,11 +213,12 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
   if (q->res == y) return F8_ERR_UNSUPPORTED;
   if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t *acc0 = scratch_for(s, acc0_padded(Cout));
-  if (!acc0) return F8_ERR_DEVICE;
+  int32_t *scratch = scratch_for(s, 64 + acc0_padded(Cout));
+  if (!scratch) return F8_ERR_DEVICE;
+  int32_t *acc0 = scratch + 64;
   st = enqueue_fold(w, bias, acc0, g, *q, s);
   if (st != F8_OK) return st;
-  return enqueue_conv(x, w, acc0, y, q->res, g, *q, s);
+  return enqueue_conv(x, w, acc0, scratch, y, q->res, g, *q, s);
 }
 
 f8_status f8_gemm_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int M, int K, int N,

@@ -157,7 +157,7 @@ struct f8_chain {
             return F8_ERR_DEVICE;
           src = xp;
         }
-        return enqueue_conv(src, conv_weights(i, workspace), acc0, dst, res, conv_geom(i, batch), L.q, s);
+        return enqueue_conv(src, conv_weights(i, workspace), acc0, workspace, dst, res, conv_geom(i, batch), L.q, s);
       }
       case F8_OP_DWCONV: return enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s);
       case F8_OP_MAXPOOL: return enqueue_maxpool(src, dst, g, L.q.x_type, s);
@@ -184,6 +184,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   }
   if (st == F8_OK && max_id > 16 * n_layers + 16) st = F8_ERR_SHAPE;
   if (st != F8_OK) { delete c; return st; }
+  c->const_bytes = 256;                // the workspace starts with a block of zeros
   c->tensors.resize(max_id + 1);
   Tensor &t0 = c->tensors[0];
   t0.h = in_h; t0.w = in_w; t0.c = in_c; t0.type = in_type; t0.producer = -1; t0.external = true;
@@ -296,6 +297,7 @@ f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return F8_ERR_ALIGN;
   if (!c->planned) c->plan();
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemsetAsync(workspace, 0, 256, s) != hipSuccess) return F8_ERR_DEVICE;
   for (size_t i = 0; i < c->layers.size(); ++i) {
     const f8_layer_desc &L = c->layers[i];
     if (L.op != F8_OP_CONV) continue;

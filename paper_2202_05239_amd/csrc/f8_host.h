@@ -37,9 +37,10 @@ f8_status check_geom(Geom &g, bool depthwise);
 // Pointer alignment the int32 operands need.
 f8_status check_align(const int32_t *bias, const void *y, const f8_quant &q, const void *res);
 
-// Enqueue the dense layer with a ready acc0 vector (device, acc0_padded(Cout) ints).
-f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, void *y, const void *res,
-                       const Geom &g, const f8_quant &q, hipStream_t stream);
+// Enqueue the dense layer with a ready acc0 vector (device, acc0_padded(Cout) ints) and a
+// device pointer to at least 64 bytes of zeros.
+f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
+                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream);
 // Name of the kernel enqueue_conv launches for this layer (operands assumed 16-byte aligned).
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res);
 // Enqueue the fold of (w, bias, rounding addend, sign correction) into acc0.
