@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch the chain eagerly instead of replaying a HIP graph")
     ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -67,14 +68,26 @@ def main():
     chain = f8.Chain(net).prepare(B)
     out = torch.empty((B,) + chain.out_shape, dtype=chain.out_dtype, device="cuda")
 
+    # One step = one replay of the captured chain (all layers, nothing skipped); the eager
+    # result is kept to check that the replays reproduce it bit for bit.
+    chain.run(xt, out)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    step = chain.run
+    if not args.no_graph:
+        graph = chain.capture(xt, out)
+        step = lambda *_: graph.replay()
     for _ in range(args.warmup):
-        chain.run(xt, out)
+        step(xt, out)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        chain.run(xt, out)
+        step(xt, out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if not torch.equal(out, eager):
+        print("bench.py: graph replay differs from the eager run", file=sys.stderr)
+        sys.exit(4)
     ms_per_step = dt / args.steps * 1e3
     images_per_s = B / (dt / args.steps)
 

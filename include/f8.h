@@ -94,7 +94,7 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
 
 /* Eq. 6 for a depthwise convolution (MobileNet V1/V2 layers of Sec. 5): K = R*S taps
  * per channel, no sum across channels.  x NHWC [B][H][W][C], w [R][S][C] int8,
- * bias [C] or NULL, y NHWC [B][P][Q][C].  R*S <= 49. */
+ * bias [C] or NULL, y NHWC [B][P][Q][C]. */
 f8_status f8_dwconv_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y,
                           int B, int H, int W, int C, int R, int S,
                           int stride_h, int stride_w, int pad_h, int pad_w,
@@ -186,6 +186,11 @@ const char *f8_status_str(f8_status s);
 /* Frees the per-stream scratch buffers of the single-layer calls (after the caller has
  * synchronised the streams that used them). */
 void f8_release_scratch(void);
+/* Measurement aid: plain streaming copy of `bytes` bytes (a multiple of 16; both device
+ * pointers 16-byte aligned; the ranges must not overlap), 16 bytes per lane.  It is the
+ * yardstick for what HBM delivers to a kernel that reads and writes every byte once, and the
+ * known-size reference against which the memory-traffic counters are scaled. */
+f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream);
 /* Library version, for the binding to check that it loaded what it was built against. */
 int f8_abi_version(void);
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "f8_chain_create", "f8_chain_workspace_bytes", "f8_chain_prepare", "f8_chain_run",
     "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
-    "f8_clip_from_alpha", "f8_status_str", "f8_release_scratch", "f8_abi_version",
+    "f8_clip_from_alpha", "f8_status_str", "f8_release_scratch", "f8_abi_version", "f8_copy_bytes",
 ]
 
 
@@ -87,6 +87,7 @@ def lib():
     L.f8_clip_from_alpha.restype = ctypes.c_int32
     L.f8_status_str.argtypes = [i32]
     L.f8_status_str.restype = ctypes.c_char_p
+    L.f8_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.f8_release_scratch.restype = None
     L.f8_abi_version.restype = ctypes.c_int
     if L.f8_abi_version() != 1:
@@ -173,6 +174,13 @@ def f8_clip_from_alpha(alpha, fl_y, is_signed=False):
     return int(lib().f8_clip_from_alpha(float(alpha), int(fl_y), int(bool(is_signed))))
 
 
+def f8_copy_bytes(src, dst):
+    """Plain streaming copy of src into dst (same byte size, a multiple of 16)."""
+    n = src.numel() * src.element_size()
+    _check(lib().f8_copy_bytes(_ptr(src), _ptr(dst), n, _stream()), "f8_copy_bytes")
+    return dst
+
+
 def out_hw(H, W, R, S, stride, pad):
     P = 0 if H + 2 * pad[0] - R < 0 else (H + 2 * pad[0] - R) // stride[0] + 1
     Q = 0 if W + 2 * pad[1] - S < 0 else (W + 2 * pad[1] - S) // stride[1] + 1
@@ -239,6 +247,18 @@ class Chain:
         _check(lib().f8_chain_run(self.handle, _ptr(x), _ptr(out), _ptr(self.workspace), B, _stream()),
                "f8_chain_run")
         return out
+
+    def capture(self, x, out):
+        """Record one run of the chain on (x, out) into a HIP graph and return it (a
+        torch.cuda.CUDAGraph; call .replay()).  The chain only launches kernels, so the capture
+        holds nothing else; run the chain once before capturing so that one-time set-up calls
+        (kernel attributes) are not part of the capture."""
+        self.run(x, out)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.run(x, out)
+        return g
 
     def tensor(self, tid):
         """Copy of intermediate tensor `tid` after a run (None if its memory was reused)."""

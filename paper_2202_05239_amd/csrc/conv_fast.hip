@@ -134,10 +134,14 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
       x_iw0[i] = (int)qq * p.sw - p.pw;
       x_off[i] = ((int)b * p.H + x_ih0[i]) * p.W * p.C + x_iw0[i] * p.C;
       if (UT) {
-        for (int r = 0; r < p.R; ++r)
-          for (int s2 = 0; s2 < p.S; ++s2)
-            if ((unsigned)(x_ih0[i] + r) < (unsigned)p.H && (unsigned)(x_iw0[i] + s2) < (unsigned)p.W)
-              x_mask[i] |= 1u << (r * p.S + s2);
+        if (p.R * p.S == 1 && p.ph == 0 && p.pw == 0) {
+          x_mask[i] = 1u;                          // 1x1, unpadded: the only tap is always inside
+        } else {
+          for (int r = 0; r < p.R; ++r)
+            for (int s2 = 0; s2 < p.S; ++s2)
+              if ((unsigned)(x_ih0[i] + r) < (unsigned)p.H && (unsigned)(x_iw0[i] + s2) < (unsigned)p.W)
+                x_mask[i] |= 1u << (r * p.S + s2);
+        }
         x_off[i] += (int)p.x_delta + cl * 16;
       }
     } else {
@@ -245,6 +249,24 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
     }
   }
 
+  // Residual tile: small tiles fetch it into registers now (16 bytes per thread and piece),
+  // so that its latency overlaps the K loop instead of following it.
+  constexpr int CPR = BN / EV;                    // EV-byte pieces per tile row
+  constexpr int RCH = BM * CPR / NT;              // pieces per thread
+  constexpr bool RES_PREFETCH = EV == 16 && RCH <= 4 && (BM * CPR) % NT == 0;
+  v4i res_pre[RES_PREFETCH ? RCH : 1];
+  if (RES_PREFETCH && p.res) {
+    const uint8_t *res = static_cast<const uint8_t *>(p.res);
+#pragma unroll
+    for (int i = 0; i < RCH; ++i) {
+      const int idx = tid + i * NT;
+      const int row = idx / CPR, pc = idx - row * CPR;
+      const int m = m0 + row, n = n0 + pc * 16;
+      res_pre[i] = v4i{0, 0, 0, 0};
+      if (m < p.M && n < p.N) res_pre[i] = *reinterpret_cast<const v4i *>(res + (size_t)m * p.N + n);
+    }
+  }
+
   // fragment read offsets inside a stage: row l32 of a 32-row block, chunk 2 ks + half
   const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t *)lds);
   uint32_t foff[KS];
@@ -348,44 +370,77 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[nb][mb][4g+j] is channel n0+wn0+nb*32+8g+4*half+j of pixel m0+wm0+mb*32+l32.
   uint8_t *epi = lds;
-  constexpr int CPR = BN / EV;                    // EV-byte pieces per tile row
   if (p.res) {
-    const uint8_t *res = static_cast<const uint8_t *>(p.res);
-    for (int idx = tid; idx < BM * CPR; idx += NT) {
-      const int row = idx / CPR, pc = idx - row * CPR;
-      const int m = m0 + row, n = n0 + pc * EV;
-      if (m < p.M && n < p.N) {
-        if (EV == 16) *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) =
-            *reinterpret_cast<const v4i *>(res + (size_t)m * p.N + n);
-        else *reinterpret_cast<uint32_t *>(epi + row * PITCH + pc * 4) =
-            *reinterpret_cast<const uint32_t *>(res + (size_t)m * p.N + n);
+    if (RES_PREFETCH) {
+#pragma unroll
+      for (int i = 0; i < RCH; ++i) {
+        const int idx = tid + i * NT;
+        const int row = idx / CPR, pc = idx - row * CPR;
+        *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) = res_pre[i];
+      }
+    } else {
+      const uint8_t *res = static_cast<const uint8_t *>(p.res);
+      for (int idx = tid; idx < BM * CPR; idx += NT) {
+        const int row = idx / CPR, pc = idx - row * CPR;
+        const int m = m0 + row, n = n0 + pc * EV;
+        if (m < p.M && n < p.N) {
+          if (EV == 16) *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) =
+              *reinterpret_cast<const v4i *>(res + (size_t)m * p.N + n);
+          else *reinterpret_cast<uint32_t *>(epi + row * PITCH + pc * 4) =
+              *reinterpret_cast<const uint32_t *>(res + (size_t)m * p.N + n);
+        }
       }
     }
     __syncthreads();
   }
-  const bool rsigned = p.res_type == T_S8;
+  // One instance of the per-lane work for each (residual kind, shift direction); the choice
+  // is uniform, so it is a scalar branch and the inner code carries no selects.
+  //   RK: 0 none, 1 unsigned residual, 2 signed residual.  RD: residual shifted left (d >= 0)
+  //   or rounded right.  NEG: output scaled up (shift < 0).
+  auto finish_tile = [&](auto rk_tag, auto rd_tag, auto neg_tag) {
+    constexpr int RK = decltype(rk_tag)::value;
+    constexpr bool RLEFT = decltype(rd_tag)::value;
+    constexpr bool NEG = decltype(neg_tag)::value;
+    const int d = p.res_d, sh = p.shift, lo = p.lo, hi = p.hi;
+    const int rhalf = RLEFT ? 0 : (1 << (-d - 1));
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
+      for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint8_t *slot = epi + (wm0 + mb * 32 + l32) * PITCH + wn0 + nb * 32 + g * 8 + half * 4;
-        int v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
-        if (p.res) {
-          const uint32_t rv = *reinterpret_cast<const uint32_t *>(slot);
+        for (int g = 0; g < 4; ++g) {
+          uint8_t *slot = epi + (wm0 + mb * 32 + l32) * PITCH + wn0 + nb * 32 + g * 8 + half * 4;
+          int v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
+          if (RK != 0) {
+            const uint32_t rv = *reinterpret_cast<const uint32_t *>(slot);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] += align_res(byte_of(rv, j, rsigned), p.res_d);
+            for (int j = 0; j < 4; ++j) {
+              const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe((int)rv, 8 * j, 8)
+                                    : (int)__builtin_amdgcn_ubfe(rv, 8 * j, 8);
+              v[j] += RLEFT ? (r << d) : ((r + rhalf) >> (-d));
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = requant<NEG>(v[j], sh, lo, hi);
+          *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
         }
-        if (p.shift >= 0) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = requant<false>(v[j], p.shift, p.lo, p.hi);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = requant<true>(v[j], p.shift, p.lo, p.hi);
-        }
-        *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
       }
+    }
+  };
+  {
+    using std::integral_constant;
+    using std::true_type;
+    using std::false_type;
+    const int rk = !p.res ? 0 : (p.res_type == T_S8 ? 2 : 1);
+    const bool left = p.res_d >= 0, neg = p.shift < 0;
+    if (neg) {            // rare: outputs finer than the accumulator; one generic instance per residual kind
+      if (rk == 0) finish_tile(integral_constant<int, 0>{}, true_type{}, true_type{});
+      else if (rk == 1) { if (left) finish_tile(integral_constant<int, 1>{}, true_type{}, true_type{}); else finish_tile(integral_constant<int, 1>{}, false_type{}, true_type{}); }
+      else { if (left) finish_tile(integral_constant<int, 2>{}, true_type{}, true_type{}); else finish_tile(integral_constant<int, 2>{}, false_type{}, true_type{}); }
+    } else {
+      if (rk == 0) finish_tile(integral_constant<int, 0>{}, true_type{}, false_type{});
+      else if (rk == 1) { if (left) finish_tile(integral_constant<int, 1>{}, true_type{}, false_type{}); else finish_tile(integral_constant<int, 1>{}, false_type{}, false_type{}); }
+      else { if (left) finish_tile(integral_constant<int, 2>{}, true_type{}, false_type{}); else finish_tile(integral_constant<int, 2>{}, false_type{}, false_type{}); }
     }
   }
   __syncthreads();
@@ -433,11 +488,13 @@ int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
   return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 4, false>(p, stream);
 }
 
-constexpr int N_VARIANTS = 8;
+constexpr int N_VARIANTS = 14;
 const char *const kVariantNames[N_VARIANTS] = {
     "conv_fast<256x128,k64,s3>", "conv_fast<256x64,k64,s3>",  "conv_fast<128x128,k64,s2>",
     "conv_fast<128x64,k64,s2>",  "conv_fast<128x128,k128,s2>", "conv_fast<256x128,k128,s2>",
-    "conv_fast<128x128,k128,s3>", "conv_fast<128x64,k128,s2>"};
+    "conv_fast<128x128,k128,s3>", "conv_fast<128x64,k128,s2>", "conv_fast<128x64,k64,s1>",
+    "conv_fast<128x64,k128,s1>",  "conv_fast<128x128,k64,s1>", "conv_fast<128x256,k64,s2>",
+    "conv_fast<64x256,k64,s2>",   "conv_fast<128x256,k128,s2>"};
 
 int forced_variant() {
   static const int v = [] { const char *e = getenv("F8_CONV_VARIANT"); return e ? atoi(e) : -1; }();
@@ -486,7 +543,16 @@ int launch_conv_fast(const ConvParams &p, hipStream_t stream) {
     case 4: return launch_fast_tile<128, 128, 2, 2, 128, 2, 2>(p, ev, stream);
     case 5: return launch_fast_tile<256, 128, 2, 2, 128, 2, 1>(p, ev, stream);
     case 6: return launch_fast_tile<128, 128, 2, 2, 128, 3, 1>(p, ev, stream);
-    default: return launch_fast_tile<128, 64, 2, 2, 128, 2, 3>(p, ev, stream);
+    case 7: return launch_fast_tile<128, 64, 2, 2, 128, 2, 3>(p, ev, stream);
+    // single-stage variants: the whole K fits one step, more workgroups per CU
+    case 8: return p.K <= 64 ? launch_fast_tile<128, 64, 2, 2, 64, 1, 6>(p, ev, stream) : -1;
+    case 9: return p.K <= 128 ? launch_fast_tile<128, 64, 2, 2, 128, 1, 5>(p, ev, stream) : -1;
+    case 10: return p.K <= 64 ? launch_fast_tile<128, 128, 2, 2, 64, 1, 4>(p, ev, stream) : -1;
+    // full-row variants: every output (and residual) row of up to 256 channels is one
+    // contiguous run, the activations are read once
+    case 11: return launch_fast_tile<128, 256, 2, 2, 64, 2, 2>(p, ev, stream);
+    case 12: return launch_fast_tile<64, 256, 2, 2, 64, 2, 3>(p, ev, stream);
+    default: return launch_fast_tile<128, 256, 2, 2, 128, 2, 2>(p, ev, stream);
   }
 }
 

@@ -30,6 +30,9 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream);
 int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream);
 int launch_gpool(const DwParams &p, bool vec4, hipStream_t stream);
 
+// Streaming copy of bytes / 16 * 16 bytes (both pointers 16-byte aligned).
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
+
 // Stem re-layout for convolutions with C <= 4 input channels: explicit zero border and
 // channels padded to 4 (input), window rows padded to Sp taps of 4 channels (weights).
 int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp, int Wp, int ph, int pw,

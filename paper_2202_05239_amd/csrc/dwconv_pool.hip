@@ -184,6 +184,15 @@ __global__ __launch_bounds__(NT) void repack_weights_kernel(const int8_t *w, uin
   wp[gid] = v;
 }
 
+// Plain streaming copy, 16 bytes per lane: the yardstick for what HBM delivers to a kernel
+// that reads and writes every byte once, and the known-size reference for the memory
+// traffic counters.
+__global__ __launch_bounds__(NT) void copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * NT + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * NT;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 inline unsigned blocks_for(long long total) { return (unsigned)((total + NT - 1) / NT); }
 
 }  // namespace
@@ -218,6 +227,16 @@ int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C,
   if (total <= 0) return 0;
   hipLaunchKernelGGL(repack_weights_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, w,
                      static_cast<uint32_t *>(wp), N, R, S, C, Sp, total);
+  return (int)hipGetLastError();
+}
+
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return 0;
+  const size_t want = (n16 + NT - 1) / NT;
+  const unsigned blocks = (unsigned)(want < 1024 ? want : 1024);     // 4 workgroups per CU, grid-stride
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(NT), 0, stream, static_cast<const v4i *>(src),
+                     static_cast<v4i *>(dst), n16);
   return (int)hipGetLastError();
 }
 

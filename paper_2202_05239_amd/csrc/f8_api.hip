@@ -105,6 +105,8 @@ const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   p.C = g.Cin; p.N = g.Cout; p.y_type = q.y_type; p.res_type = q.res_type;
   p.H = g.H; p.W = g.W; p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
   p.P = g.P; p.Q = g.Q;
+  p.M = (g.B > 0 ? g.B : 1) * g.P * g.Q;
+  p.K = g.R * g.S * g.Cin;
   if (conv_fast_applicable(p)) return conv_fast_variant_name(conv_fast_variant(p));
   return conv_variant_name(conv_variant(g.Cout));
 }
@@ -303,6 +305,12 @@ void f8_release_scratch(void) {
   for (auto &kv : g_scratch)
     if (kv.second.ptr) (void)hipFree(kv.second.ptr);
   g_scratch.clear();
+}
+
+f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream) {
+  if (!src || !dst) return F8_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst) | bytes) & 15) return F8_ERR_ALIGN;
+  return launch_copy(src, dst, bytes, static_cast<hipStream_t>(stream)) == 0 ? F8_OK : F8_ERR_DEVICE;
 }
 
 int f8_abi_version(void) { return 1; }
