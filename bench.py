@@ -33,6 +33,70 @@ def cpu_baseline(net, x, threads, images):
                       "host thread, %.1f s wall" % (images, x.shape[0], dt)}
 
 
+def layer_rows(f8, net, chain, layer_ms, B):
+    """Per-layer table: time, algorithmic ops and bytes, fractions of both rooflines."""
+    rows = []
+    for i, (L, ms) in enumerate(zip(net.layers, layer_ms)):
+        kname, ops, nbytes = chain.layer_info(i, B)
+        t = ms * 1e-3
+        tops, gbs = ops / t / 1e12, nbytes / t / 1e9
+        t_mfma, t_hbm = ops / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        rows.append({"layer": L.name, "kernel": kname, "us": ms * 1e3, "ops": ops, "bytes": nbytes, "TOPS": tops,
+                     "pct_mfma_peak": 100 * tops / PEAK_INT8_TOPS, "alg_GBs": gbs,
+                     "pct_hbm_peak": 100 * gbs / PEAK_HBM_GBS,
+                     "binds": "mfma" if (L.op == "conv" and t_mfma > t_hbm) else "hbm",
+                     "pct_of_roofline": 100 * max(t_mfma if L.op == "conv" else 0.0, t_hbm) / t})
+    return rows
+
+
+def single_layer_figures(torch, f8, wl, repeats):
+    """The two single-layer figures of the headline metric, timed with HIP events on the
+    launch stream through the same chain runner: the 3x3 dense layer of configs[1] (TOP/s
+    against the int8 matrix peak) and the depthwise layer of configs[2] (algorithmic GB/s
+    against the HBM peak), plus the streaming copy as the yardstick of what HBM gives."""
+    out = {}
+    x1, L1 = wl.config1()
+    net1 = wl.Net(name="config1", in_hw=L1.in_hw, in_c=L1.Cin, x_type=L1.x_type, fl_x=L1.fl_x, layers=[L1])
+    x2, net2 = wl.config2(with_residual=True)
+    for key, x, net in (("configs[1]", x1, net1), ("configs[2]", x2, net2)):
+        B = x.shape[0]
+        xt = torch.from_numpy(x).to("cuda")
+        chain = f8.Chain(net).prepare(B)
+        y = torch.empty((B,) + chain.out_shape, dtype=chain.out_dtype, device="cuda")
+        chain.run(xt, y)
+        ms = chain.profile(xt, y, repeats=repeats)
+        for r in layer_rows(f8, net, chain, ms, B):
+            out["%s %s" % (key, r["layer"])] = {k: r[k] for k in
+                                                ("kernel", "us", "TOPS", "pct_mfma_peak", "alg_GBs", "pct_hbm_peak", "binds")}
+        chain.close()
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    f8.f8_copy_bytes(a, b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        f8.f8_copy_bytes(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy 1 GiB"] = {"GBs_read_plus_write": 2.0 * n * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+    return out
+
+
+def copy_calibration():
+    """Three launches of the plain copy kernel over 1 GiB: the known-size reference for
+    the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    from paper_2202_05239_amd import binding as f8
+    n = 1 << 30
+    a = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        f8.f8_copy_bytes(a, b)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_per_launch": n}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,13 +107,19 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the chain eagerly instead of replaying a HIP graph")
     ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
+    ap.add_argument("--no-single-layer", action="store_true", help="skip the configs[1] / configs[2] layer figures")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run the plain copy kernel on 1 GiB (reference for the traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(the path shards by batch with no communication; see DESIGN.md)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
+    if args.copy_calibration:
+        copy_calibration()
+        return
+
     import torch
     from paper_2202_05239_amd import binding as f8
     from paper_2202_05239_amd import workloads as wl
@@ -93,19 +163,10 @@ def main():
 
     # Per-kernel device time of the same steps, HIP events on the launch stream.
     layer_ms = chain.profile(xt, out, repeats=max(1, args.steps))
-    rows, by_kernel = [], {}
-    for i, (L, ms) in enumerate(zip(net.layers, layer_ms)):
-        kname, ops, nbytes = chain.layer_info(i, B)
-        t = ms * 1e-3
-        tops, gbs = ops / t / 1e12, nbytes / t / 1e9
-        t_mfma, t_hbm = ops / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
-        rows.append({"layer": L.name, "kernel": kname, "us": ms * 1e3, "TOPS": tops,
-                     "pct_mfma_peak": 100 * tops / PEAK_INT8_TOPS, "alg_GBs": gbs,
-                     "pct_hbm_peak": 100 * gbs / PEAK_HBM_GBS,
-                     "binds": "mfma" if t_mfma > t_hbm else "hbm",
-                     "pct_of_roofline": 100 * max(t_mfma, t_hbm) / t})
-        k = by_kernel.setdefault(kname, {"ms": 0.0, "ops": 0.0, "bytes": 0.0, "launches": 0})
-        k["ms"] += ms; k["ops"] += ops; k["bytes"] += nbytes; k["launches"] += 1
+    rows, by_kernel = layer_rows(f8, net, chain, layer_ms, B), {}
+    for r in rows:
+        k = by_kernel.setdefault(r["kernel"], {"ms": 0.0, "ops": 0.0, "bytes": 0.0, "launches": 0})
+        k["ms"] += r["us"] * 1e-3; k["ops"] += r["ops"]; k["bytes"] += r["bytes"]; k["launches"] += 1
     dom = max(by_kernel, key=lambda n: by_kernel[n]["ms"])
     d = by_kernel[dom]
     t_m, t_h = d["ops"] / (PEAK_INT8_TOPS * 1e12), d["bytes"] / (PEAK_HBM_GBS * 1e9)
@@ -137,6 +198,8 @@ def main():
         "whole_net_TOPS": total_ops / (dt / args.steps) / 1e12,
         "roofline": roof,
     }
+    if not args.no_single_layer:
+        rec["single_layer"] = single_layer_figures(torch, f8, wl, repeats=50)
     if not args.no_cpu_baseline:
         threads = max(1, min(16, os.cpu_count() or 1, 8))
         rec["cpu_baseline"] = cpu_baseline(net, x, threads, threads)

@@ -166,9 +166,12 @@ void f8_chain_destroy(f8_chain *c);
  *   kernel_name, at most name_len bytes with the terminator) and the layer's algorithmic
  *   work for `batch` images: operations (2 per multiply-accumulate; 0 for pools) and
  *   bytes (every operand and result touched once).
- * f8_chain_profile: runs the chain `repeats` times like f8_chain_run with a HIP event
- *   recorded on `stream` before and after every layer, waits for the stream, and writes
- *   each layer's mean device time in milliseconds to layer_ms[f8_chain_num_layers]. */
+ * f8_chain_profile: runs the chain 2 * `repeats` times with a HIP event recorded on
+ *   `stream` before and after every layer, once with every layer launched once and once
+ *   with every layer launched five times back to back; the difference divided by four is
+ *   the duration of one launch in a busy stream (the cost of the event pair cancels).
+ *   Waits for the stream and writes each layer's mean launch duration in milliseconds to
+ *   layer_ms[f8_chain_num_layers].  The chain's output is the same as after f8_chain_run. */
 int f8_chain_num_layers(const f8_chain *c);
 f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *kernel_name,
                               int name_len, double *alg_ops, double *alg_bytes);

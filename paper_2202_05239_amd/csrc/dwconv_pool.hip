@@ -70,6 +70,163 @@ __global__ __launch_bounds__(NT) void dwconv_generic_kernel(const DwParams p, co
   else yp[0] = (uint8_t)acc[0];
 }
 
+// ---- 3x3 depthwise layer, stride 1 or 2 ------------------------------------------------
+// One thread owns 4 consecutive channels (one dword of NHWC) of a strip of TQ = 4 output
+// columns and walks down TP = 8 output rows, so every input row it loads serves up to three
+// output rows and the 3 x 3 x 4 weights are unpacked once.  The arithmetic runs on the packed
+// dot product (4 signed 8-bit products per lane-operation): each loaded row is transposed
+// with byte permutes from "4 channels of one pixel" to "4 neighbouring pixels of one
+// channel", so a window of one output is 3 of the 4 bytes of one dword (the fourth meets a
+// zero weight).  Unsigned activations are fed as x xor 0x80 with 128 * sum(w) added to the
+// start value, as in the dense kernels; padding is zero before the xor.
+struct DwTiling {
+  FastDiv fd_cg, fd_qs, fd_pc;
+  int CG, QS, PC;            // channel dwords, column strips, row chunks
+};
+
+constexpr int DW_TQ = 4, DW_TP = 8;
+
+__device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+  return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// (a, b, c, d) = 4 pixels x 4 channels  ->  t[ch] = bytes (a.ch, b.ch, c.ch, d.ch)
+__device__ __forceinline__ void transpose4(uint32_t a, uint32_t b, uint32_t c, uint32_t d, uint32_t t[4]) {
+  const uint32_t ab_lo = perm(b, a, 0x05010400u), ab_hi = perm(b, a, 0x07030602u);
+  const uint32_t cd_lo = perm(d, c, 0x05010400u), cd_hi = perm(d, c, 0x07030602u);
+  t[0] = perm(cd_lo, ab_lo, 0x05040100u);
+  t[1] = perm(cd_lo, ab_lo, 0x07060302u);
+  t[2] = perm(cd_hi, ab_hi, 0x05040100u);
+  t[3] = perm(cd_hi, ab_hi, 0x07060302u);
+}
+
+template <int STRIDE, bool XS>
+__global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl, const uint32_t total) {
+  constexpr int TQ = DW_TQ, TP = DW_TP;
+  constexpr int NCOL = (TQ - 1) * STRIDE + 3;
+  constexpr int NROW = (TP - 1) * STRIDE + 3;
+  const uint32_t gid = blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const uint32_t u1 = tl.fd_cg.div(gid);
+  const int cg = (int)(gid - u1 * (uint32_t)tl.CG);
+  const uint32_t u2 = tl.fd_qs.div(u1);
+  const int strip = (int)(u1 - u2 * (uint32_t)tl.QS);
+  const uint32_t b = tl.fd_pc.div(u2);
+  const int chunk = (int)(u2 - b * (uint32_t)tl.PC);
+  const int c = cg * 4;
+  const int q0 = strip * TQ, p0 = chunk * TP;
+  const int iw0 = q0 * STRIDE - p.pw, ih0 = p0 * STRIDE - p.ph;
+
+  // weights: wt[r][ch] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0)
+  uint32_t wt[3][4];
+  int acc0[4];
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[c + ch] : 0);
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    const uint32_t w0 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 0) * p.C + c);
+    const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + c);
+    const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + c);
+    const uint32_t lo = perm(w1, w0, 0x05010400u), hi = perm(w1, w0, 0x07030602u);
+    wt[r][0] = perm(w2, lo, 0x0c040100u);
+    wt[r][1] = perm(w2, lo, 0x0c050302u);
+    wt[r][2] = perm(w2, hi, 0x0c060100u);
+    wt[r][3] = perm(w2, hi, 0x0c070302u);
+    if (!XS) {
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch) acc0[ch] += 128 * __builtin_amdgcn_sdot4((int)wt[r][ch], 0x01010101, 0, false);
+    }
+  }
+
+  // which of this strip's input columns lie inside the image
+  uint32_t col_ok = 0;
+#pragma unroll
+  for (int j = 0; j < NCOL; ++j) col_ok |= ((unsigned)(iw0 + j) < (unsigned)p.W ? 1u : 0u) << j;
+  const long long row_bytes = (long long)p.W * p.C;
+  const uint8_t *xcol = p.x + ((long long)b * p.H * p.W + iw0) * p.C + c;     // column iw0 of row 0 of image b
+  uint8_t *ycol = static_cast<uint8_t *>(p.y) + ((size_t)b * p.P * p.Q + q0) * p.C + c;
+
+  uint32_t win[3][4][4];        // [input row mod 3][channel][output column]: the window dwords
+  // Loads are branch-free (an out-of-image tap reads the tensor's first dword and is then
+  // replaced by zero) and run PF input rows ahead of the arithmetic, so every wave keeps
+  // 2 * NCOL dwords per lane in flight.
+  constexpr int PF = 2;
+  uint32_t ring[PF + 1][NCOL];
+  auto load_row = [&](int i, uint32_t (&dst)[NCOL]) {
+    const int ih = ih0 + i;
+    const bool row_ok = (unsigned)ih < (unsigned)p.H;
+    const uint8_t *xrow = xcol + (long long)ih * row_bytes;
+#pragma unroll
+    for (int j = 0; j < NCOL; ++j) {
+      const bool ok = row_ok && ((col_ok >> j) & 1u);
+      const uint8_t *a = ok ? xrow + (long long)j * p.C : p.x;
+      const uint32_t v = *reinterpret_cast<const uint32_t *>(a);
+      dst[j] = ok ? v : 0u;
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < PF; ++i) load_row(i, ring[i]);
+#pragma unroll
+  for (int i = 0; i < NROW; ++i) {
+    if (i + PF < NROW) load_row(i + PF, ring[(i + PF) % (PF + 1)]);
+    uint32_t raw[NCOL];
+#pragma unroll
+    for (int j = 0; j < NCOL; ++j) raw[j] = XS ? ring[i % (PF + 1)][j] : (ring[i % (PF + 1)][j] ^ 0x80808080u);
+    uint32_t (&wn)[4][4] = win[i % 3];
+    uint32_t t[4], u[4];
+    transpose4(raw[0], raw[1], raw[2], raw[3], t);
+    if (STRIDE == 1) {
+      const uint32_t ef_lo = perm(raw[5], raw[4], 0x05010400u), ef_hi = perm(raw[5], raw[4], 0x07030602u);
+      u[0] = ef_lo; u[1] = ef_lo >> 16; u[2] = ef_hi; u[3] = ef_hi >> 16;
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch) {
+        wn[ch][0] = t[ch];
+        wn[ch][1] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 1);
+        wn[ch][2] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 2);
+        wn[ch][3] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 3);
+      }
+    } else {
+      transpose4(raw[4], raw[5], raw[6], raw[7], u);
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch) {
+        wn[ch][0] = t[ch];
+        wn[ch][1] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 2);
+        wn[ch][2] = u[ch];
+        wn[ch][3] = __builtin_amdgcn_alignbyte(raw[8] >> (8 * ch), u[ch], 2);
+      }
+    }
+    // the output row whose last input row this is
+    if (i >= 2 && (i - 2) % STRIDE == 0) {
+      const int pl = (i - 2) / STRIDE;
+      const int pp = p0 + pl;
+      int acc[4][4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch) acc[q][ch] = acc0[ch];
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            acc[q][ch] = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + r) % 3][ch][q], (int)wt[r][ch], acc[q][ch], false);
+      if (pp < p.P) {
+        uint8_t *yrow = ycol + (size_t)pp * p.Q * p.C;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (q0 + q < p.Q) {
+            int v[4];
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch) v[ch] = requant<false>(acc[q][ch], p.shift, p.lo, p.hi);
+            *reinterpret_cast<uint32_t *>(yrow + (size_t)q * p.C) = pack4(v[0], v[1], v[2], v[3]);
+          }
+        }
+      }
+    }
+  }
+}
+
 // Max pooling: one thread = CV consecutive channels of one output pixel; out-of-image
 // taps are skipped, so padding never wins.
 template <int CV>
@@ -109,6 +266,60 @@ __global__ __launch_bounds__(NT) void maxpool_kernel(const PoolParams p, const l
   else yp[0] = (uint8_t)best[0];
 }
 
+// Max pooling, 16 channels (one 16-byte vector) of one output pixel per thread, window size a
+// compile-time constant.  Loads are branch-free (an out-of-image tap reads the tensor's first
+// vector and is replaced by the smallest value).  The byte-wise maximum runs on the packed
+// 16-bit unsigned max, two bytes per operation; signed bytes are compared as x xor 0x80.
+struct PoolTiling {
+  FastDiv fd_cg, fd_q, fd_p;
+  int CG;
+};
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b)));
+}
+
+template <int R, int S>
+__global__ __launch_bounds__(NT) void maxpool_vec16_kernel(const PoolParams p, const PoolTiling tl, const uint32_t total) {
+  const uint32_t gid = blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const uint32_t pix = tl.fd_cg.div(gid);
+  const int c = (int)(gid - pix * (uint32_t)tl.CG) * 16;
+  const uint32_t t = tl.fd_q.div(pix);
+  const int q = (int)(pix - t * (uint32_t)p.Q);
+  const uint32_t b = tl.fd_p.div(t);
+  const int pp = (int)(t - b * (uint32_t)p.P);
+  const uint32_t flip = p.type == T_S8 ? 0x80808080u : 0u;
+  const int ih0 = pp * p.sh - p.ph, iw0 = q * p.sw - p.pw;
+  const uint8_t *img = p.x + (size_t)b * p.H * p.W * p.C + c;
+  v4i v[R * S];
+  bool ok[R * S];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const int ih = ih0 + r, iw = iw0 + s;
+      ok[r * S + s] = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+      const uint8_t *a = ok[r * S + s] ? img + ((long long)ih * p.W + iw) * p.C : p.x;
+      v[r * S + s] = *reinterpret_cast<const v4i *>(a);
+    }
+  uint32_t even[4] = {0, 0, 0, 0}, odd[4] = {0, 0, 0, 0};      // bytes 0,2 and bytes 1,3 of each dword
+#pragma unroll
+  for (int k = 0; k < R * S; ++k)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t d = ok[k] ? ((uint32_t)v[k][j] ^ flip) : 0u;
+      even[j] = pk_max_u16(even[j], d & 0x00ff00ffu);
+      odd[j] = pk_max_u16(odd[j], (d >> 8) & 0x00ff00ffu);
+    }
+  v4i o;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) o[j] = (int)((even[j] | (odd[j] << 8)) ^ flip);
+  *reinterpret_cast<v4i *>(p.y + (size_t)pix * p.C + c) = o;
+}
+
 // Global sum pool + requantisation: one thread = CV channels of one image.
 template <int CV>
 __global__ __launch_bounds__(NT) void gpool_kernel(const DwParams p, const long long total) {
@@ -123,7 +334,21 @@ __global__ __launch_bounds__(NT) void gpool_kernel(const DwParams p, const long 
 #pragma unroll
   for (int i = 0; i < CV; ++i) acc[i] = p.rnd;
   const uint8_t *xp = p.x + (size_t)b * p.H * p.W * p.C + c;
-  for (int i = 0; i < p.H * p.W; ++i) {
+  const int HW = p.H * p.W;
+  int i = 0;
+  if (CV == 4) {
+    // 8 independent loads in flight per lane
+    for (; i + 8 <= HW; i += 8) {
+      uint32_t xv[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) xv[k] = *reinterpret_cast<const uint32_t *>(xp + (size_t)(i + k) * p.C);
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] += byte_of(xv[k], j, xs);
+    }
+  }
+  for (; i < HW; ++i) {
     if (CV == 4) {
       const uint32_t xv = *reinterpret_cast<const uint32_t *>(xp + (size_t)i * p.C);
 #pragma unroll
@@ -197,9 +422,37 @@ inline unsigned blocks_for(long long total) { return (unsigned)((total + NT - 1)
 
 }  // namespace
 
+bool dwconv_fast_applicable(const DwParams &p, bool vec4) {
+  if (!vec4 || p.R != 3 || p.S != 3 || p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+  if (p.res || p.y_type == T_S32 || p.shift < 0) return false;
+  if (p.bias && (reinterpret_cast<uintptr_t>(p.bias) & 3)) return false;
+  const long long threads = (long long)p.B * ((p.P + DW_TP - 1) / DW_TP) * ((p.Q + DW_TQ - 1) / DW_TQ) * (p.C / 4);
+  return threads > 0 && threads < (1ll << 31);
+}
+
 int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
   const long long total = (long long)p.B * p.P * p.Q * (p.C / (vec4 ? 4 : 1));
   if (total <= 0) return 0;
+  if (dwconv_fast_applicable(p, vec4)) {
+    DwTiling tl;
+    tl.CG = p.C / 4;
+    tl.QS = (p.Q + DW_TQ - 1) / DW_TQ;
+    tl.PC = (p.P + DW_TP - 1) / DW_TP;
+    tl.fd_cg = FastDiv((uint32_t)tl.CG);
+    tl.fd_qs = FastDiv((uint32_t)tl.QS);
+    tl.fd_pc = FastDiv((uint32_t)tl.PC);
+    const uint32_t threads = (uint32_t)((long long)p.B * tl.PC * tl.QS * tl.CG);
+    const dim3 grid((threads + NT - 1) / NT), block(NT);
+    const bool xs = p.x_type == T_S8;
+    if (p.sh == 1) {
+      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<1, true>), grid, block, 0, stream, p, tl, threads);
+      else hipLaunchKernelGGL((dwconv3x3_kernel<1, false>), grid, block, 0, stream, p, tl, threads);
+    } else {
+      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<2, true>), grid, block, 0, stream, p, tl, threads);
+      else hipLaunchKernelGGL((dwconv3x3_kernel<2, false>), grid, block, 0, stream, p, tl, threads);
+    }
+    return (int)hipGetLastError();
+  }
   if (vec4) hipLaunchKernelGGL(dwconv_generic_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
   else hipLaunchKernelGGL(dwconv_generic_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
   return (int)hipGetLastError();
@@ -208,6 +461,20 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
 int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream) {
   const long long total = (long long)p.B * p.P * p.Q * (p.C / (vec4 ? 4 : 1));
   if (total <= 0) return 0;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.y) | (uintptr_t)p.C;
+  const bool win3 = p.R == 3 && p.S == 3, win2 = p.R == 2 && p.S == 2;
+  const long long threads = (long long)p.B * p.P * p.Q * (p.C / 16);
+  if ((bits & 15) == 0 && (win3 || win2) && threads < (1ll << 31)) {
+    PoolTiling tl;
+    tl.CG = p.C / 16;
+    tl.fd_cg = FastDiv((uint32_t)tl.CG);
+    tl.fd_q = FastDiv((uint32_t)p.Q);
+    tl.fd_p = FastDiv((uint32_t)p.P);
+    const dim3 grid((unsigned)((threads + NT - 1) / NT)), block(NT);
+    if (win3) hipLaunchKernelGGL((maxpool_vec16_kernel<3, 3>), grid, block, 0, stream, p, tl, (uint32_t)threads);
+    else hipLaunchKernelGGL((maxpool_vec16_kernel<2, 2>), grid, block, 0, stream, p, tl, (uint32_t)threads);
+    return (int)hipGetLastError();
+  }
   if (vec4) hipLaunchKernelGGL(maxpool_kernel<4>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
   else hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks_for(total)), dim3(NT), 0, stream, p, total);
   return (int)hipGetLastError();

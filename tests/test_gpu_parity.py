@@ -241,6 +241,12 @@ DW_CASES = [
     (1, 9, 11, 7, 3, 3, 1, 1, "u8", "u8", "u8"),           # channels not a multiple of 4
     (1, 8, 8, 24, 3, 3, 1, 0, "u8", "s32", None),
     (3, 7, 7, 576, 3, 3, 1, 1, "u8", "u8", None),
+    (2, 17, 13, 36, 3, 3, 2, 1, "s8", "u8", None),         # stride 2, ragged strips and row chunks
+    (1, 30, 9, 20, 3, 3, 1, 0, "s8", "s8", None),          # no padding, several row chunks
+    (2, 33, 10, 8, 3, 3, 2, 0, "u8", "s8", None),
+    (1, 3, 3, 4, 3, 3, 1, 1, "u8", "u8", None),            # image as small as the window
+    (1, 12, 12, 16, 3, 3, 1, 2, "u8", "u8", None),         # padding wider than the usual 1
+    (2, 14, 14, 64, 3, 3, 1, 1, "u8", "u8", "s8"),         # residual: generic kernel
 ]
 
 
@@ -258,8 +264,15 @@ def test_depthwise_sweep(oracle, case):
 def test_pools(oracle):
     rng = np.random.default_rng(80)
     for kind, shape, k, st, pd in (("u8", (2, 31, 29, 64), 3, 2, 1), ("s8", (1, 10, 10, 6), 2, 2, 0),
-                                   ("u8", (1, 7, 9, 5), 3, 1, 1)):
-        x = wl.draw_u8(rng, shape) if kind == "u8" else rng.integers(-128, 0, shape, dtype=np.int8)
+                                   ("u8", (1, 7, 9, 5), 3, 1, 1), ("s8", (2, 13, 17, 32), 3, 2, 1),
+                                   ("s8", (1, 8, 8, 16), 2, 2, 0), ("u8", (3, 6, 5, 48), 3, 1, 1),
+                                   ("s8", (1, 9, 9, 16), 3, 3, 0)):
+        if kind == "u8":
+            x = wl.draw_u8(rng, shape)
+        elif shape[3] == 6:
+            x = rng.integers(-128, 0, shape, dtype=np.int8)          # all negative: padding must never win
+        else:
+            x = rng.integers(-128, 128, shape, dtype=np.int8)
         want = oracle.maxpool(x, kind, (k, k), (st, st), (pd, pd))
         L = wl.LayerSpec(op="maxpool", Cin=shape[3], Cout=shape[3], R=k, S=k, stride=st, pad=pd,
                          x_type=kind, y_type=kind, out_hw=want.shape[1:3])
