@@ -32,7 +32,29 @@ namespace {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int NT = 256;
+
+// Optional timeline of every workgroup (built only with -DF8_TRACE, never in the product
+// library): 8 slots of the 100 MHz wall clock per workgroup, written by thread 0.
+#ifdef F8_TRACE
+#ifndef F8_EXP_BITS
+#define F8_EXP_BITS 0          // timing experiments (results invalid): 1 no refill loads, 2 no fragment reads, 4 no matrix ops, 8 no xor
+#endif
+#define F8_EXP(bit) ((F8_EXP_BITS) & (bit))
+__device__ unsigned long long *g_trace = nullptr;
+#define F8_TRACE_POINT(i)                                                                         \
+  do {                                                                                            \
+    if (threadIdx.x == 0 && g_trace) g_trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64();      \
+  } while (0)
+#define F8_TRACE_HWID()                                                                           \
+  do {                                                                                            \
+    if (threadIdx.x == 0 && g_trace)                                                              \
+      g_trace[(size_t)blockIdx.x * 8 + 7] = (unsigned long long)__builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)); \
+  } while (0)
+#else
+#define F8_EXP(bit) 0
+#define F8_TRACE_POINT(i) do {} while (0)
+#define F8_TRACE_HWID() do {} while (0)
+#endif
 
 // One LDS-direct load per call, whatever the predicate: the source address is selected as
 // data (the empty asm keeps the compiler from turning the select into two loads under
@@ -82,9 +104,10 @@ __device__ __forceinline__ int row_swizzle(int row) {
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>
-__global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p, const int tiles_n,
-                                                             const int ntiles) {
-  static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel(const ConvParams p, const int tiles_n,
+                                                                                 const int ntiles) {
+  static_assert(WAVES_M * WAVES_N == 4 || WAVES_M * WAVES_N == 8, "four or eight waves per workgroup");
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
   static_assert(BK == 64 || BK == 128, "K step of 64 or 128 bytes");
   constexpr int CH = BK / 16;                     // 16-byte chunks per row
   constexpr int RPG = NT / CH;                    // rows covered by one load of the whole workgroup
@@ -100,6 +123,8 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
   static_assert(NB + MB <= 15, "fragment reads of half a step must fit lgkmcnt");
 
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  F8_TRACE_POINT(0);
+  F8_TRACE_HWID();
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -134,13 +159,14 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
       x_iw0[i] = (int)qq * p.sw - p.pw;
       x_off[i] = ((int)b * p.H + x_ih0[i]) * p.W * p.C + x_iw0[i] * p.C;
       if (UT) {
-        if (p.R * p.S == 1 && p.ph == 0 && p.pw == 0) {
-          x_mask[i] = 1u;                          // 1x1, unpadded: the only tap is always inside
-        } else {
-          for (int r = 0; r < p.R; ++r)
-            for (int s2 = 0; s2 < p.S; ++s2)
-              if ((unsigned)(x_ih0[i] + r) < (unsigned)p.H && (unsigned)(x_iw0[i] + s2) < (unsigned)p.W)
-                x_mask[i] |= 1u << (r * p.S + s2);
+        // Taps inside the image form a rectangle [r_lo, r_hi) x [s_lo, s_hi) of the window; its
+        // bit mask is (column bits) * (one bit per valid row at multiples of S): no carries.
+        const int r_lo = max(0, -x_ih0[i]), r_hi = min(p.R, p.H - x_ih0[i]);
+        const int s_lo = max(0, -x_iw0[i]), s_hi = min(p.S, p.W - x_iw0[i]);
+        if (r_hi > r_lo && s_hi > s_lo) {
+          const uint32_t cols = (s_hi >= 32 ? 0u : (1u << s_hi)) - (1u << s_lo);
+          const uint32_t top = r_hi * p.S >= 32 ? 0u : (1u << (r_hi * p.S));
+          x_mask[i] = cols * ((top - (1u << (r_lo * p.S))) & p.tap_rep);
         }
         x_off[i] += (int)p.x_delta + cl * 16;
       }
@@ -213,11 +239,11 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
         asm volatile("" : "+v"(off));
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void *)(p.lo_base + (size_t)off),
-            (__attribute__((address_space(3))) void *)(c.base + i * 4096), 16, 0, 0);
+            (__attribute__((address_space(3))) void *)(c.base + i * (NT * 16)), 16, 0, 0);
       } else {
         const bool ok = c.kvalid && (unsigned)(x_ih0[i] + c.r) < (unsigned)p.H &&
                         (unsigned)(x_iw0[i] + c.s) < (unsigned)p.W;
-        lds_direct_16(ok, p.x + (x_off[i] + c.toff), zero, c.base + i * 4096);
+        lds_direct_16(ok, p.x + (x_off[i] + c.toff), zero, c.base + i * (NT * 16));
       }
     }
 #pragma unroll
@@ -225,14 +251,37 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
       if (i + XR != j) continue;
       if (UT) {
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)w_row[i],
-                                         (__attribute__((address_space(3))) void *)(c.base + BM * BK + i * 4096),
+                                         (__attribute__((address_space(3))) void *)(c.base + BM * BK + i * (NT * 16)),
                                          16, 0, 0);
         w_row[i] += w_inc[i];
       } else {
-        lds_direct_16(c.kvalid && w_ok[i], w_row[i] + c.kstep * BK, zero, c.base + BM * BK + i * 4096);
+        lds_direct_16(c.kvalid && w_ok[i], w_row[i] + c.kstep * BK, zero, c.base + BM * BK + i * (NT * 16));
       }
     }
   };
+
+  // fragment read offsets inside a stage: row l32 of a 32-row block, chunk 2 ks + half
+  const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t *)lds);
+  uint32_t foff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    foff[ks] = (uint32_t)(l32 * BK + (((2 * ks + half) ^ row_swizzle<BK>(l32)) * 16));
+  const int xmask = (int)p.xor_mask;
+
+  const int ksteps = (p.K + BK - 1) / BK;
+  constexpr int NMF = NB * MB;                    // matrix instructions per 32 bytes of K
+  constexpr int LPM = (LPS + NMF - 1) / NMF;      // loads issued after each of them
+  // The first K step's operand loads are queued before anything else is fetched; the
+  // accumulator start values and the residual tile follow them in the queue (loads return in
+  // order, so waiting for a later stage also covers these), then the remaining stages.
+  __builtin_amdgcn_sched_barrier(0);
+  F8_TRACE_POINT(1);
+  {
+    const StepCtx c = decode_step(0, 0);
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) issue_one(c, j);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- accumulators start at acc0[n] -----------------------------------------------------
   v16i acc[NB][MB];
@@ -267,20 +316,9 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
     }
   }
 
-  // fragment read offsets inside a stage: row l32 of a 32-row block, chunk 2 ks + half
-  const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t *)lds);
-  uint32_t foff[KS];
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-    foff[ks] = (uint32_t)(l32 * BK + (((2 * ks + half) ^ row_swizzle<BK>(l32)) * 16));
-  const int xmask = (int)p.xor_mask;
-
-  const int ksteps = (p.K + BK - 1) / BK;
-  constexpr int NMF = NB * MB;                    // matrix instructions per 32 bytes of K
-  constexpr int LPM = (LPS + NMF - 1) / NMF;      // loads issued after each of them
-  __builtin_amdgcn_sched_barrier(0);   // acc0 is read before the first operand loads are queued
-#pragma unroll
-  for (int s = 0; s < NSTAGE; ++s) {
+  for (int s = 1; s < NSTAGE; ++s) {
     if (s < ksteps) {
       const StepCtx c = decode_step(s, s);
 #pragma unroll
@@ -288,6 +326,7 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
     }
   }
   auto read_frags = [&](int stage, int ks, v4i (&fa)[NB], v4i (&fb)[MB]) {
+    if (F8_EXP(2)) return;
     const uint32_t xs = lds_base + (uint32_t)(stage * STAGE + wm0 * BK);
     const uint32_t ws = lds_base + (uint32_t)(stage * STAGE + BM * BK + wn0 * BK);
 #pragma unroll
@@ -303,7 +342,7 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       asm volatile("" : "+v"(fb[mb]));
-      fb[mb].x ^= xmask; fb[mb].y ^= xmask; fb[mb].z ^= xmask; fb[mb].w ^= xmask;
+      if (!F8_EXP(8)) { fb[mb].x ^= xmask; fb[mb].y ^= xmask; fb[mb].z ^= xmask; fb[mb].w ^= xmask; }
     }
   };
 
@@ -314,8 +353,10 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
   // passed, is refilled with the loads of K step t + NSTAGE, spread between the matrix
   // instructions.  Three instances of the step body: with refill, without, and the last
   // step (nothing follows).
+  F8_TRACE_POINT(2);
   wait_ahead<NSTAGE - 1, LPS>(min(NSTAGE - 1, ksteps - 1));
   __syncthreads();
+  F8_TRACE_POINT(3);
   v4i fa[2][NB], fb[2][MB];
   read_frags(0, 0, fa[0], fb[0]);
   land_frags(fa[0], fb[0]);
@@ -347,9 +388,9 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
       for (int q = 0; q < NMF; ++q) {
         const int nb = q / MB, mb = q % MB;
         if (q == NMF - 1 && reads) land_frags(fa[nxt], fb[nxt]);
-        acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
+        if (!F8_EXP(4)) acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (last_slice && REFILL) {
+        if (last_slice && REFILL && !F8_EXP(1)) {
 #pragma unroll
           for (int j = q * LPM; j < (q + 1) * LPM && j < LPS; ++j) issue_one(c, j);
           __builtin_amdgcn_sched_barrier(0);
@@ -364,6 +405,7 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
     for (; t + 1 < ksteps; ++t) kstep_body(t, std::false_type{}, std::true_type{});
     kstep_body(t, std::false_type{}, std::false_type{});
   }
+  F8_TRACE_POINT(4);
   wait_vm<0>();
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
 
@@ -444,6 +486,7 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
     }
   }
   __syncthreads();
+  F8_TRACE_POINT(5);
   uint8_t *y = static_cast<uint8_t *>(p.y);
   for (int idx = tid; idx < BM * CPR; idx += NT) {
     const int row = idx / CPR, pc = idx - row * CPR;
@@ -455,6 +498,7 @@ __global__ __launch_bounds__(NT, MINB) void conv_fast_kernel(const ConvParams p,
           *reinterpret_cast<const uint32_t *>(epi + row * PITCH + pc * 4);
     }
   }
+  F8_TRACE_POINT(6);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>
@@ -473,7 +517,7 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
     if (e != hipSuccess) return (int)e;
     once = true;
   }
-  hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(NT), smem, stream, p, tiles_n, (int)ntiles);
+  hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(64 * WAVES_M * WAVES_N), smem, stream, p, tiles_n, (int)ntiles);
   return (int)hipGetLastError();
 }
 
@@ -488,18 +532,33 @@ int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
   return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 4, false>(p, stream);
 }
 
-constexpr int N_VARIANTS = 14;
+constexpr int N_VARIANTS = 24;
 const char *const kVariantNames[N_VARIANTS] = {
     "conv_fast<256x128,k64,s3>", "conv_fast<256x64,k64,s3>",  "conv_fast<128x128,k64,s2>",
     "conv_fast<128x64,k64,s2>",  "conv_fast<128x128,k128,s2>", "conv_fast<256x128,k128,s2>",
     "conv_fast<128x128,k128,s3>", "conv_fast<128x64,k128,s2>", "conv_fast<128x64,k64,s1>",
     "conv_fast<128x64,k128,s1>",  "conv_fast<128x128,k64,s1>", "conv_fast<128x256,k64,s2>",
-    "conv_fast<64x256,k64,s2>",   "conv_fast<128x256,k128,s2>"};
+    "conv_fast<64x256,k64,s2>",   "conv_fast<128x256,k128,s2>", "conv_fast<128x128,k64,s3>",
+    "conv_fast<128x128,k64,s4>",  "conv_fast<128x64,k64,s3>",   "conv_fast<128x64,k64,s4>",
+    "conv_fast<256x256,k128,s2,w2x4>", "conv_fast<256x256,k128,s2,w4x2>", "conv_fast<256x256,k64,s3,w2x4>",
+    "conv_fast<256x128,k128,s2,w4x2>", "conv_fast<256x256,k128,s2,w2x2>", "conv_fast<256x256,k64,s3,w2x2>"};
 
 int forced_variant() {
-  static const int v = [] { const char *e = getenv("F8_CONV_VARIANT"); return e ? atoi(e) : -1; }();
-  return v;
+  const char *e = getenv("F8_CONV_VARIANT");     // tuning aid: force one tile variant
+  return e ? atoi(e) : -1;
 }
+
+}  // namespace
+
+#ifdef F8_TRACE
+extern "C" int f8_trace_exp(int bits) { return bits == (F8_EXP_BITS) ? 0 : 1; }
+extern "C" int f8_trace_buffer(void *device_ptr) {
+  unsigned long long *ptr = static_cast<unsigned long long *>(device_ptr);
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &ptr, sizeof(ptr));
+}
+#endif
+
+namespace {
 
 }  // namespace
 
@@ -522,12 +581,29 @@ bool conv_fast_applicable(const ConvParams &p) {
 int conv_fast_variant(const ConvParams &p) {
   const int f = forced_variant();
   if (f >= 0 && f < N_VARIANTS) return f;
-  // Measured on MI355X over the ResNet-50 layer shapes: short-K and narrow layers are bound
-  // by memory latency and want many small workgroups per CU; long-K layers want whole
-  // 128-byte lines per row.
-  if (p.N <= 64 || p.K <= 128) return 3;
-  if (p.K >= 2048 && (p.C & 127) == 0) return 4;
-  return 2;
+  // Rules fitted to measurements of every variant on the ResNet-50 (batch 256) and ResNet-18
+  // (batch 64) layer shapes on MI355X.  Bigger tiles move fewer bytes from L2 into LDS per
+  // multiply-accumulate but only pay off while there are enough of them to occupy 256 CUs:
+  //  * narrow outputs, or too few 128 x 128 tiles: 128 x 64 (128-byte K steps when K is long);
+  //  * one K step (K <= 64): single-stage 128 x 128, four workgroups per CU;
+  //  * long K with whole 128-byte lines per row: eight waves on 256 x 256, else on 256 x 128,
+  //    else four waves on 128 x 128 with 128-byte K steps;
+  //  * otherwise 128 x 128 with 64-byte K steps, a three-deep ring once K is long enough.
+  auto tiles = [&](int bm, int bn) { return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+  const long long t128 = tiles(128, 128);
+  const bool lines = (p.C & 127) == 0;
+  if (p.N <= 64) return 3;
+  if (t128 < 160) return p.K >= 1024 && lines ? 7 : 3;
+  if (p.K <= 64) return t128 >= 1024 ? 10 : 3;
+  if (p.K <= 128) return t128 >= 1024 ? 2 : 3;
+  if (p.K >= 1024 && lines) {
+    if (p.N >= 256) {
+      if (tiles(256, 256) >= 128) return 19;
+      if (tiles(256, 128) >= 160) return 21;
+    }
+    return 4;
+  }
+  return p.K >= 512 ? 14 : 2;
 }
 
 const char *conv_fast_variant_name(int v) { return v >= 0 && v < N_VARIANTS ? kVariantNames[v] : "?"; }
@@ -552,7 +628,20 @@ int launch_conv_fast(const ConvParams &p, hipStream_t stream) {
     // contiguous run, the activations are read once
     case 11: return launch_fast_tile<128, 256, 2, 2, 64, 2, 2>(p, ev, stream);
     case 12: return launch_fast_tile<64, 256, 2, 2, 64, 2, 3>(p, ev, stream);
-    default: return launch_fast_tile<128, 256, 2, 2, 128, 2, 2>(p, ev, stream);
+    case 13: return launch_fast_tile<128, 256, 2, 2, 128, 2, 2>(p, ev, stream);
+    // deeper rings
+    case 14: return launch_fast_tile<128, 128, 2, 2, 64, 3, 3>(p, ev, stream);
+    case 15: return launch_fast_tile<128, 128, 2, 2, 64, 4, 2>(p, ev, stream);
+    case 16: return launch_fast_tile<128, 64, 2, 2, 64, 3, 4>(p, ev, stream);
+    case 17: return launch_fast_tile<128, 64, 2, 2, 64, 4, 3>(p, ev, stream);
+    // eight waves, 256 x 256: four times the arithmetic per byte moved from L2 to LDS
+    case 18: return launch_fast_tile<256, 256, 2, 4, 128, 2, 1>(p, ev, stream);
+    case 19: return launch_fast_tile<256, 256, 4, 2, 128, 2, 1>(p, ev, stream);
+    case 20: return launch_fast_tile<256, 256, 2, 4, 64, 3, 1>(p, ev, stream);
+    case 21: return launch_fast_tile<256, 128, 4, 2, 128, 2, 1>(p, ev, stream);
+    // four waves of 128 x 128: the fewest LDS bytes per matrix instruction
+    case 22: return launch_fast_tile<256, 256, 2, 2, 128, 2, 1>(p, ev, stream);
+    default: return launch_fast_tile<256, 256, 2, 2, 64, 3, 1>(p, ev, stream);
   }
 }
 

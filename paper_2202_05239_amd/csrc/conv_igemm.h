@@ -27,6 +27,7 @@ struct ConvParams {
   const uint8_t *lo_base;
   uint32_t x_delta, z_delta;
   int near;
+  uint32_t tap_rep;         // bit r * S set for every window row r (R * S <= 32, else unused)
   FastDiv fd_pq, fd_q, fd_c, fd_s, fd_cpt, fd_cpt2;   // by P*Q, Q, C, S, C / 64, C / 128
 };
 

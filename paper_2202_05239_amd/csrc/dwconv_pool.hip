@@ -105,7 +105,8 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
   constexpr int TQ = DW_TQ, TP = DW_TP;
   constexpr int NCOL = (TQ - 1) * STRIDE + 3;
   constexpr int NROW = (TP - 1) * STRIDE + 3;
-  const uint32_t gid = blockIdx.x * NT + threadIdx.x;
+  // neighbouring row chunks share input rows: keep them on one XCD (one L2)
+  const uint32_t gid = xcd_remap(blockIdx.x, gridDim.x) * NT + threadIdx.x;
   if (gid >= total) return;
   const uint32_t u1 = tl.fd_cg.div(gid);
   const int cg = (int)(gid - u1 * (uint32_t)tl.CG);
@@ -283,7 +284,8 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
 
 template <int R, int S>
 __global__ __launch_bounds__(NT) void maxpool_vec16_kernel(const PoolParams p, const PoolTiling tl, const uint32_t total) {
-  const uint32_t gid = blockIdx.x * NT + threadIdx.x;
+  // overlapping windows of neighbouring output rows: keep them on one XCD (one L2)
+  const uint32_t gid = xcd_remap(blockIdx.x, gridDim.x) * NT + threadIdx.x;
   if (gid >= total) return;
   const uint32_t pix = tl.fd_cg.div(gid);
   const int c = (int)(gid - pix * (uint32_t)tl.CG) * 16;

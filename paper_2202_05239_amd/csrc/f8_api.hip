@@ -93,6 +93,9 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   p.fd_cpt2 = FastDiv((uint32_t)((g.Cin & 127) == 0 ? g.Cin / 128 : 1));
   { static const int rm = [] { const char *e = getenv("F8_XCD_REMAP"); return e ? atoi(e) : 1; }(); p.remap = rm != 0; }
   p.fd_s = FastDiv((uint32_t)g.S);
+  p.tap_rep = 0;
+  if (g.R * g.S <= 32)
+    for (int r = 0; r < g.R; ++r) p.tap_rep |= 1u << (r * g.S);
   if (p.M == 0 || p.N == 0) return F8_OK;
   if (conv_fast_applicable(p)) return launch_conv_fast(p, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
   return launch_conv_igemm(p, vec, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
