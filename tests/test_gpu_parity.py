@@ -304,3 +304,72 @@ def test_repeatable_and_streams(oracle):
         outs.append(y.cpu().numpy())
     for o in outs:
         assert_same(o, want, "repeat")
+
+
+# ------------------------------------------------------------------------- tile variants
+
+N_TILE_VARIANTS = 24
+SINGLE_STAGE = {8: 64, 9: 128, 10: 64}          # variants that hold the whole K in one step
+
+
+@pytest.mark.parametrize("variant", range(N_TILE_VARIANTS))
+def test_every_tile_variant(oracle, variant, monkeypatch):
+    """The tile choice is a tuning decision, never a numerical one: every tile variant of the
+    fast dense kernel, forced through the tuning knob, gives the oracle's bits on ragged
+    shapes (tails in M, N and K, padding, stride, residual, both K-step widths)."""
+    monkeypatch.setenv("F8_CONV_VARIANT", str(variant))
+    kmax = SINGLE_STAGE.get(variant)
+    cases = [
+        (2, 19, 23, 64, 72, 1, 1, 1, 0, "u8", "u8", "u8"),           # K = 64: one step for everyone
+        (3, 13, 11, 128, 136, 1, 1, 1, 0, "s8", "s8", None),         # K = 128
+    ]
+    if kmax is None:
+        cases += [
+            (2, 15, 17, 32, 272, 3, 3, 1, 1, "u8", "u8", "s8"),      # K = 288, three N tiles of 128
+            (1, 21, 9, 256, 40, 3, 3, 2, 1, "u8", "s8", None),       # K = 2304, stride 2
+            (2, 9, 9, 384, 520, 1, 1, 1, 0, "u8", "u8", None),       # 128-byte lines, ragged N
+        ]
+    rng = np.random.default_rng(1000 + variant)
+    for case in cases:
+        B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt = case
+        if kmax is not None and R * S * Cin > kmax:
+            continue
+        x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt)
+        want = oracle.conv2d_fixed(x, L.w, L.bias, L, (st, st), (pd, pd), res)
+        assert_same(gpu_layer(L, x, res), want, "variant %d case %s" % (variant, str(case)))
+
+
+# ------------------------------------------------------------------------- measurement aids
+
+def test_profile_graph_replay_and_copy(oracle):
+    """The per-layer profiler leaves the chain's output unchanged; a captured HIP graph of the
+    chain reproduces the eager bits on every replay, with eager work between replays; the
+    copy yardstick copies."""
+    x, net = wl.config4(batch=4, hw=64)
+    xt = torch.from_numpy(x).to(DEV)
+    chain = f8.Chain(net).prepare(4)
+    out = torch.empty((4,) + chain.out_shape, dtype=chain.out_dtype, device=DEV)
+    chain.run(xt, out)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    want = oracle.run_network_parallel(net, x, host_threads())
+    assert_same(eager.cpu().numpy(), want, "eager")
+    ms = chain.profile(xt, out, repeats=2)
+    assert len(ms) == len(net.layers) and all(t > 0 for t in ms)
+    assert torch.equal(out, eager)
+    name, ops, nbytes = chain.layer_info(1, 4)
+    assert name and nbytes > 0
+    graph = chain.capture(xt, out)
+    for i in range(4):
+        out.fill_(i)                                   # eager work between the replays
+        scratch = torch.randn(1 << 16, device=DEV).sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d" % i
+    del scratch
+    src = torch.randint(0, 256, (1 << 20,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros_like(src)
+    f8.f8_copy_bytes(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
