@@ -40,15 +40,15 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 #define F8_EXP_BITS 0          // timing experiments (results invalid): 1 no refill loads, 2 no fragment reads, 4 no matrix ops, 8 no xor
 #endif
 #define F8_EXP(bit) ((F8_EXP_BITS) & (bit))
-__device__ unsigned long long *g_trace = nullptr;
+static unsigned long long *g_trace_host = nullptr;    // device buffer handed to the next launches
 #define F8_TRACE_POINT(i)                                                                         \
   do {                                                                                            \
-    if (threadIdx.x == 0 && g_trace) g_trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64();      \
+    if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64();      \
   } while (0)
 #define F8_TRACE_HWID()                                                                           \
   do {                                                                                            \
-    if (threadIdx.x == 0 && g_trace)                                                              \
-      g_trace[(size_t)blockIdx.x * 8 + 7] = (unsigned long long)__builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)); \
+    if (threadIdx.x == 0 && p.trace)                                                              \
+      p.trace[(size_t)blockIdx.x * 8 + 7] = (unsigned long long)__builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)); \
   } while (0)
 #else
 #define F8_EXP(bit) 0
@@ -188,6 +188,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     if (UT && !w_ok[i]) { w_row[i] = reinterpret_cast<const int8_t *>(p.zero); w_inc[i] = 0; }
   }
   const uint8_t *zero = p.zero;
+  const bool ktail = (p.K % BK) != 0;
 
   // Loads of one K step, one LDS-direct load per call of issue_one so that the main loop can
   // spread them between matrix instructions.  K-steps are issued strictly in order (the UT
@@ -206,14 +207,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     c.kstep = kstep;
     if (UT) {
       // scalar: which tap and which BK-channel slice this K step is
-      const FastDiv &fd_cpt = BK == 64 ? p.fd_cpt : p.fd_cpt2;
-      c.tap = fd_cpt.div((uint32_t)kstep);
-      const uint32_t cs = (uint32_t)kstep - c.tap * fd_cpt.d;
-      const uint32_t r = p.fd_s.div(c.tap);
-      const uint32_t s2 = c.tap - r * p.S;
-      c.toff = ((int)r * p.W + (int)s2) * p.C + (int)cs * BK;
+      if (p.R * p.S == 1) {
+        // a single tap: K steps are channel slices, the last one may be partial
+        c.tap = 0;
+        c.toff = kstep * BK;
+        c.kvalid = kstep * BK + cl * 16 < p.K;
+      } else {
+        const FastDiv &fd_cpt = BK == 64 ? p.fd_cpt : p.fd_cpt2;
+        c.tap = fd_cpt.div((uint32_t)kstep);
+        const uint32_t cs = (uint32_t)kstep - c.tap * fd_cpt.d;
+        const uint32_t r = p.fd_s.div(c.tap);
+        const uint32_t s2 = c.tap - r * p.S;
+        c.toff = ((int)r * p.W + (int)s2) * p.C + (int)cs * BK;
+        c.kvalid = true;
+      }
       c.r = c.s = 0;
-      c.kvalid = true;
     } else {
       // A unit is 16 channels of one tap (C % 16 == 0) or 16 / C whole taps of one window
       // row (C < 16, windows never clipped): either way 16 contiguous bytes starting at
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     for (int i = 0; i < XR; ++i) {
       if (i != j) continue;
       if (UT) {
-        const bool ok = (x_mask[i] >> c.tap) & 1u;
+        const bool ok = ((x_mask[i] >> c.tap) & 1u) && c.kvalid;
         uint32_t off = ok ? (uint32_t)(x_off[i] + c.toff) : p.z_delta;
         asm volatile("" : "+v"(off));
         __builtin_amdgcn_global_load_lds(
@@ -250,9 +258,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     for (int i = 0; i < WR; ++i) {
       if (i + XR != j) continue;
       if (UT) {
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)w_row[i],
-                                         (__attribute__((address_space(3))) void *)(c.base + BM * BK + i * (NT * 16)),
-                                         16, 0, 0);
+        if (ktail) {        // uniform: K is not a multiple of the step, chunks past the end read zeros
+          lds_direct_16(c.kvalid, w_row[i], zero, c.base + BM * BK + i * (NT * 16));
+        } else {
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)w_row[i],
+                                           (__attribute__((address_space(3))) void *)(c.base + BM * BK + i * (NT * 16)),
+                                           16, 0, 0);
+        }
         w_row[i] += w_inc[i];
       } else {
         lds_direct_16(c.kvalid && w_ok[i], w_row[i] + c.kstep * BK, zero, c.base + BM * BK + i * (NT * 16));
@@ -411,6 +423,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[nb][mb][4g+j] is channel n0+wn0+nb*32+8g+4*half+j of pixel m0+wm0+mb*32+l32.
+  if (p.y_type == T_S32) {
+    // raw int32 accumulators (the classifier's logits): four consecutive channels per store
+    int32_t *y32 = static_cast<int32_t *>(p.y);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = m0 + wm0 + mb * 32 + l32;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = n0 + wn0 + nb * 32 + g * 8 + half * 4;
+          if (m < p.M && n < p.N)
+            *reinterpret_cast<v4i *>(y32 + (size_t)m * p.N + n) =
+                v4i{acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
+        }
+      }
+    }
+    return;
+  }
   uint8_t *epi = lds;
   if (p.res) {
     if (RES_PREFETCH) {
@@ -517,13 +548,20 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
     if (e != hipSuccess) return (int)e;
     once = true;
   }
+#ifdef F8_TRACE
+  ConvParams pt = p;
+  pt.trace = g_trace_host;
+  hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(64 * WAVES_M * WAVES_N), smem, stream, pt, tiles_n, (int)ntiles);
+#else
   hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(64 * WAVES_M * WAVES_N), smem, stream, p, tiles_n, (int)ntiles);
+#endif
   return (int)hipGetLastError();
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB>
 int launch_fast_tile(const ConvParams &p, int ev, hipStream_t stream) {
-  const bool ut = p.C % BK == 0 && p.R * p.S <= 32 && p.near;
+  // scalar tap decode: a K step never straddles two taps (whole steps per tap, or one tap only)
+  const bool ut = (p.C % BK == 0 || p.R * p.S == 1) && p.R * p.S <= 32 && p.near;
   if (ut) {
     if (ev == 16) return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 16, true>(p, stream);
     return launch_fast_tile_ev<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, 4, true>(p, stream);
@@ -553,14 +591,10 @@ int forced_variant() {
 #ifdef F8_TRACE
 extern "C" int f8_trace_exp(int bits) { return bits == (F8_EXP_BITS) ? 0 : 1; }
 extern "C" int f8_trace_buffer(void *device_ptr) {
-  unsigned long long *ptr = static_cast<unsigned long long *>(device_ptr);
-  return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &ptr, sizeof(ptr));
+  g_trace_host = static_cast<unsigned long long *>(device_ptr);
+  return 0;
 }
 #endif
-
-namespace {
-
-}  // namespace
 
 bool conv_fast_applicable(const ConvParams &p) {
   const uintptr_t bits = reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w);
@@ -571,8 +605,10 @@ bool conv_fast_applicable(const ConvParams &p) {
   const bool packed = p.C < 16 && 16 % p.C == 0 && ((p.S * p.C) & 15) == 0 && p.ph == 0 && p.pw == 0 &&
                       (p.P - 1) * p.sh + p.R <= p.H && (p.Q - 1) * p.sw + p.S <= p.W;
   if (!wide && !packed) return false;
-  if (p.y_type == T_S32 || (p.res && p.res_type == T_S32)) return false;
   if (p.N & 3) return false;
+  if (p.y_type == T_S32)      // raw accumulators (logits): stored straight from the registers, no residual
+    return !p.res && (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
+  if (p.res && p.res_type == T_S32) return false;
   uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res);
   if (ybits & 3) return false;
   return true;
@@ -594,6 +630,9 @@ int conv_fast_variant(const ConvParams &p) {
   const bool lines = (p.C & 127) == 0;
   if (p.N <= 64) return 3;
   if (t128 < 160) return p.K >= 1024 && lines ? 7 : 3;
+  // the last 128-wide tile would be mostly padding (N = 144, 160, 192 ...): 64-wide tiles
+  const int pad128 = (p.N + 127) / 128 * 128 - p.N, pad64 = (p.N + 63) / 64 * 64 - p.N;
+  if (pad128 - pad64 >= 64 && pad128 * 5 > p.N) return p.K <= 64 ? 8 : (p.K >= 512 ? 16 : 3);
   if (p.K <= 64) return t128 >= 1024 ? 10 : 3;
   if (p.K <= 128) return t128 >= 1024 ? 2 : 3;
   if (p.K >= 1024 && lines) {

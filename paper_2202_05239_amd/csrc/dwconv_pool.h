@@ -39,4 +39,8 @@ int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp
                      hipStream_t stream);
 int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C, int Sp, hipStream_t stream);
 
+// Channel padding: rows of C bytes -> rows of Cp bytes (Cp % 4 == 0, Cp >= C), zeros in C..Cp-1.
+// dst 4-byte aligned.
+int launch_pad_rows(const void *src, void *dst, long long rows, int C, int Cp, hipStream_t stream);
+
 }  // namespace f8

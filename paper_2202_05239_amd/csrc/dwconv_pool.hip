@@ -411,6 +411,26 @@ __global__ __launch_bounds__(NT) void repack_weights_kernel(const int8_t *w, uin
   wp[gid] = v;
 }
 
+// rows of C bytes -> rows of Cp bytes with zeros in C..Cp-1; one thread per output dword.
+__global__ __launch_bounds__(NT) void pad_rows_kernel(const uint8_t *src, uint32_t *dst, int C, int Cp, long long total,
+                                                      int dword_rows) {
+  const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const int dpr = Cp >> 2;                       // dwords per output row
+  const long long row = gid / dpr;
+  const int k = (int)(gid - row * dpr) * 4;
+  const uint8_t *s = src + row * C + k;
+  uint32_t v = 0;
+  if (dword_rows) {                              // C % 4 == 0 and src 4-byte aligned: whole dwords
+    if (k < C) v = *reinterpret_cast<const uint32_t *>(s);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (k + j < C) v |= (uint32_t)s[j] << (8 * j);
+  }
+  dst[gid] = v;
+}
+
 // Plain streaming copy, 16 bytes per lane: the yardstick for what HBM delivers to a kernel
 // that reads and writes every byte once, and the known-size reference for the memory
 // traffic counters.
@@ -496,6 +516,15 @@ int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C,
   if (total <= 0) return 0;
   hipLaunchKernelGGL(repack_weights_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, w,
                      static_cast<uint32_t *>(wp), N, R, S, C, Sp, total);
+  return (int)hipGetLastError();
+}
+
+int launch_pad_rows(const void *src, void *dst, long long rows, int C, int Cp, hipStream_t stream) {
+  const long long total = rows * (Cp / 4);
+  if (total <= 0) return 0;
+  const int dword_rows = (C & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0;
+  hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, static_cast<const uint8_t *>(src),
+                     static_cast<uint32_t *>(dst), C, Cp, total, dword_rows);
   return (int)hipGetLastError();
 }
 

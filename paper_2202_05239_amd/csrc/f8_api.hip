@@ -93,6 +93,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   p.fd_cpt2 = FastDiv((uint32_t)((g.Cin & 127) == 0 ? g.Cin / 128 : 1));
   { static const int rm = [] { const char *e = getenv("F8_XCD_REMAP"); return e ? atoi(e) : 1; }(); p.remap = rm != 0; }
   p.fd_s = FastDiv((uint32_t)g.S);
+  p.trace = nullptr;
   p.tap_rep = 0;
   if (g.R * g.S <= 32)
     for (int r = 0; r < g.R; ++r) p.tap_rep |= 1u << (r * g.S);

@@ -12,6 +12,9 @@
 // and 4 channels, each window row is padded to a multiple of 4 taps with zero weights.
 // The sums are unchanged (only zero products are added), windows are never clipped, and
 // 16 contiguous bytes hold four whole taps, which is what the fast kernel's loads need.
+// A dense layer whose input channel count is above 4 and not a multiple of 16 (24 in the
+// first MobileNetV2 blocks) is run on a copy of its input and weights with the channels
+// padded with zeros to the next multiple of 16, for the same reason.
 #include <algorithm>
 #include <new>
 #include <vector>
@@ -36,7 +39,8 @@ struct Tensor {
 
 struct Stem {
   bool on = false;
-  int Sp = 0, Hp = 0, Wp = 0;       // padded window width, padded image extent (4 channels)
+  int Cp = 4;                       // channels after the re-layout: 4 (stem) or a multiple of 16
+  int Sp = 0, Hp = 0, Wp = 0;       // stem: padded window width, padded image extent
   size_t w_off = 0;                 // re-laid-out weights: byte offset in the constants region
   size_t x_off_per_image = 0;       // re-laid-out input: arena offset per image
   size_t x_bytes_per_image = 0;
@@ -131,8 +135,10 @@ struct f8_chain {
   Geom conv_geom(size_t i, int batch) const {
     Geom g = geom[i];
     g.B = batch;
-    if (stem[i].on) {
+    if (stem[i].on && stem[i].Cp == 4) {
       g.H = stem[i].Hp; g.W = stem[i].Wp; g.Cin = 4; g.S = stem[i].Sp; g.ph = 0; g.pw = 0;
+    } else if (stem[i].on) {
+      g.Cin = stem[i].Cp;
     }
     return g;
   }
@@ -153,8 +159,10 @@ struct f8_chain {
         const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
         if (stem[i].on) {
           void *xp = arena(workspace) + stem[i].x_off_per_image * (size_t)batch;
-          if (launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s) != 0)
-            return F8_ERR_DEVICE;
+          const int e = stem[i].Cp == 4
+                            ? launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s)
+                            : launch_pad_rows(src, xp, (long long)batch * g.H * g.W, g.Cin, stem[i].Cp, s);
+          if (e != 0) return F8_ERR_DEVICE;
           src = xp;
         }
         return enqueue_conv(src, conv_weights(i, workspace), acc0, workspace, dst, res, conv_geom(i, batch), L.q, s);
@@ -256,6 +264,12 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
         sm.x_bytes_per_image = (size_t)sm.Hp * sm.Wp * 4;
         sm.w_off = c->const_bytes;
         c->const_bytes += round256((size_t)L.Cout * g.R * sm.Sp * 4);
+      } else if (L.Cin > 4 && (L.Cin & 15) != 0 && L.q.y_type != F8_S32 && (L.Cout & 3) == 0) {
+        sm.on = true;
+        sm.Cp = (L.Cin + 15) / 16 * 16;
+        sm.x_bytes_per_image = (size_t)g.H * g.W * sm.Cp;
+        sm.w_off = c->const_bytes;
+        c->const_bytes += round256((size_t)L.Cout * g.R * g.S * sm.Cp);
       }
     }
     c->stem.push_back(sm);
@@ -303,7 +317,10 @@ f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream
     if (L.op != F8_OP_CONV) continue;
     if (c->stem[i].on) {
       void *wp = static_cast<uint8_t *>(workspace) + c->stem[i].w_off;
-      if (launch_repack_weights(L.w, wp, L.Cout, L.R, L.S, L.Cin, c->stem[i].Sp, s) != 0) return F8_ERR_DEVICE;
+      const int e = c->stem[i].Cp == 4
+                        ? launch_repack_weights(L.w, wp, L.Cout, L.R, L.S, L.Cin, c->stem[i].Sp, s)
+                        : launch_pad_rows(L.w, wp, (long long)L.Cout * L.R * L.S, L.Cin, c->stem[i].Cp, s);
+      if (e != 0) return F8_ERR_DEVICE;
     }
     int32_t *acc0 = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
     const f8_status st = enqueue_fold(c->conv_weights(i, workspace), L.bias, acc0, c->conv_geom(i, 1), L.q, s);

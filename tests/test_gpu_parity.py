@@ -167,6 +167,10 @@ DENSE_CASES = [
     (1, 1, 1, 16, 16, 1, 1, 1, 0, "u8", "u8", None, 0),          # single pixel
     (1, 6, 6, 1, 1, 3, 3, 1, 1, "u8", "u8", None, 0),            # single channel in and out
     (4, 14, 14, 256, 64, 1, 1, 1, 0, "u8", "u8", "u8", 0),
+    (2, 14, 14, 144, 24, 1, 1, 1, 0, "u8", "s8", "s8", 0),       # 1x1 with a partial last K step
+    (2, 10, 11, 32, 144, 1, 1, 1, 0, "s8", "u8", None, 0),       # K shorter than one step, N = 144
+    (1, 9, 9, 208, 80, 1, 1, 2, 0, "u8", "u8", None, 0),         # K = 13 x 16, strided 1x1
+    (2, 6, 6, 96, 576, 1, 1, 1, 0, "u8", "u8", None, 0),
 ]
 
 
@@ -322,12 +326,15 @@ def test_every_tile_variant(oracle, variant, monkeypatch):
     cases = [
         (2, 19, 23, 64, 72, 1, 1, 1, 0, "u8", "u8", "u8"),           # K = 64: one step for everyone
         (3, 13, 11, 128, 136, 1, 1, 1, 0, "s8", "s8", None),         # K = 128
+        (2, 7, 9, 48, 20, 1, 1, 1, 0, "u8", "u8", "u8"),             # K = 48: partial step
     ]
     if kmax is None:
         cases += [
             (2, 15, 17, 32, 272, 3, 3, 1, 1, "u8", "u8", "s8"),      # K = 288, three N tiles of 128
             (1, 21, 9, 256, 40, 3, 3, 2, 1, "u8", "s8", None),       # K = 2304, stride 2
             (2, 9, 9, 384, 520, 1, 1, 1, 0, "u8", "u8", None),       # 128-byte lines, ragged N
+            (2, 11, 5, 144, 24, 1, 1, 1, 0, "u8", "s8", "s8"),       # 1x1, K = 144: partial last step
+            (1, 9, 9, 208, 80, 1, 1, 2, 0, "s8", "u8", None),
         ]
     rng = np.random.default_rng(1000 + variant)
     for case in cases:
@@ -373,3 +380,36 @@ def test_profile_graph_replay_and_copy(oracle):
     f8.f8_copy_bytes(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+def test_chain_channel_padding(oracle):
+    """Dense layers whose input channel count is not a multiple of 16 run in the chain on a
+    zero-padded copy of input and weights: same bits as the oracle and as the single-layer
+    entry point, which takes the generic kernel."""
+    rng = np.random.default_rng(4242)
+    B, H, W = 3, 13, 11
+    x = wl.draw_u8(rng, (B, H, W, 20))
+    net = wl.Net(name="odd_channels", in_hw=(H, W), in_c=20, x_type="u8", fl_x=4)
+    specs = [(20, 40, 3, 1, 1, "u8", "u8"), (40, 24, 1, 1, 0, "u8", "s8"), (24, 36, 3, 2, 1, "s8", "u8")]
+    hw, src = (H, W), 0
+    for i, (cin, cout, k, st, pd, xt, yt) in enumerate(specs):
+        _, L, _ = wl.random_conv_case(rng, 1, hw[0], hw[1], cin, cout, k, k, st, pd, xt, yt, None)
+        L.src, L.dst, L.name = src, src + 1, "l%d" % i
+        if i:
+            L.fl_x = net.layers[-1].fl_y
+            L.fl_y = max(0, L.fl_x + L.fl_w - 6)
+        net.layers.append(L)
+        hw, src = L.out_hw, src + 1
+    net.fl_x = net.layers[0].fl_x
+    want = oracle.run_network(net, x, keep_all=True)
+    chain = f8.Chain(net, keep_all=True).prepare(B)
+    out = chain.run(torch.from_numpy(x).to(DEV))
+    torch.cuda.synchronize()
+    for L in net.layers[:-1]:
+        assert_same(chain.tensor(L.dst).cpu().numpy(), want[L.dst], "padded chain " + L.name)
+    assert_same(out.cpu().numpy(), want[net.layers[-1].dst], "padded chain output")
+    assert "conv_fast" in chain.layer_info(0, B)[0] and "conv_fast" in chain.layer_info(2, B)[0]
+    t = {0: x}
+    for L in net.layers:
+        t[L.dst] = gpu_layer(L, t[L.src])
+        assert_same(t[L.dst], want[L.dst], "single layer " + L.name)
