@@ -346,6 +346,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) fb[mb] = lds_read_frag(xs + foff[ks], mb * BLK);
   };
+  // one fragment read (index j of NB + MB) of a slice
+  auto read_one = [&](int stage, int ks, int j, v4i (&fa)[NB], v4i (&fb)[MB]) {
+    const uint32_t xs = lds_base + (uint32_t)(stage * STAGE + wm0 * BK);
+    const uint32_t ws = lds_base + (uint32_t)(stage * STAGE + BM * BK + wn0 * BK);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) if (nb == j) fa[nb] = lds_read_frag(ws + foff[ks], nb * BLK);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) if (mb + NB == j) fb[mb] = lds_read_frag(xs + foff[ks], mb * BLK);
+  };
   // fragments are usable once the LDS counter has drained; the xor makes activations signed
   auto land_frags = [&](v4i (&fa)[NB], v4i (&fb)[MB]) {
     wait_lgkm<0>();
@@ -384,13 +393,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
       const bool last_slice = ks == KS - 1;
       StepCtx c{};
       bool reads = true;
+      // Tiles with more matrix instructions per slice than fragments issue one fragment read
+      // after each instruction instead of all of them up front: the LDS requests of the eight
+      // waves no longer arrive in one burst.
+      constexpr bool SPREAD = NMF > NB + MB;
+      int rstage = stage, rks = ks + 1;
       if (!last_slice) {
-        read_frags(stage, ks + 1, fa[nxt], fb[nxt]);
+        if (!SPREAD) read_frags(stage, ks + 1, fa[nxt], fb[nxt]);
       } else if (NEXT) {
         // K step t+1 must have landed; steps t+2 .. t+NSTAGE-1 may stay in flight
         wait_ahead<NSTAGE - 2, LPS>(min(NSTAGE - 2, ksteps - 2 - t));
         __syncthreads();
-        read_frags(stage + 1 == NSTAGE ? 0 : stage + 1, 0, fa[nxt], fb[nxt]);
+        rstage = stage + 1 == NSTAGE ? 0 : stage + 1; rks = 0;
+        if (!SPREAD) read_frags(rstage, 0, fa[nxt], fb[nxt]);
         if (REFILL) c = decode_step(t + NSTAGE, stage);
       } else {
         reads = false;
@@ -402,6 +417,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
         if (q == NMF - 1 && reads) land_frags(fa[nxt], fb[nxt]);
         if (!F8_EXP(4)) acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        if (SPREAD && reads && q < NB + MB) {
+          read_one(rstage, rks, q, fa[nxt], fb[nxt]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         if (last_slice && REFILL && !F8_EXP(1)) {
 #pragma unroll
           for (int j = q * LPM; j < (q + 1) * LPM && j < LPS; ++j) issue_one(c, j);
