@@ -242,6 +242,25 @@ class _NetBuilder:
         self.net.layers.append(L)
         return dst
 
+    def dwconv(self, name, src, k, stride, pad):
+        """Depthwise layer followed by the unsigned quantiser (ReLU + clip)."""
+        rng, s = self.rng, self.t[src]
+        c = s["c"]
+        fl_w = int(rng.integers(self.fl_w_range[0], self.fl_w_range[1] + 1))
+        fl_y = int(rng.integers(self.fl_a_range[0], self.fl_a_range[1] + 1))
+        w = draw_weight(rng, (k, k, c), float(np.sqrt(2.0 / (k * k))), fl_w)
+        bias = draw_bias(rng, c, s["fl"] + fl_w)
+        hw = (_out(s["hw"][0], k, stride, pad), _out(s["hw"][1], k, stride, pad))
+        hi = 255
+        if self.clip_draw and int(rng.integers(0, 4)) == 0:
+            hi = int(rng.integers(96, 255))
+        dst = self._new(hw, c, "u8", fl_y)
+        self.net.layers.append(LayerSpec(
+            op="dwconv", name=name, src=src, dst=dst, Cin=c, Cout=c, R=k, S=k, stride=stride, pad=pad,
+            fl_x=s["fl"], fl_w=fl_w, fl_y=fl_y, clip_lo=0, clip_hi=hi, x_type=s["type"], y_type="u8",
+            w=w, bias=bias, in_hw=s["hw"], out_hw=hw))
+        return dst
+
     def maxpool(self, name, src, k=3, stride=2, pad=1):
         s = self.t[src]
         hw = (_out(s["hw"][0], k, stride, pad), _out(s["hw"][1], k, stride, pad))
@@ -307,6 +326,40 @@ def resnet50b(rng, hw=224, classes=1000, widths=(64, 128, 256, 512), depths=(3, 
     t = b.gpool("gpool", t)
     b.conv("fc", t, classes, 1, 1, 0, raw=True)
     return b.net
+
+
+def mobilenet_v2(rng, hw=224, classes=1000, clip_draw=True):
+    """MobileNetV2 body in fixed point (paper Sec. 5 / Appx: ReLU6 replaced by the unsigned
+    quantiser, linear bottleneck outputs signed): 3x3/2 stem, 17 inverted-residual blocks
+    (1x1 expand, 3x3 depthwise, 1x1 linear projection, identity shortcut when shapes match),
+    1x1 to 1280 channels, global pool, classifier."""
+    b = _NetBuilder("mobilenet_v2", rng, hw, 3, "s8", 5, (5, 9), (2, 6), clip_draw)
+    t = b.conv("stem", 0, 32, 3, 2, 1)
+    cfg = ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1))
+    blk = 0
+    for expand, c, n, stride in cfg:
+        for i in range(n):
+            blk += 1
+            pre = "b%d." % blk
+            st = stride if i == 0 else 1
+            cin = b.t[t]["c"]
+            u = t
+            if expand != 1:
+                u = b.conv(pre + "expand", u, cin * expand, 1, 1, 0)
+            u = b.dwconv(pre + "dw", u, 3, st, 1)
+            shortcut = t if (st == 1 and cin == c) else -1
+            t = b.conv(pre + "project", u, c, 1, 1, 0, relu=False, res=shortcut)
+    t = b.conv("head", t, 1280, 1, 1, 0)
+    t = b.gpool("gpool", t)
+    b.conv("fc", t, classes, 1, 1, 0, raw=True)
+    return b.net
+
+
+def mobilenet_v2_forward(seed=None, batch=64, hw=224):
+    """Whole fixed-point MobileNetV2 forward (beyond the five baseline configs)."""
+    rng = np.random.default_rng(seed_of(5) if seed is None else seed)
+    x = _resnet_input(rng, batch, hw)
+    return x, mobilenet_v2(rng, hw)
 
 
 def config3(seed=None, batch=64, hw=224):

@@ -139,8 +139,16 @@ def test_config4_resnet50(oracle):
     assert out.shape == (256, 1, 1, 1000)
 
 
+def test_mobilenet_v2_forward(oracle):
+    """Beyond the five baseline configs: the whole fixed-point MobileNetV2 (stem, 17 inverted
+    residual blocks with depthwise layers and signed linear bottlenecks, head, pool, classifier)."""
+    x, net = wl.mobilenet_v2_forward(batch=64)                      # 224x224x3
+    out = check_network(oracle, x, net, [0, 1, 2, 31, 32, 61, 62, 63], "mobilenet_v2")
+    assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
+
+
 def test_small_networks_full_compare(oracle):
-    for cfg, batch in ((wl.config3, 5), (wl.config4, 3)):
+    for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3)):
         x, net = cfg(batch=batch, hw=64)
         check_network(oracle, x, net, list(range(batch)), net.name + " 64x64")
 
