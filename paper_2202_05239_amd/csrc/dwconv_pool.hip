@@ -100,13 +100,34 @@ __device__ __forceinline__ void transpose4(uint32_t a, uint32_t b, uint32_t c, u
   t[3] = perm(cd_hi, ab_hi, 0x07060302u);
 }
 
+// clamp with lo <= hi as one instruction
+__device__ __forceinline__ int med3(int v, int lo, int hi) {
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+  return r;
+}
+
+// d = dot4(a, b) + c with a destination of its own (the builtin's accumulate-in-place form
+// needs a copy of the start value first)
+__device__ __forceinline__ int dot4_from(uint32_t a, uint32_t b, int c) {
+  int r;
+  asm("v_dot4_i32_i8 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+constexpr int DW_NT = 64;        // one wave per workgroup: small layers still spread over all CUs
+
 template <int STRIDE, bool XS>
-__global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl, const uint32_t total) {
+__global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl, const uint32_t total) {
   constexpr int TQ = DW_TQ, TP = DW_TP;
   constexpr int NCOL = (TQ - 1) * STRIDE + 3;
   constexpr int NROW = (TP - 1) * STRIDE + 3;
+  // Window dwords kept per input row and channel.  Stride 1: two (columns 0..3 and 2..5), each
+  // serving two outputs through the weight dwords (w0, w1, w2, 0) and (0, w0, w1, w2).
+  // Stride 2: four (columns 0.., 2.., 4.., 6..).
+  constexpr int NWIN = STRIDE == 1 ? 2 : 4;
   // neighbouring row chunks share input rows: keep them on one XCD (one L2)
-  const uint32_t gid = xcd_remap(blockIdx.x, gridDim.x) * NT + threadIdx.x;
+  const uint32_t gid = xcd_remap(blockIdx.x, gridDim.x) * DW_NT + threadIdx.x;
   if (gid >= total) return;
   const uint32_t u1 = tl.fd_cg.div(gid);
   const int cg = (int)(gid - u1 * (uint32_t)tl.CG);
@@ -118,8 +139,8 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
   const int q0 = strip * TQ, p0 = chunk * TP;
   const int iw0 = q0 * STRIDE - p.pw, ih0 = p0 * STRIDE - p.ph;
 
-  // weights: wt[r][ch] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0)
-  uint32_t wt[3][4];
+  // weights: wt[r][ch][0] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0), [1] = the same one byte up
+  uint32_t wt[3][4][STRIDE == 1 ? 2 : 1];
   int acc0[4];
 #pragma unroll
   for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[c + ch] : 0);
@@ -129,13 +150,14 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
     const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + c);
     const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + c);
     const uint32_t lo = perm(w1, w0, 0x05010400u), hi = perm(w1, w0, 0x07030602u);
-    wt[r][0] = perm(w2, lo, 0x0c040100u);
-    wt[r][1] = perm(w2, lo, 0x0c050302u);
-    wt[r][2] = perm(w2, hi, 0x0c060100u);
-    wt[r][3] = perm(w2, hi, 0x0c070302u);
-    if (!XS) {
+    wt[r][0][0] = perm(w2, lo, 0x0c040100u);
+    wt[r][1][0] = perm(w2, lo, 0x0c050302u);
+    wt[r][2][0] = perm(w2, hi, 0x0c060100u);
+    wt[r][3][0] = perm(w2, hi, 0x0c070302u);
 #pragma unroll
-      for (int ch = 0; ch < 4; ++ch) acc0[ch] += 128 * __builtin_amdgcn_sdot4((int)wt[r][ch], 0x01010101, 0, false);
+    for (int ch = 0; ch < 4; ++ch) {
+      if (!XS) acc0[ch] += 128 * __builtin_amdgcn_sdot4((int)wt[r][ch][0], 0x01010101, 0, false);
+      if (STRIDE == 1) wt[r][ch][1] = wt[r][ch][0] << 8;
     }
   }
 
@@ -143,25 +165,26 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
   uint32_t col_ok = 0;
 #pragma unroll
   for (int j = 0; j < NCOL; ++j) col_ok |= ((unsigned)(iw0 + j) < (unsigned)p.W ? 1u : 0u) << j;
-  const long long row_bytes = (long long)p.W * p.C;
-  const uint8_t *xcol = p.x + ((long long)b * p.H * p.W + iw0) * p.C + c;     // column iw0 of row 0 of image b
+  // 32-bit byte offsets from p.x (the tensor is below 2 GiB); may wrap for taps outside the
+  // image, which are never dereferenced
+  const uint32_t row_bytes = (uint32_t)(p.W * p.C);
+  const uint32_t xcol = ((b * (uint32_t)p.H + (uint32_t)ih0) * (uint32_t)p.W + (uint32_t)iw0) * (uint32_t)p.C + (uint32_t)c;
   uint8_t *ycol = static_cast<uint8_t *>(p.y) + ((size_t)b * p.P * p.Q + q0) * p.C + c;
 
-  uint32_t win[3][4][4];        // [input row mod 3][channel][output column]: the window dwords
+  uint32_t win[3][4][NWIN];     // [input row mod 3][channel][window]
   // Loads are branch-free (an out-of-image tap reads the tensor's first dword and is then
   // replaced by zero) and run PF input rows ahead of the arithmetic, so every wave keeps
   // 2 * NCOL dwords per lane in flight.
   constexpr int PF = 2;
   uint32_t ring[PF + 1][NCOL];
   auto load_row = [&](int i, uint32_t (&dst)[NCOL]) {
-    const int ih = ih0 + i;
-    const bool row_ok = (unsigned)ih < (unsigned)p.H;
-    const uint8_t *xrow = xcol + (long long)ih * row_bytes;
+    const bool row_ok = (unsigned)(ih0 + i) < (unsigned)p.H;
+    const uint32_t xrow = xcol + (uint32_t)i * row_bytes;
 #pragma unroll
     for (int j = 0; j < NCOL; ++j) {
       const bool ok = row_ok && ((col_ok >> j) & 1u);
-      const uint8_t *a = ok ? xrow + (long long)j * p.C : p.x;
-      const uint32_t v = *reinterpret_cast<const uint32_t *>(a);
+      const uint32_t off = ok ? xrow + (uint32_t)(j * p.C) : 0u;
+      const uint32_t v = *reinterpret_cast<const uint32_t *>(p.x + (size_t)off);
       dst[j] = ok ? v : 0u;
     }
   };
@@ -173,7 +196,7 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
     uint32_t raw[NCOL];
 #pragma unroll
     for (int j = 0; j < NCOL; ++j) raw[j] = XS ? ring[i % (PF + 1)][j] : (ring[i % (PF + 1)][j] ^ 0x80808080u);
-    uint32_t (&wn)[4][4] = win[i % 3];
+    uint32_t (&wn)[4][NWIN] = win[i % 3];
     uint32_t t[4], u[4];
     transpose4(raw[0], raw[1], raw[2], raw[3], t);
     if (STRIDE == 1) {
@@ -181,10 +204,8 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
       u[0] = ef_lo; u[1] = ef_lo >> 16; u[2] = ef_hi; u[3] = ef_hi >> 16;
 #pragma unroll
       for (int ch = 0; ch < 4; ++ch) {
-        wn[ch][0] = t[ch];
-        wn[ch][1] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 1);
-        wn[ch][2] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 2);
-        wn[ch][3] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 3);
+        wn[ch][0] = t[ch];                                            // columns 0..3
+        wn[ch][1] = __builtin_amdgcn_alignbyte(u[ch], t[ch], 2);      // columns 2..5
       }
     } else {
       transpose4(raw[4], raw[5], raw[6], raw[7], u);
@@ -202,16 +223,14 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
       const int pp = p0 + pl;
       int acc[4][4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
-        for (int ch = 0; ch < 4; ++ch) acc[q][ch] = acc0[ch];
-#pragma unroll
-      for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            acc[q][ch] = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + r) % 3][ch][q], (int)wt[r][ch], acc[q][ch], false);
+        for (int q = 0; q < 4; ++q) {
+          const int wi = STRIDE == 1 ? q >> 1 : q, wv = STRIDE == 1 ? q & 1 : 0;
+          int a = dot4_from(win[(pl * STRIDE + 0) % 3][ch][wi], wt[0][ch][wv], acc0[ch]);
+          a = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + 1) % 3][ch][wi], (int)wt[1][ch][wv], a, false);
+          acc[q][ch] = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + 2) % 3][ch][wi], (int)wt[2][ch][wv], a, false);
+        }
       if (pp < p.P) {
         uint8_t *yrow = ycol + (size_t)pp * p.Q * p.C;
 #pragma unroll
@@ -219,7 +238,7 @@ __global__ __launch_bounds__(NT) void dwconv3x3_kernel(const DwParams p, const D
           if (q0 + q < p.Q) {
             int v[4];
 #pragma unroll
-            for (int ch = 0; ch < 4; ++ch) v[ch] = requant<false>(acc[q][ch], p.shift, p.lo, p.hi);
+            for (int ch = 0; ch < 4; ++ch) v[ch] = med3(acc[q][ch] >> p.shift, p.lo, p.hi);
             *reinterpret_cast<uint32_t *>(yrow + (size_t)q * p.C) = pack4(v[0], v[1], v[2], v[3]);
           }
         }
@@ -464,7 +483,7 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
     tl.fd_qs = FastDiv((uint32_t)tl.QS);
     tl.fd_pc = FastDiv((uint32_t)tl.PC);
     const uint32_t threads = (uint32_t)((long long)p.B * tl.PC * tl.QS * tl.CG);
-    const dim3 grid((threads + NT - 1) / NT), block(NT);
+    const dim3 grid((threads + DW_NT - 1) / DW_NT), block(DW_NT);
     const bool xs = p.x_type == T_S8;
     if (p.sh == 1) {
       if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<1, true>), grid, block, 0, stream, p, tl, threads);

@@ -421,3 +421,38 @@ def test_chain_channel_padding(oracle):
     for L in net.layers:
         t[L.dst] = gpu_layer(L, t[L.src])
         assert_same(t[L.dst], want[L.dst], "single layer " + L.name)
+
+
+# ------------------------------------------------------------------------- random geometry
+
+def test_random_geometry_fuzz(oracle):
+    """Seeded random layer geometries (window, stride, padding, channel counts, types, residual
+    kinds, shifts) against the oracle: dense and depthwise, every draw bit-exact."""
+    rng = np.random.default_rng(20220205)
+    types = ["u8", "s8"]
+    for it in range(60):
+        depthwise = it % 3 == 2
+        R = int(rng.choice([1, 1, 2, 3, 3, 5]))
+        S = R if rng.random() < 0.8 else int(rng.choice([1, 2, 3, 4]))
+        if depthwise:
+            R = S = int(rng.choice([3, 3, 3, 5, 2]))
+        stride = int(rng.choice([1, 1, 2, 3]))
+        pad = int(rng.integers(0, max(R, S)))
+        H = int(rng.integers(max(1, R - 2 * pad), 24))
+        W = int(rng.integers(max(1, S - 2 * pad), 24))
+        B = int(rng.integers(1, 4))
+        Cin = int(rng.choice([1, 3, 4, 8, 12, 16, 24, 32, 48, 64, 80, 96, 128, 144, 192, 256]))
+        Cout = Cin if depthwise else int(rng.choice([1, 4, 8, 10, 16, 24, 40, 64, 72, 128, 136, 200, 256, 320]))
+        xt = types[int(rng.integers(0, 2))]
+        yt = "s32" if (rng.random() < 0.1) else types[int(rng.integers(0, 2))]
+        rt = None if rng.random() < 0.5 else ["u8", "s8", "s32"][int(rng.integers(0, 3))]
+        shift = None if (yt == "s32" or rng.random() < 0.7) else int(rng.choice([0, -1, -3, 1, 16]))
+        x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, stride, pad, xt, yt, rt, shift=shift,
+                                        depthwise=depthwise)
+        if L.out_hw[0] < 1 or L.out_hw[1] < 1:
+            continue
+        fn = oracle.dwconv_fixed if depthwise else oracle.conv2d_fixed
+        want = fn(x, L.w, L.bias, L, (stride, stride), (pad, pad), res)
+        what = "fuzz %d: dw=%s B%d %dx%d C%d->%d k%dx%d s%d p%d %s->%s res %s shift %s" % (
+            it, depthwise, B, H, W, Cin, Cout, R, S, stride, pad, xt, yt, rt, shift)
+        assert_same(gpu_layer(L, x, res), want, what)
