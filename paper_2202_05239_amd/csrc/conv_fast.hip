@@ -560,12 +560,16 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
   constexpr int epi_bytes = BM * (BN + 16);
   constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   auto k = conv_fast_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, EV, UT>;
-  static bool once = false;   // raising the dynamic LDS limit is idempotent; racing callers set the same value
-  if (!once) {
+  // Raising the dynamic LDS limit is per device and idempotent (racing callers set the same
+  // value); remember which devices have it.
+  static unsigned long long done_mask = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+  if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return (int)e;
-    once = true;
+    if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
   }
 #ifdef F8_TRACE
   ConvParams pt = p;

@@ -413,6 +413,45 @@ __global__ __launch_bounds__(NT) void pad_input_kernel(const uint8_t *x, uint32_
   xp[gid] = v;
 }
 
+// The same re-layout for C = 3 (the RGB stem), four output pixels (one 16-byte store) per thread.
+// The 12 input bytes of the four pixels are fetched as the four aligned dwords that cover them
+// and shifted into place; dwords outside the tensor and pixels outside the image give zeros.
+// Needs x 4-byte aligned, B * H * W * 3 a multiple of 4 and Wp a multiple of 4.
+struct PadTiling {
+  FastDiv fd_g, fd_hp;     // by Wp / 4, by Hp
+};
+
+__global__ __launch_bounds__(NT) void pad_input3_kernel(const uint8_t *x, v4i *xp, int H, int W, int Hp, int Wp, int ph,
+                                                        int pw, const PadTiling tl, uint32_t total, long long x_bytes) {
+  const uint32_t gid = blockIdx.x * NT + threadIdx.x;
+  if (gid >= total) return;
+  const uint32_t t = tl.fd_g.div(gid);
+  const int g = (int)(gid - t * (uint32_t)(Wp >> 2));
+  const uint32_t b = tl.fd_hp.div(t);
+  const int i = (int)(t - b * (uint32_t)Hp);
+  const int ih = i - ph, iw0 = 4 * g - pw;
+  v4i out = {0, 0, 0, 0};
+  if ((unsigned)ih < (unsigned)H && iw0 > -4 && iw0 < W) {
+    const long long o = (((long long)b * H + ih) * W + iw0) * 3;       // first byte of pixel iw0 (may lie before the row)
+    const long long a = o & ~3ll;
+    const int sh = (int)(o & 3);
+    uint32_t w[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const long long ad = a + 4 * d;
+      w[d] = (ad >= 0 && ad + 4 <= x_bytes) ? *reinterpret_cast<const uint32_t *>(x + ad) : 0u;
+    }
+    const uint32_t u0 = __builtin_amdgcn_alignbyte(w[1], w[0], (uint32_t)sh);
+    const uint32_t u1 = __builtin_amdgcn_alignbyte(w[2], w[1], (uint32_t)sh);
+    const uint32_t u2 = __builtin_amdgcn_alignbyte(w[3], w[2], (uint32_t)sh);
+    const uint32_t px[4] = {u0 & 0x00ffffffu, __builtin_amdgcn_alignbyte(u1, u0, 3) & 0x00ffffffu,
+                            __builtin_amdgcn_alignbyte(u2, u1, 2) & 0x00ffffffu, u2 >> 8};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) out[k] = (unsigned)(iw0 + k) < (unsigned)W ? (int)px[k] : 0;
+  }
+  xp[gid] = out;
+}
+
 // w [N][R][S][C] -> wp [N][R][Sp][4], zeros in taps S..Sp-1 and channels C..3.
 __global__ __launch_bounds__(NT) void repack_weights_kernel(const int8_t *w, uint32_t *wp, int N, int R, int S, int C,
                                                             int Sp, long long total) {
@@ -525,6 +564,17 @@ int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp
                      hipStream_t stream) {
   const long long total = (long long)B * Hp * Wp;
   if (total <= 0) return 0;
+  const long long x_bytes = (long long)B * H * W * C;
+  if (C == 3 && (Wp & 3) == 0 && (x_bytes & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 3) == 0 &&
+      (reinterpret_cast<uintptr_t>(xp) & 15) == 0 && total / 4 < (1ll << 31)) {
+    PadTiling tl;
+    tl.fd_g = FastDiv((uint32_t)(Wp >> 2));
+    tl.fd_hp = FastDiv((uint32_t)Hp);
+    const uint32_t threads = (uint32_t)(total / 4);
+    hipLaunchKernelGGL(pad_input3_kernel, dim3((threads + NT - 1) / NT), dim3(NT), 0, stream,
+                       static_cast<const uint8_t *>(x), static_cast<v4i *>(xp), H, W, Hp, Wp, ph, pw, tl, threads, x_bytes);
+    return (int)hipGetLastError();
+  }
   hipLaunchKernelGGL(pad_input_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, static_cast<const uint8_t *>(x),
                      static_cast<uint32_t *>(xp), B, H, W, C, Hp, Wp, ph, pw, total);
   return (int)hipGetLastError();

@@ -260,7 +260,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
         sm.on = true;
         sm.Sp = (L.S + 3) / 4 * 4;
         sm.Hp = (g.P - 1) * g.sh + g.R;
-        sm.Wp = (g.Q - 1) * g.sw + sm.Sp;
+        sm.Wp = ((g.Q - 1) * g.sw + sm.Sp + 3) / 4 * 4;     // whole 16-byte groups of pixels per row
         sm.x_bytes_per_image = (size_t)sm.Hp * sm.Wp * 4;
         sm.w_off = c->const_bytes;
         c->const_bytes += round256((size_t)L.Cout * g.R * sm.Sp * 4);
