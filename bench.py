@@ -118,7 +118,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=256)
-    ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18", "mobilenetv2"])
+    ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18", "mobilenetv2", "mobilenetv1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the chain eagerly instead of replaying a HIP graph")
     ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
@@ -148,8 +148,10 @@ def main():
         x, net = wl.config4(batch=args.batch)
     elif args.net == "resnet18":
         x, net = wl.config3(batch=args.batch)
-    else:
+    elif args.net == "mobilenetv2":
         x, net = wl.mobilenet_v2_forward(batch=args.batch)
+    else:
+        x, net = wl.mobilenet_v1_forward(batch=args.batch)
     B = x.shape[0]
     xt = torch.from_numpy(x).to("cuda")
     chain = f8.Chain(net).prepare(B)
@@ -207,12 +209,12 @@ def main():
     total_ops = sum(2.0 * L.macs_per_image * B for L in net.layers)
     rec = {
         "metric": "images/s, fixed-point %s forward (int8 conv on MFMA + shift/clip epilogue), batch %d, 1 GPU"
-                  % ({"resnet50": "ResNet-50", "resnet18": "ResNet-18", "mobilenetv2": "MobileNetV2"}[args.net], B),
+                  % ({"resnet50": "ResNet-50", "resnet18": "ResNet-18", "mobilenetv2": "MobileNetV2", "mobilenetv1": "MobileNetV1"}[args.net], B),
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: full %s fixed-point forward, batch %d, 224x224x3, seeded FL per layer"
-                               % ({"resnet50": "configs[4]", "resnet18": "configs[3]", "mobilenetv2": "extra"}[args.net],
+                               % ({"resnet50": "configs[4]", "resnet18": "configs[3]", "mobilenetv2": "extra", "mobilenetv1": "extra"}[args.net],
                                   net.name, B),
                    "global_batch": B, "input": "224x224x3 int8", "layers": len(net.layers)},
         "whole_net_TOPS": total_ops / (dt / args.steps) / 1e12,

@@ -355,6 +355,28 @@ def mobilenet_v2(rng, hw=224, classes=1000, clip_draw=True):
     return b.net
 
 
+def mobilenet_v1(rng, hw=224, classes=1000, clip_draw=True):
+    """MobileNetV1 body in fixed point: 3x3/2 stem, 13 depthwise-separable blocks (3x3 depthwise,
+    1x1 pointwise, each followed by the unsigned quantiser), global pool, classifier."""
+    b = _NetBuilder("mobilenet_v1", rng, hw, 3, "s8", 5, (5, 9), (2, 6), clip_draw)
+    t = b.conv("stem", 0, 32, 3, 2, 1)
+    cfg = ((64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1), (512, 1), (512, 1), (512, 1),
+           (512, 1), (1024, 2), (1024, 1))
+    for i, (c, stride) in enumerate(cfg):
+        t = b.dwconv("b%d.dw" % (i + 1), t, 3, stride, 1)
+        t = b.conv("b%d.pw" % (i + 1), t, c, 1, 1, 0)
+    t = b.gpool("gpool", t)
+    b.conv("fc", t, classes, 1, 1, 0, raw=True)
+    return b.net
+
+
+def mobilenet_v1_forward(seed=None, batch=64, hw=224):
+    """Whole fixed-point MobileNetV1 forward (beyond the five baseline configs)."""
+    rng = np.random.default_rng(seed_of(6) if seed is None else seed)
+    x = _resnet_input(rng, batch, hw)
+    return x, mobilenet_v1(rng, hw)
+
+
 def mobilenet_v2_forward(seed=None, batch=64, hw=224):
     """Whole fixed-point MobileNetV2 forward (beyond the five baseline configs)."""
     rng = np.random.default_rng(seed_of(5) if seed is None else seed)

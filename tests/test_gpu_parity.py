@@ -147,8 +147,14 @@ def test_mobilenet_v2_forward(oracle):
     assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
 
 
+def test_mobilenet_v1_forward(oracle):
+    x, net = wl.mobilenet_v1_forward(batch=32)                      # 224x224x3
+    out = check_network(oracle, x, net, [0, 1, 15, 16, 30, 31], "mobilenet_v1")
+    assert out.shape == (32, 1, 1, 1000) and out.dtype == torch.int32
+
+
 def test_small_networks_full_compare(oracle):
-    for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3)):
+    for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3), (wl.mobilenet_v1_forward, 2)):
         x, net = cfg(batch=batch, hw=64)
         check_network(oracle, x, net, list(range(batch)), net.name + " 64x64")
 
