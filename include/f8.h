@@ -159,6 +159,12 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
 /* With keep_all != 0 no two tensors share memory (bigger workspace, every intermediate
  * can be inspected).  Call before f8_chain_workspace_bytes. */
 f8_status f8_chain_set_keep_all(f8_chain *c, int keep_all);
+/* Inverted-residual blocks (1x1 dense, 3x3 depthwise stride 1 pad 1, 1x1 dense, optional shortcut
+ * from the block input; MobileNetV2, paper Sec. 5 and Appx) whose intermediate tensors have no other
+ * reader can run as one kernel that keeps them on chip.  Same results; those tensors are then not
+ * available through f8_chain_tensor.  Off by default (fusion = 1 switches it on; never used with
+ * keep_all).  Call before f8_chain_workspace_bytes. */
+f8_status f8_chain_set_fusion(f8_chain *c, int fusion);
 void f8_chain_destroy(f8_chain *c);
 
 /* Measurement aids for the chain (not on the hot path).

@@ -100,6 +100,16 @@ def test_config2_mbv2_block(oracle, with_residual):
     assert_same(out.cpu().numpy(), want[net.layers[-1].dst], "config2 chain")
     for L in net.layers[:-1]:
         assert_same(chain.tensor(L.dst).cpu().numpy(), want[L.dst], "config2 chain " + L.name)
+    # with fusion on the block runs as one kernel: same bits, no intermediates
+    fused = f8.Chain(net, fusion=True).prepare(x.shape[0])
+    assert fused.layer_info(0, x.shape[0])[0] == "block_fused"
+    out2 = fused.run(torch.from_numpy(x).to(DEV))
+    torch.cuda.synchronize()
+    assert_same(out2.cpu().numpy(), want[net.layers[-1].dst], "config2 fused block")
+    assert fused.tensor(net.layers[0].dst) is None
+    plain = f8.Chain(net).prepare(x.shape[0])
+    assert plain.layer_info(0, x.shape[0])[0] != "block_fused"
+    assert torch.equal(plain.run(torch.from_numpy(x).to(DEV)), out2)
 
 
 # ------------------------------------------------------------------------- whole networks
@@ -123,6 +133,12 @@ def check_network(oracle, x, net, oracle_images, what):
     torch.cuda.synchronize()
     assert torch.equal(a, out) and torch.equal(b, out), what + " lean plan / rerun"
     assert lean.workspace_bytes(x.shape[0]) < chain.workspace_bytes(x.shape[0])
+    # fused inverted-residual blocks (where the network has any): the same logits again
+    fused = f8.Chain(net, fusion=True).prepare(x.shape[0])
+    if any(fused.layer_info(i, x.shape[0])[0] == "block_fused" for i in range(len(net.layers))):
+        c = fused.run(xt)
+        torch.cuda.synchronize()
+        assert torch.equal(c, out), what + " fused blocks"
     return out
 
 
