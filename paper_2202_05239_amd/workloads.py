@@ -446,3 +446,51 @@ def random_conv_case(rng, B, H, W, Cin, Cout, R, S, stride, pad, x_type="u8", y_
             res = rng.integers(-2 ** 20, 2 ** 20, size=shape, dtype=np.int32)
         L.res = 0
     return x, L, res
+
+
+# ----------------------------------------------------------------------------- floating-point side
+# Inputs of the steps upstream of the integer layers: tensors to quantise, Gaussian samples of
+# the toy experiment, and the trained-model quantities of a Conv-BN block.  Drawn values only.
+
+def fp_tensor(seed, n, std=1.0, mean=0.0):
+    """n float32 values ~ N(mean, std)."""
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(n) * std + mean).astype(np.float32)
+
+
+def toy_samples(seed=None, n=10000):
+    """The unit-variance zero-mean Gaussian samples of the toy experiment (scaled by the caller
+    to each standard deviation), float32."""
+    rng = np.random.default_rng(seed_of(7) if seed is None else seed)
+    return rng.standard_normal(n).astype(np.float32)
+
+
+@dataclass
+class FpBlock:
+    """Floating-point quantities of one Conv-BN block: W [Cout][K] (K = R*S*Cin flattened in
+    the integer layers' weight order), the BN scale gamma, shift beta, running mean mu and
+    running standard deviation sigma, the clipping levels and fractional lengths of its input
+    quantiser (alpha_in, fl_in) and of its child's (alpha_out, fl_out)."""
+    W: np.ndarray
+    gamma: np.ndarray
+    beta: np.ndarray
+    mu: np.ndarray
+    sigma: np.ndarray
+    alpha_in: float
+    fl_in: int
+    alpha_out: float
+    fl_out: int
+
+
+def fp_conv_bn_block(seed, cout, k):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal((cout, k)) * np.sqrt(2.0 / k)).astype(np.float32)
+    gamma = rng.uniform(0.4, 1.6, cout).astype(np.float32)
+    gamma *= rng.choice(np.array([-1.0, 1.0], np.float32), cout, p=[0.1, 0.9])
+    beta = (rng.standard_normal(cout) * 0.3).astype(np.float32)
+    mu = (rng.standard_normal(cout) * 0.5).astype(np.float32)
+    sigma = rng.uniform(0.5, 2.0, cout).astype(np.float32)
+    alpha_in = float(np.float32(rng.uniform(2.0, 8.0)))
+    alpha_out = float(np.float32(rng.uniform(2.0, 8.0)))
+    return FpBlock(W, gamma, beta, mu, sigma, alpha_in, int(rng.integers(3, 7)), alpha_out,
+                   int(rng.integers(3, 7)))
