@@ -184,6 +184,84 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
 f8_status f8_chain_profile(f8_chain *c, const void *x, void *out, void *workspace, int batch,
                            void *stream, int repeats, float *layer_ms);
 
+/* ---- upstream of the integer layers: quantisers on real tensors, fractional-length choice,
+ *      Conv-BN folding.  All tensors are device pointers to float32 unless said otherwise; every
+ *      call only enqueues kernels on `stream` and allocates nothing.  `round` is round half up,
+ *      as in the integer layers.  WL = 8 throughout. ---- */
+
+/* Eq. 2 (unsigned, codes 0..255, 0 <= fl <= 8) and Eq. 9 (signed, codes -127..127, 0 <= fl <= 7):
+ *   y[i] = 2^-fl * round(clip(x[i] * 2^fl, lo, hi)).
+ * Exact in float32 (a power-of-two scaling, a clip, a rounding of a value below 2^8).  A NaN takes
+ * the lower bound.  x and y may be the same buffer.  n = 0 is a no-op.  F8_ERR_FL for fl outside
+ * the format's range, F8_ERR_ALIGN for pointers that are not 4-byte aligned (16-byte aligned
+ * pointers take the vector path). */
+f8_status f8_fix_quant_f32(const float *x, float *y, size_t n, int fl, int is_signed, void *stream);
+/* The integer inside Eq. 2 / Eq. 9, as one byte per element (uint8 or int8): the input format of
+ * the integer layers. */
+f8_status f8_fix_quant_code(const float *x, void *q, size_t n, int fl, int is_signed, void *stream);
+/* Eq. 3 with M = 255:  y = k_out * round(k_in * clip(x, 0, alpha)),  k_in = fl32(255 / alpha),
+ * k_out = fl32(alpha / 255), every operation in float32 in that order.  alpha must be finite and
+ * positive (F8_ERR_CLIP). */
+f8_status f8_pact_f32(const float *x, float *y, size_t n, float alpha, void *stream);
+/* Eq. 4: the same function written through the unsigned fix_quant,
+ *   y = eta * fix_quant(x / eta),  eta = fl32(f8_eta_fix(alpha, fl)),
+ * division, quantiser and product each in float32. */
+f8_status f8_pact_fix_f32(const float *x, float *y, size_t n, float alpha, int fl, void *stream);
+/* Eq. 5 (host): the fix scaling factor 2^fl * alpha / 255. */
+double f8_eta_fix(double alpha, int fl);
+/* Eq. 1 (host): floor(log2(40 / sigma)) for a signed tensor, floor(log2(70 / sigma)) for an
+ * unsigned one, kept inside 0..7 / 0..8; sigma <= 0 (or NaN) gives the largest.  For an unsigned
+ * (rectified) tensor sigma is that of the values before the rectifier (Sec. 3.1). */
+int f8_opt_fl(double sigma, int is_signed);
+
+/* Device scratch every reduction below needs: this many doubles, 8-byte aligned, contents
+ * irrelevant before and after; calls that run concurrently need one each. */
+#define F8_STATS_WORK_DOUBLES 2048
+typedef struct {
+  double mean, std;                 /* over all n elements; std is the population one (divide by n) */
+  int32_t fl_signed, fl_unsigned;   /* Eq. 1 applied to std */
+} f8_stats;
+/* Statistics of a tensor for the fractional-length rule (Eq. 1), accumulated in fp64 about the
+ * first element, in a fixed order (the result does not change from run to run).  `stats` is a
+ * device pointer, written by the last kernel of the call.  n = 0 gives mean 0, std 0. */
+f8_status f8_tensor_stats_f32(const float *x, size_t n, f8_stats *stats, double *work, void *stream);
+/* The toy experiment of Sec. 3.1 (and the appendix on the statistical analysis) for one format:
+ *   out[0] = sum |v - fix_quant(v)|,  out[1] = sum |v|,  out[2] = out[0] / out[1],
+ * with v = x for the signed format and v = max(x, 0) for the unsigned one; out is a device
+ * pointer to three doubles; sums in fp64 in a fixed order.  out[2] is NaN when every v is 0. */
+f8_status f8_quant_error_f32(const float *x, size_t n, int fl, int is_signed, double *out, double *work,
+                             void *stream);
+
+/* Folding of one Conv-BN block into the integer layer's parameters (Eq. 6, Sec. 4.3).
+ *   w      [cout][k] float32, k = R*S*Cin in the integer layer's weight order (k = R*S for a
+ *          depthwise layer stored [C][R*S]; transpose to [R][S][C] is the caller's)
+ *   gamma, beta, mu, sigma   [cout] float32: BN scale, shift, running mean, running standard
+ *          deviation (sqrt(var + eps), formed by the caller).  A layer without BN passes
+ *          gamma = sigma = 1, mu = 0, beta = its bias.
+ *   eta_in, eta_out   fix scaling factors (Eq. 5) of this block's input quantiser and of its
+ *          child's (the master child's where there are several); 1 for a tensor quantised by
+ *          fix_quant directly
+ *   fl_x   fractional length of the input activation codes
+ *   fl_w   >= 0: fractional length of the weights; < 0: choose it by Eq. 1 from the standard
+ *          deviation of the whole effective weight tensor (then `stats` must be given)
+ * Computes, in fp64 with every operation rounded on its own and in this order,
+ *   g_i = gamma_i / sigma_i,   scale_i = g_i * (eta_in / eta_out),   W_eff = w * scale_i,
+ *   b_eff_i = (beta_i - g_i * mu_i) / eta_out,
+ *   wq = round(clip(W_eff * 2^fl_w, -127, 127))             (Eq. 9, int8 [cout][k])
+ *   bq = round(b_eff * 2^(fl_x + fl_w)) saturated to int32  (the accumulator's format)
+ * and, if `stats` is not NULL, the statistics of W_eff with the chosen fl_w in stats->fl_signed.
+ * wq, bq, stats and work are device pointers; work holds f8_fold_work_doubles(cout) doubles.
+ * cout * k must stay below 2^31 (F8_ERR_SHAPE); eta must be finite and positive (F8_ERR_CLIP). */
+typedef struct {
+  int32_t cout, k;
+  double eta_in, eta_out;
+  int32_t fl_x, fl_w;
+} f8_fold_desc;
+size_t f8_fold_work_doubles(int cout);
+f8_status f8_fold_conv_bn(const float *w, const float *gamma, const float *beta, const float *mu,
+                          const float *sigma, const f8_fold_desc *d, int8_t *wq, int32_t *bq,
+                          f8_stats *stats, double *work, void *stream);
+
 /* ---- helpers (host side, set-up only) ---- */
 
 /* A PACT clipping level alpha (Eq. 3) expressed in output LSBs for fractional length

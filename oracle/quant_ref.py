@@ -89,7 +89,14 @@ def opt_fl(sigma, is_signed, wl=8):
     ratio = (40.0 if is_signed else 70.0) / sigma
     if math.isinf(ratio):
         return top
-    return int(min(max(math.floor(math.log2(ratio)), 0), top))
+    k = math.floor(math.log2(ratio))
+    # log2 of a value one rounding step below a power of two may come back as the integer
+    # itself; the floor is taken of the exact logarithm
+    if 2.0 ** k > ratio:
+        k -= 1
+    elif 2.0 ** (k + 1) <= ratio:
+        k += 1
+    return int(min(max(k, 0), top))
 
 
 def rel_quant_error(x, fl, is_signed, wl=8):

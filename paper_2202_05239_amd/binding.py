@@ -26,7 +26,10 @@ EXPORTS = [
     "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
     "f8_clip_from_alpha", "f8_status_str", "f8_release_scratch", "f8_abi_version", "f8_copy_bytes",
+    "f8_fix_quant_f32", "f8_fix_quant_code", "f8_pact_f32", "f8_pact_fix_f32", "f8_eta_fix", "f8_opt_fl",
+    "f8_tensor_stats_f32", "f8_quant_error_f32", "f8_fold_work_doubles", "f8_fold_conv_bn",
 ]
+F8_STATS_WORK_DOUBLES = 2048
 
 
 class F8Error(RuntimeError):
@@ -50,6 +53,17 @@ class f8_layer_desc(ctypes.Structure):
                 ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32),
                 ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32),
                 ("q", f8_quant), ("w", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+class f8_stats(ctypes.Structure):
+    _fields_ = [("mean", ctypes.c_double), ("std", ctypes.c_double),
+                ("fl_signed", ctypes.c_int32), ("fl_unsigned", ctypes.c_int32)]
+
+
+class f8_fold_desc(ctypes.Structure):
+    _fields_ = [("cout", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("eta_in", ctypes.c_double), ("eta_out", ctypes.c_double),
+                ("fl_x", ctypes.c_int32), ("fl_w", ctypes.c_int32)]
 
 
 _lib = None
@@ -90,6 +104,19 @@ def lib():
     L.f8_status_str.restype = ctypes.c_char_p
     L.f8_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.f8_release_scratch.restype = None
+    sz, f32, f64 = ctypes.c_size_t, ctypes.c_float, ctypes.c_double
+    L.f8_fix_quant_f32.argtypes = [vp, vp, sz, i32, i32, vp]
+    L.f8_fix_quant_code.argtypes = [vp, vp, sz, i32, i32, vp]
+    L.f8_pact_f32.argtypes = [vp, vp, sz, f32, vp]
+    L.f8_pact_fix_f32.argtypes = [vp, vp, sz, f32, i32, vp]
+    L.f8_eta_fix.argtypes = [f64, i32]
+    L.f8_eta_fix.restype = f64
+    L.f8_opt_fl.argtypes = [f64, i32]
+    L.f8_tensor_stats_f32.argtypes = [vp, sz, vp, vp, vp]
+    L.f8_quant_error_f32.argtypes = [vp, sz, i32, i32, vp, vp, vp]
+    L.f8_fold_work_doubles.argtypes = [i32]
+    L.f8_fold_work_doubles.restype = sz
+    L.f8_fold_conv_bn.argtypes = [vp] * 5 + [ctypes.POINTER(f8_fold_desc)] + [vp] * 5
     L.f8_abi_version.restype = ctypes.c_int
     if L.f8_abi_version() != 1:
         raise RuntimeError("libf8.so has ABI version %d, binding expects 1" % L.f8_abi_version())
@@ -180,6 +207,96 @@ def f8_copy_bytes(src, dst):
     n = src.numel() * src.element_size()
     _check(lib().f8_copy_bytes(_ptr(src), _ptr(dst), n, _stream()), "f8_copy_bytes")
     return dst
+
+
+# ---- upstream of the integer layers (float32 tensors on the GPU) ------------------------------
+
+def _f32(t):
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("expected a contiguous float32 tensor")
+    return t
+
+
+def f8_fix_quant_f32(x, fl, is_signed, out=None):
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().f8_fix_quant_f32(_ptr(_f32(x)), _ptr(_f32(out)), x.numel(), int(fl), int(bool(is_signed)),
+                                  _stream()), "f8_fix_quant_f32")
+    return out
+
+
+def f8_fix_quant_code(x, fl, is_signed, out=None):
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int8 if is_signed else torch.uint8, device=x.device)
+    _check(lib().f8_fix_quant_code(_ptr(_f32(x)), _ptr(out), x.numel(), int(fl), int(bool(is_signed)),
+                                   _stream()), "f8_fix_quant_code")
+    return out
+
+
+def f8_pact_f32(x, alpha, out=None):
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().f8_pact_f32(_ptr(_f32(x)), _ptr(_f32(out)), x.numel(), float(alpha), _stream()), "f8_pact_f32")
+    return out
+
+
+def f8_pact_fix_f32(x, alpha, fl, out=None):
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().f8_pact_fix_f32(_ptr(_f32(x)), _ptr(_f32(out)), x.numel(), float(alpha), int(fl), _stream()),
+           "f8_pact_fix_f32")
+    return out
+
+
+def f8_eta_fix(alpha, fl):
+    return float(lib().f8_eta_fix(float(alpha), int(fl)))
+
+
+def f8_opt_fl(sigma, is_signed):
+    return int(lib().f8_opt_fl(float(sigma), int(bool(is_signed))))
+
+
+def _read_stats(buf):
+    """f8_stats out of a 24-byte device buffer (synchronises)."""
+    raw = buf.cpu().numpy().tobytes()
+    s = f8_stats.from_buffer_copy(raw)
+    return {"mean": s.mean, "std": s.std, "fl_signed": s.fl_signed, "fl_unsigned": s.fl_unsigned}
+
+
+def f8_tensor_stats_f32(x, work=None):
+    """Mean, population standard deviation and the Eq. 1 fractional lengths of x, as a dict
+    (reads the 24-byte result back, which synchronises)."""
+    if work is None:
+        work = torch.empty(F8_STATS_WORK_DOUBLES, dtype=torch.float64, device=x.device)
+    buf = torch.empty(24, dtype=torch.uint8, device=x.device)
+    _check(lib().f8_tensor_stats_f32(_ptr(_f32(x)), x.numel(), _ptr(buf), _ptr(work), _stream()),
+           "f8_tensor_stats_f32")
+    return _read_stats(buf)
+
+
+def f8_quant_error_f32(x, fl, is_signed, out=None, work=None):
+    """Device tensor of three doubles: sum |v - fix_quant(v)|, sum |v|, their ratio."""
+    if work is None:
+        work = torch.empty(F8_STATS_WORK_DOUBLES, dtype=torch.float64, device=x.device)
+    if out is None:
+        out = torch.empty(3, dtype=torch.float64, device=x.device)
+    _check(lib().f8_quant_error_f32(_ptr(_f32(x)), x.numel(), int(fl), int(bool(is_signed)), _ptr(out), _ptr(work),
+                                    _stream()), "f8_quant_error_f32")
+    return out
+
+
+def f8_fold_conv_bn(w, gamma, beta, mu, sigma, eta_in, eta_out, fl_x, fl_w=None, want_stats=True):
+    """Integer parameters of a folded Conv-BN block: (wq int8 like w, bq int32 [cout], stats dict or
+    None).  w is [cout][...]; fl_w=None lets the library choose it (Eq. 1), reported in
+    stats['fl_signed']."""
+    cout = w.shape[0]
+    k = w.numel() // max(cout, 1)
+    d = f8_fold_desc(cout, k, float(eta_in), float(eta_out), int(fl_x), -1 if fl_w is None else int(fl_w))
+    wq = torch.empty(w.shape, dtype=torch.int8, device=w.device)
+    bq = torch.empty(cout, dtype=torch.int32, device=w.device)
+    work = torch.empty(lib().f8_fold_work_doubles(cout), dtype=torch.float64, device=w.device)
+    buf = torch.empty(24, dtype=torch.uint8, device=w.device) if (want_stats or fl_w is None) else None
+    _check(lib().f8_fold_conv_bn(_ptr(_f32(w)), _ptr(_f32(gamma)), _ptr(_f32(beta)), _ptr(_f32(mu)),
+                                 _ptr(_f32(sigma)), ctypes.byref(d), _ptr(wq), _ptr(bq), _ptr(buf), _ptr(work),
+                                 _stream()), "f8_fold_conv_bn")
+    return wq, bq, (None if buf is None else _read_stats(buf))
 
 
 def out_hw(H, W, R, S, stride, pad):

@@ -159,3 +159,48 @@ def test_binding_refuses_to_run_without_library(monkeypatch):
     monkeypatch.setattr(f8, "LIB_PATH", "/nonexistent/libf8.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         f8.lib()
+
+
+def test_quant_tools_host_side():
+    """Eq. 1 and Eq. 5 on the host against the oracle, and argument validation of the device
+    entry points (every call below fails before anything is launched)."""
+    from oracle import quant_ref as qr
+    L = f8.lib()
+    rng = np.random.default_rng(5)
+    sig = np.concatenate([10 ** rng.uniform(-4, 4, 2000), [40.0, 20.0, 70.0, 35.0, 0.3125, 0.0,
+                                                            np.nextafter(20.0, 30.0), np.nextafter(20.0, 0.0), 1e-320, 1e308]])
+    for s in sig:
+        for is_signed in (True, False):
+            assert f8.f8_opt_fl(s, is_signed) == qr.opt_fl(float(s), is_signed), (s, is_signed)
+    assert f8.f8_opt_fl(float("nan"), True) == 7
+    for alpha, fl in ((3.0, 4), (255.0, 0), (0.7, 8), (6.0, 1)):
+        assert f8.f8_eta_fix(alpha, fl) == qr.eta_fix(alpha, fl)
+    assert L.f8_fix_quant_f32(FAKE, FAKE, 16, 9, 0, None) == 3
+    assert L.f8_fix_quant_f32(FAKE, FAKE, 16, 8, 1, None) == 3
+    assert L.f8_fix_quant_f32(FAKE, FAKE, 16, -1, 0, None) == 3
+    assert L.f8_fix_quant_f32(None, FAKE, 16, 4, 0, None) == 1
+    assert L.f8_fix_quant_f32(None, None, 0, 4, 0, None) == 0           # empty: no-op
+    assert L.f8_fix_quant_f32(ctypes.c_void_p(0x1002), FAKE, 16, 4, 0, None) == 7
+    assert L.f8_fix_quant_code(FAKE, None, 16, 4, 0, None) == 1
+    assert L.f8_pact_f32(FAKE, FAKE, 16, 0.0, None) == 4
+    assert L.f8_pact_f32(FAKE, FAKE, 16, float("inf"), None) == 4
+    assert L.f8_pact_fix_f32(FAKE, FAKE, 16, 2.0, 9, None) == 3
+    assert L.f8_tensor_stats_f32(FAKE, 16, None, FAKE, None) == 1
+    assert L.f8_tensor_stats_f32(FAKE, 16, FAKE, None, None) == 1
+    assert L.f8_quant_error_f32(FAKE, 16, 8, 1, FAKE, FAKE, None) == 3
+    assert L.f8_quant_error_f32(FAKE, 16, 3, 1, None, FAKE, None) == 1
+    assert L.f8_fold_work_doubles(64) == 2048 + 128
+
+    def fold(cout=8, k=16, eta_in=1.0, eta_out=1.0, fl_x=4, fl_w=-1, w=FAKE, stats=FAKE):
+        d = f8.f8_fold_desc(cout, k, eta_in, eta_out, fl_x, fl_w)
+        return L.f8_fold_conv_bn(w, FAKE, FAKE, FAKE, FAKE, ctypes.byref(d), FAKE, FAKE, stats, FAKE, None)
+    assert fold(cout=-1) == 2
+    assert fold(cout=65536, k=65536) == 2
+    assert fold(cout=0) == 0
+    assert fold(w=None) == 1
+    assert fold(stats=None) == 1                      # Eq. 1 needs the statistics buffer
+    assert fold(fl_w=8) == 3
+    assert fold(fl_x=9) == 3
+    assert fold(eta_out=0.0) == 4
+    assert fold(eta_in=float("inf")) == 4
+    assert L.f8_fold_conv_bn(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, None) == 1
