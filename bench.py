@@ -6,6 +6,7 @@ bottleneck) over a batch of 256 seeded synthetic 224x224x3 images that already s
 global pool.  Prints ONE JSON line (see README / DESIGN for the fields).
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -112,6 +113,54 @@ def copy_calibration():
     print(json.dumps({"copy_bytes_per_launch": n}))
 
 
+def quant_tools_figures(repeats=10):
+    """Throughput of the steps upstream of the integer layers on a 1 GiB float32 tensor
+    (2^28 elements ~ N(0, 1)) and of the folding of a 2048 x 4608 Conv-BN block, timed with
+    HIP events on the launch stream; algorithmic bytes = every input element read once, every
+    output element written once."""
+    import torch
+    from paper_2202_05239_amd import binding as f8
+    L = f8.lib()
+    n = 1 << 28
+    x = torch.randn(n, device="cuda")
+    y = torch.empty_like(x)
+    q = torch.empty(n, dtype=torch.uint8, device="cuda")
+    work = torch.empty(f8.F8_STATS_WORK_DOUBLES + 2 * 2048, dtype=torch.float64, device="cuda")
+    out = torch.empty(3, dtype=torch.float64, device="cuda")
+    stats = torch.empty(24, dtype=torch.uint8, device="cuda")
+    cout, k = 2048, 4608
+    w = x[:cout * k].view(cout, k)
+    wq = torch.empty((cout, k), dtype=torch.int8, device="cuda")
+    bq = torch.empty(cout, dtype=torch.int32, device="cuda")
+    g, beta, mu, sg = (torch.rand(cout, device="cuda") + 0.5 for _ in range(4))
+    s = f8._stream()
+    desc = f8.f8_fold_desc(cout, k, 0.3, 0.2, 4, -1)
+    rows = [
+        ("fix_quant_f32 (Eq. 2/9)", 8 * n, lambda: f8.f8_fix_quant_f32(x, 5, True, out=y)),
+        ("fix_quant_code (Eq. 2/9)", 5 * n, lambda: f8.f8_fix_quant_code(x, 5, False, out=q)),
+        ("pact_f32 (Eq. 3)", 8 * n, lambda: f8.f8_pact_f32(x, 4.7, out=y)),
+        ("pact_fix_f32 (Eq. 4)", 8 * n, lambda: f8.f8_pact_fix_f32(x, 4.7, 5, out=y)),
+        ("tensor_stats_f32 (Eq. 1)", 4 * n, lambda: L.f8_tensor_stats_f32(f8._ptr(x), n, f8._ptr(stats), f8._ptr(work), s)),
+        ("quant_error_f32 (toy experiment)", 4 * n, lambda: f8.f8_quant_error_f32(x, 5, True, out=out, work=work)),
+        ("fold_conv_bn 2048x4608 (Eq. 6, FL_w by Eq. 1)", 9 * cout * k + 24 * cout,
+         lambda: L.f8_fold_conv_bn(f8._ptr(w), f8._ptr(g), f8._ptr(beta), f8._ptr(mu), f8._ptr(sg), ctypes.byref(desc),
+                                   f8._ptr(wq), f8._ptr(bq), f8._ptr(stats), f8._ptr(work), s)),
+    ]
+    res = {}
+    for name, nbytes, fn in rows:
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(repeats):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / repeats
+        res[name] = {"us": us, "alg_MB": nbytes / 1e6, "alg_GBs": nbytes / us / 1e3,
+                     "pct_hbm_peak": 100 * nbytes / us / 1e3 / PEAK_HBM_GBS}
+    print(json.dumps({"quant_tools": res}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +175,8 @@ def main():
     ap.add_argument("--no-single-layer", action="store_true", help="skip the configs[1] / configs[2] layer figures")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (reference for the traffic counters)")
+    ap.add_argument("--quant-tools", action="store_true",
+                    help="only time the steps upstream of the integer layers (quantisers, statistics, folding)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
@@ -134,6 +185,9 @@ def main():
 
     if args.copy_calibration:
         copy_calibration()
+        return
+    if args.quant_tools:
+        quant_tools_figures()
         return
 
     import torch

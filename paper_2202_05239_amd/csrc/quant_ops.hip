@@ -16,6 +16,10 @@
 #include "../../include/f8.h"
 #include "f8_device.h"
 
+// Every product below is rounded before it is used: a multiply fused into a following
+// subtraction would let an unrounded product decide a tie differently from the stated steps.
+#pragma clang fp contract(off)
+
 namespace f8 {
 namespace {
 
