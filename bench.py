@@ -167,7 +167,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=256)
-    ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18", "mobilenetv2", "mobilenetv1"])
+    ap.add_argument("--net", default="resnet50", choices=["resnet50", "resnet18", "mobilenetv2", "mobilenetv1", "resnet50_private_fl"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the chain eagerly instead of replaying a HIP graph")
     ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
@@ -205,6 +205,8 @@ def main():
         x, net = wl.config3(batch=args.batch)
     elif args.net == "mobilenetv2":
         x, net = wl.mobilenet_v2_forward(batch=args.batch)
+    elif args.net == "resnet50_private_fl":
+        x, net = wl.resnet50_private_fl(batch=args.batch)
     else:
         x, net = wl.mobilenet_v1_forward(batch=args.batch)
     B = x.shape[0]
@@ -269,7 +271,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: full %s fixed-point forward, batch %d, 224x224x3, seeded FL per layer"
-                               % ({"resnet50": "configs[4]", "resnet18": "configs[3]", "mobilenetv2": "extra", "mobilenetv1": "extra"}[args.net],
+                               % ({"resnet50": "configs[4]", "resnet18": "configs[3]"}.get(args.net, "extra"),
                                   net.name, B),
                    "global_batch": B, "input": "224x224x3 int8", "layers": len(net.layers)},
         "whole_net_TOPS": total_ops / (dt / args.steps) / 1e12,

@@ -92,6 +92,25 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
                           int stride_h, int stride_w, int pad_h, int pad_w,
                           const f8_quant *q, void *stream);
 
+/* A second 8-bit format for the same accumulator (Sec. 4.3, "clipping-level sharing": the
+ * children of one layer keep private fractional lengths, so the parent's 32-bit result is
+ * quantised once per child format). */
+typedef struct {
+  int32_t fl_y;               /* fractional length of the second output                    */
+  int32_t clip_lo, clip_hi;   /* its clip bounds in its own LSBs, same rules as f8_quant   */
+  int32_t y_type;             /* F8_U8 or F8_S8                                            */
+} f8_requant2;
+
+/* f8_conv2d_fixed with two outputs: y as before, and
+ *   y2 = clip(shift_round(A, fl_x + fl_w - q2->fl_y), q2->clip_lo, q2->clip_hi)
+ * from the same A (bias and residual included), each with its own single rounding.  Both
+ * outputs are 8-bit (q->y_type must not be F8_S32); y2 has y's shape, must not overlap y, x
+ * or the residual.  The second shift obeys the same limits as the first (F8_ERR_FL). */
+f8_status f8_conv2d_fixed_dual(const void *x, const int8_t *w, const int32_t *bias, void *y, void *y2,
+                               int B, int H, int W, int Cin, int Cout, int R, int S,
+                               int stride_h, int stride_w, int pad_h, int pad_w,
+                               const f8_quant *q, const f8_requant2 *q2, void *stream);
+
 /* Eq. 6 for a depthwise convolution (MobileNet V1/V2 layers of Sec. 5): K = R*S taps
  * per channel, no sum across channels.  x NHWC [B][H][W][C], w [R][S][C] int8,
  * bias [C] or NULL, y NHWC [B][P][Q][C]. */
@@ -132,6 +151,9 @@ typedef struct {
   f8_quant q;
   const int8_t *w;                  /* CONV [Cout][R][S][Cin]; DWCONV [R][S][C]; else NULL */
   const int32_t *bias;              /* [Cout] or NULL                                   */
+  int32_t dst2;                     /* CONV only: id of a second output tensor in format q2
+                                       (see f8_conv2d_fixed_dual), or <= 0 for none     */
+  f8_requant2 q2;
 } f8_layer_desc;
 
 typedef struct f8_chain f8_chain;

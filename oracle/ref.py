@@ -171,6 +171,23 @@ def global_pool_fixed(x, q):
 # whole-network runner: one oracle call per layer, in execution order
 # ---------------------------------------------------------------------------------
 
+class _SecondFormat:
+    """The quantisation record of a layer with its output format replaced by the second one."""
+
+    def __init__(self, L):
+        self.fl_x, self.fl_w, self.x_type = L.fl_x, L.fl_w, L.x_type
+        self.res_type, self.fl_res = L.res_type, L.fl_res
+        self.fl_y, self.clip_lo, self.clip_hi, self.y_type = L.fl_y2, L.clip_lo2, L.clip_hi2, L.y2_type
+
+
+def conv2d_fixed_dual(x, w, bias, q, stride=(1, 1), pad=(0, 0), res=None):
+    """A layer with two output formats (paper Sec. 4.3, children with private fractional
+    lengths): by definition each output is the layer evaluated with that format, so the oracle
+    simply evaluates it twice."""
+    return (conv2d_fixed(x, w, bias, q, stride, pad, res),
+            conv2d_fixed(x, w, bias, _SecondFormat(q), stride, pad, res))
+
+
 def run_layer(L, x, res=None):
     """Run one layer description on host arrays through the C oracle."""
     if L.op == "conv":
@@ -185,6 +202,15 @@ def run_layer(L, x, res=None):
     raise ValueError(L.op)
 
 
+def _SecondFormat_layer(L):
+    """Copy of a layer description whose output format is the second one."""
+    import copy
+    M = copy.copy(L)
+    M.fl_y, M.clip_lo, M.clip_hi, M.y_type = L.fl_y2, L.clip_lo2, L.clip_hi2, L.y2_type
+    M.dst2 = -1
+    return M
+
+
 def run_network(net, x, keep_all=False):
     """Evaluate the layer list `net.layers` on the batch x (NHWC numpy array).
 
@@ -195,6 +221,8 @@ def run_network(net, x, keep_all=False):
     for L in net.layers:
         res = t[L.res] if L.res >= 0 else None
         t[L.dst] = run_layer(L, t[L.src], res)
+        if getattr(L, "dst2", -1) > 0:
+            t[L.dst2] = run_layer(_SecondFormat_layer(L), t[L.src], res)
     return t if keep_all else t[net.layers[-1].dst]
 
 

@@ -21,7 +21,7 @@ TORCH_DTYPE = {"u8": torch.uint8, "s8": torch.int8, "s32": torch.int32,
                F8_U8: torch.uint8, F8_S8: torch.int8, F8_S32: torch.int32}
 
 EXPORTS = [
-    "f8_gemm_fixed", "f8_conv2d_fixed", "f8_dwconv_fixed", "f8_maxpool", "f8_global_pool_fixed",
+    "f8_gemm_fixed", "f8_conv2d_fixed", "f8_conv2d_fixed_dual", "f8_dwconv_fixed", "f8_maxpool", "f8_global_pool_fixed",
     "f8_chain_create", "f8_chain_workspace_bytes", "f8_chain_prepare", "f8_chain_run",
     "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
@@ -46,13 +46,19 @@ class f8_quant(ctypes.Structure):
                 ("res", ctypes.c_void_p), ("res_type", ctypes.c_int32), ("fl_res", ctypes.c_int32)]
 
 
+class f8_requant2(ctypes.Structure):
+    _fields_ = [("fl_y", ctypes.c_int32), ("clip_lo", ctypes.c_int32), ("clip_hi", ctypes.c_int32),
+                ("y_type", ctypes.c_int32)]
+
+
 class f8_layer_desc(ctypes.Structure):
     _fields_ = [("op", ctypes.c_int32), ("src", ctypes.c_int32), ("dst", ctypes.c_int32),
                 ("res", ctypes.c_int32), ("Cin", ctypes.c_int32), ("Cout", ctypes.c_int32),
                 ("R", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32),
                 ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32),
-                ("q", f8_quant), ("w", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+                ("q", f8_quant), ("w", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("dst2", ctypes.c_int32), ("q2", f8_requant2)]
 
 
 class f8_stats(ctypes.Structure):
@@ -81,6 +87,7 @@ def lib():
     vp, i32, qp = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(f8_quant)
     L.f8_gemm_fixed.argtypes = [vp, vp, vp, vp, i32, i32, i32, qp, vp]
     L.f8_conv2d_fixed.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [qp, vp]
+    L.f8_conv2d_fixed_dual.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [qp, ctypes.POINTER(f8_requant2), vp]
     L.f8_dwconv_fixed.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [qp, vp]
     L.f8_maxpool.argtypes = [vp, vp] + [i32] * 11 + [vp]
     L.f8_global_pool_fixed.argtypes = [vp, vp, i32, i32, i32, i32, qp, vp]
@@ -118,8 +125,8 @@ def lib():
     L.f8_fold_work_doubles.restype = sz
     L.f8_fold_conv_bn.argtypes = [vp] * 5 + [ctypes.POINTER(f8_fold_desc)] + [vp] * 5
     L.f8_abi_version.restype = ctypes.c_int
-    if L.f8_abi_version() != 1:
-        raise RuntimeError("libf8.so has ABI version %d, binding expects 1" % L.f8_abi_version())
+    if L.f8_abi_version() != 2:
+        raise RuntimeError("libf8.so has ABI version %d, binding expects 2" % L.f8_abi_version())
     _lib = L
     return L
 
@@ -170,6 +177,25 @@ def f8_conv2d_fixed(x, w, bias, y, q, stride=(1, 1), pad=(0, 0), res=None):
                                  stride[0], stride[1], pad[0], pad[1], ctypes.byref(c), _stream()),
            "f8_conv2d_fixed")
     return y
+
+
+def make_requant2(q):
+    """f8_requant2 from a record with fl_y2, clip_lo2, clip_hi2, y2_type."""
+    c = f8_requant2()
+    c.fl_y, c.clip_lo, c.clip_hi, c.y_type = int(q.fl_y2), int(q.clip_lo2), int(q.clip_hi2), _TYPES[q.y2_type]
+    return c
+
+
+def f8_conv2d_fixed_dual(x, w, bias, y, y2, q, stride=(1, 1), pad=(0, 0), res=None):
+    """f8_conv2d_fixed with a second output y2 in the format q.fl_y2 / clip_lo2 / clip_hi2 / y2_type."""
+    B, H, W, Cin = x.shape
+    Cout, R, S, _ = w.shape
+    c = make_quant(q, res)
+    c2 = make_requant2(q)
+    _check(lib().f8_conv2d_fixed_dual(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(y2), B, H, W, Cin, Cout, R, S,
+                                      stride[0], stride[1], pad[0], pad[1], ctypes.byref(c), ctypes.byref(c2),
+                                      _stream()), "f8_conv2d_fixed_dual")
+    return y, y2
 
 
 def f8_dwconv_fixed(x, w, bias, y, q, stride=(1, 1), pad=(0, 0), res=None):
@@ -327,6 +353,9 @@ class Chain:
             if S.res >= 0:
                 d.q.res_type, d.q.fl_res = _TYPES[S.res_type], int(S.fl_res)
             d.w = d.bias = None
+            d.dst2 = getattr(S, "dst2", -1)
+            if d.dst2 > 0:
+                d.q2 = make_requant2(S)
             if S.w is not None:
                 wt = torch.from_numpy(S.w).contiguous().to(device)
                 self._keep.append(wt)

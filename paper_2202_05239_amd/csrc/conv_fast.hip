@@ -512,6 +512,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
               v[j] += RLEFT ? (r << d) : ((r + rhalf) >> (-d));
             }
           }
+          if (p.y2) {
+            // second format of the same accumulator (uniform branch): swap the rounding addend,
+            // shift (>= 0 on this path), clip; staged behind the first output's tile
+            const int sh2 = p.shift2, lo2 = p.lo2, hi2 = p.hi2, a2 = p.add2;
+            int u[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u[j] = requant<false>(v[j] + a2, sh2, lo2, hi2);
+            *reinterpret_cast<uint32_t *>(slot + BM * PITCH) = pack4(u[0], u[1], u[2], u[3]);
+          }
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = requant<NEG>(v[j], sh, lo, hi);
           *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
@@ -548,6 +557,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
           *reinterpret_cast<const uint32_t *>(epi + row * PITCH + pc * 4);
     }
   }
+  if (p.y2) {
+    uint8_t *y2 = static_cast<uint8_t *>(p.y2);
+    const uint8_t *epi2 = epi + BM * PITCH;
+    for (int idx = tid; idx < BM * CPR; idx += NT) {
+      const int row = idx / CPR, pc = idx - row * CPR;
+      const int m = m0 + row, n = n0 + pc * EV;
+      if (m < p.M && n < p.N) {
+        if (EV == 16) *reinterpret_cast<v4i *>(y2 + (size_t)m * p.N + n) =
+            *reinterpret_cast<const v4i *>(epi2 + row * PITCH + pc * 16);
+        else *reinterpret_cast<uint32_t *>(y2 + (size_t)m * p.N + n) =
+            *reinterpret_cast<const uint32_t *>(epi2 + row * PITCH + pc * 4);
+      }
+    }
+  }
   F8_TRACE_POINT(6);
 }
 
@@ -558,7 +581,10 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
   if (ntiles > 0x7fffffffLL) return (int)hipErrorInvalidValue;
   constexpr int stage_bytes = NSTAGE * (BM + BN) * BK;
   constexpr int epi_bytes = BM * (BN + 16);
-  constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  // a second output stages a second tile behind the first
+  constexpr int smem_max = stage_bytes > 2 * epi_bytes ? stage_bytes : 2 * epi_bytes;
+  const int need = p.y2 ? 2 * epi_bytes : epi_bytes;
+  const int smem = stage_bytes > need ? stage_bytes : need;
   auto k = conv_fast_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, MINB, EV, UT>;
   // Raising the dynamic LDS limit is per device and idempotent (racing callers set the same
   // value); remember which devices have it.
@@ -567,7 +593,7 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
   if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
   if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
     if (e != hipSuccess) return (int)e;
     if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
   }
@@ -632,8 +658,10 @@ bool conv_fast_applicable(const ConvParams &p) {
   if (p.y_type == T_S32)      // raw accumulators (logits): stored straight from the registers, no residual
     return !p.res && (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
   if (p.res && p.res_type == T_S32) return false;
-  uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res);
+  uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res) |
+                    reinterpret_cast<uintptr_t>(p.y2);
   if (ybits & 3) return false;
+  if (p.y2 && p.shift2 < 0) return false;
   return true;
 }
 
@@ -644,7 +672,8 @@ int conv_fast_variant(const ConvParams &p) {
   // (batch 64) layer shapes on MI355X.  Bigger tiles move fewer bytes from L2 into LDS per
   // multiply-accumulate but only pay off while there are enough of them to occupy 256 CUs:
   //  * narrow outputs, or too few 128 x 128 tiles: 128 x 64 (128-byte K steps when K is long);
-  //  * one K step (K <= 64): single-stage 128 x 128, four workgroups per CU;
+  //  * one K step (K <= 64): single-stage 128 x 128, four workgroups per CU; with two or more
+  //    128-wide column tiles (N >= 256) the three-stage ring's smaller occupancy measures faster;
   //  * long K with whole 128-byte lines per row: eight waves on 256 x 256, else on 256 x 128,
   //    else four waves on 128 x 128 with 128-byte K steps;
   //  * otherwise 128 x 128 with 64-byte K steps, a three-deep ring once K is long enough.
@@ -656,7 +685,7 @@ int conv_fast_variant(const ConvParams &p) {
   // the last 128-wide tile would be mostly padding (N = 144, 160, 192 ...): 64-wide tiles
   const int pad128 = (p.N + 127) / 128 * 128 - p.N, pad64 = (p.N + 63) / 64 * 64 - p.N;
   if (pad128 - pad64 >= 64 && pad128 * 5 > p.N) return p.K <= 64 ? 8 : (p.K >= 512 ? 16 : 3);
-  if (p.K <= 64) return t128 >= 1024 ? 10 : 3;
+  if (p.K <= 64) return t128 >= 1024 ? (p.N >= 256 ? 14 : 10) : 3;
   if (p.K <= 128) return t128 >= 1024 ? 2 : 3;
   if (p.K >= 1024 && lines) {
     if (p.N >= 256) {
@@ -671,7 +700,8 @@ int conv_fast_variant(const ConvParams &p) {
 const char *conv_fast_variant_name(int v) { return v >= 0 && v < N_VARIANTS ? kVariantNames[v] : "?"; }
 
 int launch_conv_fast(const ConvParams &p, hipStream_t stream) {
-  const uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res);
+  const uintptr_t ybits = reinterpret_cast<uintptr_t>(p.y) | reinterpret_cast<uintptr_t>(p.res) |
+                          reinterpret_cast<uintptr_t>(p.y2);
   const int ev = ((p.N & 15) == 0 && (ybits & 15) == 0) ? 16 : 4;
   switch (conv_fast_variant(p)) {
     case 0: return launch_fast_tile<256, 128, 2, 2, 64, 3, 2>(p, ev, stream);

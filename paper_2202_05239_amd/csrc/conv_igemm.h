@@ -19,6 +19,11 @@ struct ConvParams {
   uint32_t xor_mask;        // 0x80808080 for unsigned activations, 0 for signed
   int shift, lo, hi;        // requantisation
   int y_type, res_type, res_d;
+  // Optional second 8-bit output of the same accumulator: y2 = clip((A' + add2) >> shift2),
+  // where A' is the accumulator with the first output's rounding addend in it and add2 swaps
+  // that addend for the second one's.  y2 == nullptr: none.
+  void *y2;
+  int shift2, lo2, hi2, add2;
   int remap;                // 1: XCD-aware tile order
   // 64 bytes of zeros in device memory that stand in for padding taps and rows outside the
   // tensor (fast path).  If x and zero both lie within 4 GiB above lo_base, near = 1 and

@@ -241,6 +241,22 @@ __global__ __launch_bounds__(NT) void conv_igemm_kernel(const ConvParams p, cons
             if (n + i < p.N) yp[i] = v[i];
         }
       } else {
+        if (p.y2) {
+          // second format of the same accumulator: swap the rounding addend, shift, clip
+          int u[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            u[i] = p.shift2 >= 0 ? requant<false>(v[i] + p.add2, p.shift2, p.lo2, p.hi2)
+                                 : requant<true>(v[i] + p.add2, p.shift2, p.lo2, p.hi2);
+          uint8_t *yp2 = reinterpret_cast<uint8_t *>(p.y2) + o;
+          if (n_vec && (reinterpret_cast<uintptr_t>(p.y2) & 3) == 0) {
+            *reinterpret_cast<uint32_t *>(yp2) = pack4(u[0], u[1], u[2], u[3]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (n + i < p.N) yp2[i] = (uint8_t)u[i];
+          }
+        }
         if (p.shift >= 0) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) v[i] = requant<false>(v[i], p.shift, p.lo, p.hi);

@@ -27,6 +27,18 @@ f8_status check_quant(const f8_quant *q, bool allow_res) {
   return F8_OK;
 }
 
+f8_status check_requant2(const f8_quant &q, const f8_requant2 *q2) {
+  if (!q2) return F8_ERR_NULL;
+  if (q.y_type == F8_S32) return F8_ERR_DTYPE;
+  if (q2->y_type != F8_U8 && q2->y_type != F8_S8) return F8_ERR_DTYPE;
+  const int s = q.fl_x + q.fl_w - q2->fl_y;
+  if (s < -8 || s > 24) return F8_ERR_FL;
+  if (q2->clip_lo > q2->clip_hi) return F8_ERR_CLIP;
+  if (q2->y_type == F8_U8 && (q2->clip_lo < 0 || q2->clip_hi > 255)) return F8_ERR_CLIP;
+  if (q2->y_type == F8_S8 && (q2->clip_lo < -127 || q2->clip_hi > 127)) return F8_ERR_CLIP;
+  return F8_OK;
+}
+
 f8_status check_geom(Geom &g, bool depthwise) {
   if (g.B < 0 || g.H < 1 || g.W < 1 || g.Cin < 1 || g.Cout < 0 || g.R < 1 || g.S < 1 || g.sh < 1 ||
       g.sw < 1 || g.ph < 0 || g.pw < 0)
@@ -58,8 +70,17 @@ static int widest_vec(int C, const void *a, const void *b) {
 }
 
 f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
-                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream) {
+                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
+                       const f8_requant2 *q2, void *y2) {
   ConvParams p;
+  p.y2 = nullptr;
+  p.shift2 = p.lo2 = p.hi2 = p.add2 = 0;
+  if (q2 && y2) {
+    p.y2 = y2;
+    p.shift2 = q.fl_x + q.fl_w - q2->fl_y;
+    p.lo2 = q2->clip_lo; p.hi2 = q2->clip_hi;
+    p.add2 = (p.shift2 > 0 ? (1 << (p.shift2 - 1)) : 0) - rounding_addend(q);
+  }
   p.zero = static_cast<const uint8_t *>(zero);
   {
     const uintptr_t xa = reinterpret_cast<uintptr_t>(x), za = reinterpret_cast<uintptr_t>(zero);
@@ -105,6 +126,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
+  p.y2 = nullptr; p.shift2 = 0;
   p.near = 1;
   p.C = g.Cin; p.N = g.Cout; p.y_type = q.y_type; p.res_type = q.res_type;
   p.H = g.H; p.W = g.W; p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
@@ -227,6 +249,30 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
   return enqueue_conv(x, w, acc0, scratch, y, q->res, g, *q, s);
 }
 
+f8_status f8_conv2d_fixed_dual(const void *x, const int8_t *w, const int32_t *bias, void *y, void *y2, int B, int H,
+                               int W, int Cin, int Cout, int R, int S, int stride_h, int stride_w, int pad_h,
+                               int pad_w, const f8_quant *q, const f8_requant2 *q2, void *stream) {
+  if (!x || !w || !y || !y2) return F8_ERR_NULL;
+  f8_status st = check_quant(q, true);
+  if (st != F8_OK) return st;
+  st = check_requant2(*q, q2);
+  if (st != F8_OK) return st;
+  Geom g{B, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  st = check_geom(g, false);
+  if (st != F8_OK) return st;
+  st = check_align(bias, y, *q, q->res);
+  if (st != F8_OK) return st;
+  if (q->res == y || q->res == y2 || y == y2) return F8_ERR_UNSUPPORTED;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t *scratch = scratch_for(s, 64 + acc0_padded(Cout));
+  if (!scratch) return F8_ERR_DEVICE;
+  int32_t *acc0 = scratch + 64;
+  st = enqueue_fold(w, bias, acc0, g, *q, s);
+  if (st != F8_OK) return st;
+  return enqueue_conv(x, w, acc0, scratch, y, q->res, g, *q, s, q2, y2);
+}
+
 f8_status f8_gemm_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int M, int K, int N,
                         const f8_quant *q, void *stream) {
   if (M < 0 || K < 1 || N < 0) return (x && w && y) ? F8_ERR_SHAPE : F8_ERR_NULL;
@@ -317,6 +363,6 @@ f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream) 
   return launch_copy(src, dst, bytes, static_cast<hipStream_t>(stream)) == 0 ? F8_OK : F8_ERR_DEVICE;
 }
 
-int f8_abi_version(void) { return 1; }
+int f8_abi_version(void) { return 2; }
 
 }  // extern "C"

@@ -137,6 +137,12 @@ struct f8_chain {
       if (stem[li].on) stem[li].x_off_per_image = alloc(round256(stem[li].x_bytes_per_image));
       Tensor &d = tensors[layers[li].dst];
       if (!d.external) d.offset_per_image = alloc(round256(d.bytes_per_image));
+      if (layers[li].dst2 > 0) {
+        Tensor &d2 = tensors[layers[li].dst2];
+        d2.offset_per_image = alloc(round256(d2.bytes_per_image));
+        // never read: give the space back once this layer has run
+        if (!keep_all && d2.last_use < 0) release(d2.offset_per_image, round256(d2.bytes_per_image));
+      }
       if (keep_all) continue;
       if (stem[li].on) release(stem[li].x_off_per_image, round256(stem[li].x_bytes_per_image));
       const int ids[2] = {layers[li].src, layers[li].res};
@@ -228,7 +234,9 @@ struct f8_chain {
           if (e != 0) return F8_ERR_DEVICE;
           src = xp;
         }
-        return enqueue_conv(src, conv_weights(i, workspace), acc0, workspace, dst, res, conv_geom(i, batch), L.q, s);
+        void *dst2 = L.dst2 > 0 ? tensor_ptr(L.dst2, x, out, workspace, batch) : nullptr;
+        return enqueue_conv(src, conv_weights(i, workspace), acc0, workspace, dst, res, conv_geom(i, batch), L.q, s,
+                            dst2 ? &L.q2 : nullptr, dst2);
       }
       case F8_OP_DWCONV: return enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s);
       case F8_OP_MAXPOOL: return enqueue_maxpool(src, dst, g, L.q.x_type, s);
@@ -252,6 +260,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   for (int i = 0; i < n_layers; ++i) {
     if (layers[i].dst < 1 || layers[i].src < 0 || layers[i].res < -1) { st = F8_ERR_SHAPE; break; }
     max_id = std::max(max_id, std::max(layers[i].dst, std::max(layers[i].src, layers[i].res)));
+    max_id = std::max(max_id, (int)layers[i].dst2);
   }
   if (st == F8_OK && max_id > 16 * n_layers + 16) st = F8_ERR_SHAPE;
   if (st != F8_OK) { delete c; return st; }
@@ -264,6 +273,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   for (int i = 0; i < n_layers && st == F8_OK; ++i) {
     f8_layer_desc L = layers[i];
     L.q.res = nullptr;
+    if (L.dst2 <= 0) L.dst2 = -1;
     Tensor &s = c->tensors[L.src];
     if (s.producer == -2) { st = F8_ERR_SHAPE; break; }           // read before written
     if (c->tensors[L.dst].producer != -2) { st = F8_ERR_SHAPE; break; }   // written twice
@@ -311,6 +321,17 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
       c->tensors[L.res].fl = L.q.fl_res; c->tensors[L.res].fl_known = true;
       c->tensors[L.res].last_use = i;
     }
+    if (L.dst2 > 0) {
+      // a second format of the same result for a sibling consumer
+      if (L.op != F8_OP_CONV || L.dst2 == L.dst || L.dst2 == L.src || L.dst2 == L.res ||
+          c->tensors[L.dst2].producer != -2) { st = F8_ERR_SHAPE; break; }
+      st = check_requant2(L.q, &L.q2);
+      if (st != F8_OK) break;
+      Tensor d2 = d;
+      d2.type = L.q2.y_type; d2.fl = L.q2.fl_y;
+      d2.bytes_per_image = (size_t)d2.h * d2.w * d2.c;
+      c->tensors[L.dst2] = d2;
+    }
     s.last_use = i;
     c->tensors[L.dst] = d;
     c->layers.push_back(L);
@@ -350,6 +371,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
              L.pad_w == 0 && L.q.y_type != F8_S32 && L.q.fl_x + L.q.fl_w - L.q.fl_y >= 0;
     };
     if (c->fused[i].role != 0 || !pointwise(L0) || !pointwise(L2) || L0.res >= 0) continue;
+    if (L0.dst2 > 0 || L1.dst2 > 0 || L2.dst2 > 0) continue;
     if (L1.op != F8_OP_DWCONV || g1.R != 3 || g1.S != 3 || g1.sh != 1 || g1.sw != 1 || g1.ph != 1 || g1.pw != 1 ||
         L1.res >= 0 || L1.q.y_type == F8_S32 || L1.q.fl_x + L1.q.fl_w - L1.q.fl_y < 0)
       continue;
@@ -549,6 +571,7 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
   const double cols = g.sw >= g.S ? (double)g.Q * g.S : (double)std::min(g.W, (g.Q - 1) * g.sw + g.S);
   double bytes = (double)batch * rows * cols * g.Cin + M * g.Cout * (double)elem_size(c->tensors[L.dst].type);
   if (L.res >= 0) bytes += M * g.Cout * (double)elem_size(c->tensors[L.res].type);
+  if (L.dst2 > 0) bytes += M * g.Cout;
   switch (L.op) {
     case F8_OP_CONV: {
       Geom gk = c->conv_geom(layer, batch);

@@ -39,8 +39,12 @@ f8_status check_align(const int32_t *bias, const void *y, const f8_quant &q, con
 
 // Enqueue the dense layer with a ready acc0 vector (device, acc0_padded(Cout) ints) and a
 // device pointer to at least 64 bytes of zeros.
+// q2 / y2: optional second output format and tensor (both null for none).
 f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
-                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream);
+                       const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
+                       const f8_requant2 *q2 = nullptr, void *y2 = nullptr);
+// Checks of a second output format against the first (8-bit types, clip range, shift limits).
+f8_status check_requant2(const f8_quant &q, const f8_requant2 *q2);
 // Name of the kernel enqueue_conv launches for this layer (operands assumed 16-byte aligned).
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res);
 // Enqueue the fold of (w, bias, rounding addend, sign correction) into acc0.

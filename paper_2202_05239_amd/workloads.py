@@ -35,6 +35,9 @@ class LayerSpec:
     src / dst / res: tensor ids (0 = network input); res = -1 when there is no residual.
     *_type: 'u8', 's8' or 's32'.  clip_lo/clip_hi are in output LSBs (2^-fl_y).
     w: int8 [Cout][R][S][Cin] for 'conv', [R][S][C] for 'dwconv', None for pools.
+    dst2 > 0 ('conv' only): a second output tensor holding the same result in the format
+    fl_y2 / clip_lo2 / clip_hi2 / y2_type, for a sibling consumer with a private fractional
+    length (paper Sec. 4.3).
     """
     op: str
     name: str = ""
@@ -60,6 +63,11 @@ class LayerSpec:
     bias: Optional[np.ndarray] = None
     in_hw: Tuple[int, int] = (0, 0)
     out_hw: Tuple[int, int] = (0, 0)
+    dst2: int = -1
+    fl_y2: int = 0
+    clip_lo2: int = 0
+    clip_hi2: int = 255
+    y2_type: str = "u8"
 
     @property
     def macs_per_image(self) -> int:
@@ -215,7 +223,9 @@ class _NetBuilder:
         self.t[i] = dict(hw=hw, c=c, type=type_, fl=fl)
         return i
 
-    def conv(self, name, src, cout, k, stride, pad, relu=True, res=-1, raw=False):
+    def conv(self, name, src, cout, k, stride, pad, relu=True, res=-1, raw=False, dual=False):
+        """dual=True: the layer also writes its result in a second, separately drawn format and
+        the method returns both tensor ids."""
         rng, s = self.rng, self.t[src]
         cin = s["c"]
         K = k * k * cin
@@ -240,6 +250,15 @@ class _NetBuilder:
         if res >= 0:
             L.res_type, L.fl_res = self.t[res]["type"], self.t[res]["fl"]
         self.net.layers.append(L)
+        if dual:
+            fl_y2 = int(rng.integers(self.fl_a_range[0], self.fl_a_range[1] + 1))
+            if fl_y2 == fl_y:
+                fl_y2 = fl_y + 1
+            L.fl_y2, L.y2_type, L.clip_lo2, L.clip_hi2 = fl_y2, y_type, lo, hi
+            if relu and self.clip_draw and int(rng.integers(0, 4)) == 0:
+                L.clip_hi2 = int(rng.integers(96, 255))
+            L.dst2 = self._new(hw, cout, y_type, fl_y2)
+            return dst, L.dst2
         return dst
 
     def dwconv(self, name, src, k, stride, pad):
@@ -309,20 +328,30 @@ def resnet18(rng, hw=224, classes=1000, widths=(64, 128, 256, 512), clip_draw=Fa
 
 
 def resnet50b(rng, hw=224, classes=1000, widths=(64, 128, 256, 512), depths=(3, 4, 6, 3),
-              clip_draw=True):
-    b = _NetBuilder("resnet50b", rng, hw, 3, "s8", 5, (5, 9), (2, 6), clip_draw)
+              clip_draw=True, private_fl=False):
+    """private_fl=True: every block output is written in two formats, one per child (the next
+    block's first convolution, and its shortcut or downsample branch), each with its own
+    fractional length (paper Sec. 4.3)."""
+    b = _NetBuilder("resnet50b" + ("_private_fl" if private_fl else ""), rng, hw, 3, "s8", 5, (5, 9), (2, 6),
+                    clip_draw)
     t = b.conv("conv1", 0, 64, 7, 2, 3)
-    t = b.maxpool("maxpool", t)
+    t = t2 = b.maxpool("maxpool", t)
+    n_blocks = sum(depths)
+    done = 0
     for si, (c, d) in enumerate(zip(widths, depths)):
         for bi in range(d):
             stride = 2 if (si > 0 and bi == 0) else 1
             pre = "s%db%d." % (si + 1, bi + 1)
-            short = t
+            short = t2
             if bi == 0:
-                short = b.conv(pre + "ds", t, 4 * c, 1, stride, 0, relu=False)
+                short = b.conv(pre + "ds", t2, 4 * c, 1, stride, 0, relu=False)
             u = b.conv(pre + "conv_a", t, c, 1, 1, 0)
             u = b.conv(pre + "conv_b", u, c, 3, stride, 1)
-            t = b.conv(pre + "conv_c", u, 4 * c, 1, 1, 0, res=short)
+            done += 1
+            if private_fl and done < n_blocks:
+                t, t2 = b.conv(pre + "conv_c", u, 4 * c, 1, 1, 0, res=short, dual=True)
+            else:
+                t = t2 = b.conv(pre + "conv_c", u, 4 * c, 1, 1, 0, res=short)
     t = b.gpool("gpool", t)
     b.conv("fc", t, classes, 1, 1, 0, raw=True)
     return b.net
@@ -394,6 +423,14 @@ def config4(seed=None, batch=256, hw=224):
     rng = np.random.default_rng(seed_of(4) if seed is None else seed)
     x = _resnet_input(rng, batch, hw)
     return x, resnet50b(rng, hw)
+
+
+def resnet50_private_fl(seed=None, batch=256, hw=224):
+    """ResNet-50 in which the two children of every block output keep private fractional
+    lengths: the block's last convolution writes both formats."""
+    rng = np.random.default_rng(seed_of(8) if seed is None else seed)
+    x = _resnet_input(rng, batch, hw)
+    return x, resnet50b(rng, hw, private_fl=True)
 
 
 # ---------------------------------------------------------------------------------

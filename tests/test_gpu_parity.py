@@ -125,6 +125,9 @@ def check_network(oracle, x, net, oracle_images, what):
     for L in net.layers[:-1]:
         got = chain.tensor(L.dst).cpu().numpy()[idx]
         assert_same(got, want[L.dst], "%s layer %s" % (what, L.name))
+        if L.dst2 > 0:
+            got = chain.tensor(L.dst2).cpu().numpy()[idx]
+            assert_same(got, want[L.dst2], "%s layer %s, second format" % (what, L.name))
     assert_same(out.cpu().numpy()[idx], want[net.layers[-1].dst], what + " logits")
     # the memory-reusing plan gives the same logits, and repeated runs are identical
     lean = f8.Chain(net).prepare(x.shape[0])
@@ -169,8 +172,18 @@ def test_mobilenet_v1_forward(oracle):
     assert out.shape == (32, 1, 1, 1000) and out.dtype == torch.int32
 
 
+def test_resnet50_private_fractional_lengths(oracle):
+    """Every block output written in two formats, one per child (Sec. 4.3): both copies of every
+    such tensor, and everything downstream of them, against the oracle."""
+    x, net = wl.resnet50_private_fl(batch=64)                       # 224x224x3
+    assert sum(L.dst2 > 0 for L in net.layers) == 15
+    out = check_network(oracle, x, net, [0, 1, 62, 63], "resnet50 private FL")
+    assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
+
+
 def test_small_networks_full_compare(oracle):
-    for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3), (wl.mobilenet_v1_forward, 2)):
+    for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3), (wl.mobilenet_v1_forward, 2),
+                       (wl.resnet50_private_fl, 3)):
         x, net = cfg(batch=batch, hw=64)
         check_network(oracle, x, net, list(range(batch)), net.name + " 64x64")
 
@@ -374,6 +387,52 @@ def test_every_tile_variant(oracle, variant, monkeypatch):
         x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt)
         want = oracle.conv2d_fixed(x, L.w, L.bias, L, (st, st), (pd, pd), res)
         assert_same(gpu_layer(L, x, res), want, "variant %d case %s" % (variant, str(case)))
+
+
+# ------------------------------------------------------------------------- two output formats
+
+DUAL_CASES = [
+    # B   H   W  Cin Cout R  S st pd  x     y     y2    res   shift shift2  offset of y2
+    (2, 19, 23, 64, 72, 1, 1, 1, 0, "u8", "u8", "u8", "u8", 9, 7, 0),
+    (3, 13, 11, 128, 136, 1, 1, 1, 0, "s8", "s8", "s8", None, 8, 10, 0),
+    (2, 15, 17, 32, 272, 3, 3, 1, 1, "u8", "u8", "s8", "s8", 10, 11, 0),      # second output signed
+    (1, 21, 9, 256, 40, 3, 3, 2, 1, "u8", "s8", "u8", None, 12, 9, 4),        # y2 only 4-byte aligned
+    (2, 9, 9, 384, 520, 1, 1, 1, 0, "u8", "u8", "u8", "u8", 11, 0, 0),        # second shift 0: pure clip
+    (2, 9, 9, 64, 64, 3, 3, 1, 1, "u8", "u8", "u8", None, 6, -2, 0),          # second shift < 0: generic kernel
+    (2, 9, 9, 64, 64, 3, 3, 1, 1, "u8", "u8", "u8", "u8", -1, 5, 0),          # first shift < 0
+    (2, 10, 7, 5, 9, 3, 3, 1, 1, "s8", "u8", "u8", "s32", 7, 8, 1),           # generic kernel, odd sizes, odd address
+    (1, 6, 6, 24, 144, 1, 1, 1, 0, "s8", "u8", "u8", None, 8, 6, 0),          # generic (Cin % 16 != 0)
+    (4, 30, 30, 64, 256, 1, 1, 1, 0, "u8", "u8", "u8", "u8", 9, 8, 0),        # several tiles in M and N
+]
+
+
+@pytest.mark.parametrize("variant", [None, 3, 10, 14, 19, 21])
+def test_two_output_formats(oracle, variant, monkeypatch):
+    """One accumulator, two 8-bit outputs with their own fractional lengths and clips: each must be
+    the layer evaluated with that format (one rounding each, never a re-rounding of the other)."""
+    if variant is not None:
+        monkeypatch.setenv("F8_CONV_VARIANT", str(variant))
+    rng = np.random.default_rng(77 + (variant or 0))
+    for case in DUAL_CASES:
+        B, H, W, Cin, Cout, R, S, st, pd, xt, yt, y2t, rt, sh, sh2, off = case
+        if variant in (10,) and R * S * Cin > 64:
+            continue
+        x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt, shift=sh)
+        L.fl_y2 = L.fl_x + L.fl_w - sh2
+        L.y2_type = y2t
+        L.clip_lo2, L.clip_hi2 = (0, int(rng.integers(100, 256))) if y2t == "u8" else (-int(rng.integers(50, 128)), 127)
+        want, want2 = oracle.conv2d_fixed_dual(x, L.w, L.bias, L, (st, st), (pd, pd), res)
+        xd, wd, bd = (torch.from_numpy(a).to(DEV) for a in (x, L.w, L.bias))
+        rd = torch.from_numpy(res).to(DEV) if res is not None else None
+        P, Q = L.out_hw
+        y = torch.full((B, P, Q, Cout), 77, dtype=f8.TORCH_DTYPE[yt], device=DEV)
+        buf = torch.full((B * P * Q * Cout + 64,), 55, dtype=torch.uint8, device=DEV)
+        y2 = buf[off:off + B * P * Q * Cout].view(f8.TORCH_DTYPE[y2t]).view(B, P, Q, Cout)
+        f8.f8_conv2d_fixed_dual(xd, wd, bd, y, y2, L, (st, st), (pd, pd), rd)
+        torch.cuda.synchronize()
+        assert_same(y.cpu().numpy(), want, "dual case %s variant %s, first" % (str(case), variant))
+        assert_same(y2.cpu().numpy(), want2, "dual case %s variant %s, second" % (str(case), variant))
+        assert int(buf[off + B * P * Q * Cout:].min()) == 55 and (off == 0 or int(buf[:off].min()) == 55)
 
 
 # ------------------------------------------------------------------------- measurement aids

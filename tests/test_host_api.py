@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(f8.EXPORTS) == names
-    assert L.f8_abi_version() == 1
+    assert L.f8_abi_version() == 2
 
 
 def quant(**kw):
@@ -113,6 +113,9 @@ def make_descs(net):
             d.q.res_type, d.q.fl_res = {"u8": 0, "s8": 1, "s32": 2}[S.res_type], S.fl_res
         d.w = 0x10000 if S.w is not None else None
         d.bias = 0x20000 if S.bias is not None else None
+        d.dst2 = S.dst2
+        if S.dst2 > 0:
+            d.q2 = f8.make_requant2(S)
     return descs
 
 
@@ -204,3 +207,45 @@ def test_quant_tools_host_side():
     assert fold(eta_out=0.0) == 4
     assert fold(eta_in=float("inf")) == 4
     assert L.f8_fold_conv_bn(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, None) == 1
+
+
+def test_second_output_format_host_side():
+    """Validation of the two-format entry point, and a chain whose blocks write two formats."""
+    L = f8.lib()
+
+    def dual(q=None, q2=None, y=FAKE, y2=ctypes.c_void_p(0x2000), drop_q2=False):
+        q = q or quant()
+        r = q2 or f8.f8_requant2(4, 0, 255, f8.F8_U8)
+        return L.f8_conv2d_fixed_dual(FAKE, FAKE, None, y, y2, 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 1, ctypes.byref(q),
+                                      None if drop_q2 else ctypes.byref(r), None)
+    assert dual(y2=None) == 1
+    assert dual(drop_q2=True) == 1
+    assert dual(q=quant(y_type=f8.F8_S32)) == 5
+    assert dual(q2=f8.f8_requant2(4, 0, 255, f8.F8_S32)) == 5
+    assert dual(q2=f8.f8_requant2(17, 0, 255, f8.F8_U8)) == 3          # second shift -9
+    assert dual(q2=f8.f8_requant2(4, 0, 256, f8.F8_U8)) == 4
+    assert dual(q2=f8.f8_requant2(4, -128, 127, f8.F8_S8)) == 4
+    assert dual(q2=f8.f8_requant2(4, 9, 3, f8.F8_U8)) == 4
+    assert dual(y2=FAKE) == 8                                          # y2 must not be y
+    _, net = wl.resnet50_private_fl(batch=1, hw=64)
+    _, plain = wl.config4(batch=1, hw=64)
+    h = ctypes.c_void_p()
+    assert L.f8_chain_create(make_descs(net), len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 0
+    n1, n2 = ctypes.c_size_t(), ctypes.c_size_t()
+    assert L.f8_chain_workspace_bytes(h, 1, ctypes.byref(n1)) == 0
+    assert L.f8_chain_set_keep_all(h, 1) == 0
+    assert L.f8_chain_workspace_bytes(h, 1, ctypes.byref(n2)) == 0
+    extra = sum(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers if l.dst2 > 0)
+    total = sum(l.out_hw[0] * l.out_hw[1] * l.Cout for l in net.layers[:-1])
+    assert n2.value - n1.value > 0 and n2.value >= total + extra
+    L.f8_chain_destroy(h)
+    bad = make_descs(net)
+    i = next(k for k, l in enumerate(net.layers) if l.dst2 > 0)
+    bad[i].dst2 = bad[i].dst                                           # both outputs in one tensor
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 2
+    bad = make_descs(net)
+    bad[i].q2.fl_y += 1                                                # the consumer expects another format
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 3
+    bad = make_descs(net)
+    bad[i].q2.y_type = f8.F8_S32
+    assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 5

@@ -444,6 +444,28 @@ def test_global_pool_is_sum_then_fixquant(oracle):
 
 # --------------------------------------------------------------------------- error paths
 
+def test_second_output_format_is_one_rounding_of_the_accumulator(oracle):
+    """Two formats of one layer (Sec. 4.3, private fractional lengths): each output is the exact
+    fp64 fix_quant of the same accumulator; re-rounding the finer output into the coarser format
+    is a different (double-rounded) function, so the oracle must not be doing that."""
+    rng = np.random.default_rng(41)
+    x = rng.integers(0, 256, (64, 48)).astype(np.uint8)
+    w = np.clip(np.rint(rng.normal(0, 12, (40, 48))), -127, 127).astype(np.int8)
+    b = rng.integers(-4000, 4000, 40).astype(np.int32)
+    A = int_gemm(x, w, b)
+    q = Q(4, 6, 3, 0, 255)
+    q.fl_y2, q.clip_lo2, q.clip_hi2, q.y2_type = 1, 0, 200, "u8"
+    y, y2 = oracle.conv2d_fixed_dual(x.reshape(1, 1, 64, 48), w.reshape(40, 1, 1, 48), b, q)
+    assert np.array_equal(y.reshape(64, 40), fp64_requant(A, 7, 0, 255))
+    assert np.array_equal(y2.reshape(64, 40), fp64_requant(A, 9, 0, 200))
+    twice = np.clip(np.floor(y.reshape(64, 40).astype(np.float64) / 4 + 0.5), 0, 200)
+    assert (twice != y2.reshape(64, 40)).sum() > 0
+    # the same format twice gives the same tensor twice
+    q.fl_y2, q.clip_lo2, q.clip_hi2 = 3, 0, 255
+    y, y2 = oracle.conv2d_fixed_dual(x.reshape(1, 1, 64, 48), w.reshape(40, 1, 1, 48), b, q)
+    assert np.array_equal(y, y2)
+
+
 def test_oracle_rejects_bad_arguments(oracle):
     x = np.zeros((2, 4), np.uint8)
     w = np.zeros((3, 4), np.int8)
