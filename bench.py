@@ -266,7 +266,8 @@ def main():
     total_ops = sum(2.0 * L.macs_per_image * B for L in net.layers)
     rec = {
         "metric": "images/s, fixed-point %s forward (int8 conv on MFMA + shift/clip epilogue), batch %d, 1 GPU"
-                  % ({"resnet50": "ResNet-50", "resnet18": "ResNet-18", "mobilenetv2": "MobileNetV2", "mobilenetv1": "MobileNetV1"}[args.net], B),
+                  % ({"resnet50": "ResNet-50", "resnet18": "ResNet-18", "mobilenetv2": "MobileNetV2", "mobilenetv1": "MobileNetV1",
+                      "resnet50_private_fl": "ResNet-50 (two formats per block output)"}[args.net], B),
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
