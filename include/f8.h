@@ -27,17 +27,22 @@
  *     the caller; the struct pointers (q, layer descriptors) are HOST pointers read
  *     before the call returns.  Activations are NHWC, channel fastest.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
- *     enqueued asynchronously; the library never synchronises.
+ *     enqueued asynchronously; the library does not synchronise (one exception below).
  *   - Arguments are validated on the host before anything is launched; a call that
  *     returns an error has launched nothing.  Errors are status codes, never aborts.
  *   - Preconditions the library cannot check (they depend on device data): A and
  *     A + 2^(s-1) fit in int32 (the paper keeps accumulators in 32 bits, Sec. 4.3).
  *     K <= 65536 is enforced so that sum |X*W| alone cannot overflow.
  *   - x, w, y must not overlap.  q->res may be any tensor of y's shape except y itself.
- *   - The single-layer calls keep a small device scratch buffer per stream (the folded
- *     accumulator start value, 4 bytes per output channel), allocated on first use and
- *     released by f8_release_scratch() or at process exit.  Calls on different streams
- *     never share it; calls on one stream are ordered by the stream.
+ *   - The single-layer dense calls keep a small device scratch buffer per (device, stream):
+ *     256 bytes of zeros (the kernels' stand-in for padding) plus the folded accumulator
+ *     start value, 4 bytes per output channel rounded up to 256 channels, at least 64 KiB.
+ *     It is allocated (hipMalloc) on the first call on a stream and when a call needs more
+ *     channels than any before it; growing waits for that stream first (the one place the
+ *     library synchronises).  f8_release_scratch() frees all of them.  Calls on different
+ *     streams never share a buffer; calls on one stream are ordered by the stream.  The
+ *     chain runner and the upstream steps allocate nothing: their memory is the caller's
+ *     workspace.
  */
 #ifndef F8_H
 #define F8_H
