@@ -25,13 +25,12 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak, GB/s
 # are in profiles/resnet50_b256_hbm_traffic.md.  Counters cannot be read from inside this
 # process, so the figure of the dominant kernel is reported from here.
 MEASURED_TRAFFIC_MB = {
-    "conv_fast<128x128,k64,s2>": 174.95,
-    "conv_fast<128x128,k64,s1>": 471.69,
-    "conv_fast<128x64,k64,s2>": 154.49,
-    "conv_fast<128x128,k64,s3>": 103.15,
-    "conv_fast<128x128,k128,s2>": 74.94,
-    "conv_fast<256x256,k128,s2,w4x2>": 57.13,
-    "conv_fast<256x128,k128,s2,w4x2>": 41.68,
+    "conv_fast<128x128,k64,s2>": 174.97,
+    "conv_fast<128x128,k64,s3>": 205.96,
+    "conv_fast<128x64,k64,s2>": 154.50,
+    "conv_fast<128x128,k128,s2>": 74.90,
+    "conv_fast<256x256,k128,s2,w4x2>": 57.18,
+    "conv_fast<256x128,k128,s2,w4x2>": 41.71,
 }
 
 
