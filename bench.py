@@ -3,7 +3,7 @@
 One step = one forward pass of the whole fixed-point ResNet-50 (stride on the 3x3 of the
 bottleneck) over a batch of 256 seeded synthetic 224x224x3 images that already sit in HBM:
 53 dense layers + FC on the int8 matrix cores with the shift/clip epilogue, max pool,
-global pool.  Prints ONE JSON line (see README / DESIGN for the fields).
+global pool.  Prints ONE JSON line.
 """
 import argparse
 import ctypes
@@ -179,7 +179,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-              "(the path shards by batch with no communication; see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "(the path shards by batch: images are independent, no communication)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     if args.copy_calibration:
