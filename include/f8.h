@@ -243,7 +243,7 @@ int f8_opt_fl(double sigma, int is_signed);
 
 /* Device scratch every reduction below needs: this many doubles, 8-byte aligned, contents
  * irrelevant before and after; calls that run concurrently need one each. */
-#define F8_STATS_WORK_DOUBLES 2048
+#define F8_STATS_WORK_DOUBLES 4096
 typedef struct {
   double mean, std;                 /* over all n elements; std is the population one (divide by n) */
   int32_t fl_signed, fl_unsigned;   /* Eq. 1 applied to std */

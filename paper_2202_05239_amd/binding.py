@@ -29,7 +29,7 @@ EXPORTS = [
     "f8_fix_quant_f32", "f8_fix_quant_code", "f8_pact_f32", "f8_pact_fix_f32", "f8_eta_fix", "f8_opt_fl",
     "f8_tensor_stats_f32", "f8_quant_error_f32", "f8_fold_work_doubles", "f8_fold_conv_bn",
 ]
-F8_STATS_WORK_DOUBLES = 2048
+F8_STATS_WORK_DOUBLES = 4096
 
 
 class F8Error(RuntimeError):

@@ -24,8 +24,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 SUM_RTOL = 1e-12
 # sizes: empty, below one vector, ragged tails, several workgroups, more elements than one pass
-# of the reduction grid covers (1024 workgroups x 256 threads x 16 elements = 4 Mi)
-SIZES = [0, 1, 3, 4, 5, 1023, 4096, 65537, 1 << 20, (5 << 20) + 7]
+# of the reduction grid covers (2048 workgroups x 256 threads x 16 elements = 8 Mi)
+SIZES = [0, 1, 3, 4, 5, 1023, 4096, 65537, 1 << 20, (9 << 20) + 7]
 
 
 def dev(a):

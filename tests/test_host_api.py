@@ -192,7 +192,7 @@ def test_quant_tools_host_side():
     assert L.f8_tensor_stats_f32(FAKE, 16, FAKE, None, None) == 1
     assert L.f8_quant_error_f32(FAKE, 16, 8, 1, FAKE, FAKE, None) == 3
     assert L.f8_quant_error_f32(FAKE, 16, 3, 1, None, FAKE, None) == 1
-    assert L.f8_fold_work_doubles(64) == 2048 + 128
+    assert L.f8_fold_work_doubles(64) == 4096 + 128
 
     def fold(cout=8, k=16, eta_in=1.0, eta_out=1.0, fl_x=4, fl_w=-1, w=FAKE, stats=FAKE):
         d = f8.f8_fold_desc(cout, k, eta_in, eta_out, fl_x, fl_w)
