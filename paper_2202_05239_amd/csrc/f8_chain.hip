@@ -16,6 +16,11 @@
 // first MobileNetV2 blocks) is run on a copy of its input and weights with the channels
 // padded with zeros to the next multiple of 16, for the same reason.
 //
+// Stem + pool.  The ImageNet stem (7x7 stride-2 convolution of a 3-channel image to 64 unsigned
+// channels) followed by a 3x3 stride-2 pad-1 max pool that is its only reader runs as one kernel
+// on the re-laid-out operands; the tensor between the two then gets no memory.  (Not when every
+// tensor is to be kept; F8_STEM_POOL=0, read when the chain is created, turns it off: tuning aid.)
+//
 // Block fusion.  Three consecutive layers that form an inverted-residual block (1x1 dense,
 // 3x3 depthwise stride 1 pad 1, 1x1 dense, optional shortcut from the block input) whose two
 // intermediate tensors have no other reader run as one kernel that keeps the intermediates on
@@ -28,6 +33,7 @@
 #include <vector>
 
 #include "block_fused.h"
+#include "stem_pool.h"
 #include "f8_host.h"
 
 using namespace f8;
@@ -53,6 +59,7 @@ struct Stem {
   size_t w_off = 0;                 // re-laid-out weights: byte offset in the constants region
   size_t x_off_per_image = 0;       // re-laid-out input: arena offset per image
   size_t x_bytes_per_image = 0;
+  int pool = 0;                     // 1: this layer also does the max pool that follows; 2: that (absorbed) pool
 };
 
 // Role of a layer in a fused block, and where the block's re-laid-out constants live.
@@ -74,6 +81,8 @@ struct f8_chain {
   std::vector<Fused> fused;            // per layer
   bool fusion = false;
   bool use_fusion() const { return fusion && !keep_all; }
+  bool stem_pool = true;
+  int pool_role(size_t i) const { return stem_pool && !keep_all ? stem[i].pool : 0; }
   std::vector<Tensor> tensors;
   std::vector<size_t> acc0_off;        // per layer: byte offset in the constants region
   size_t const_bytes = 0;
@@ -125,6 +134,17 @@ struct f8_chain {
       }
     };
     for (size_t li = 0; li < layers.size(); ++li) {
+      if (pool_role(li) == 2) continue;
+      if (pool_role(li) == 1) {
+        // one kernel: re-laid-out input in, the pool's output out
+        stem[li].x_off_per_image = alloc(round256(stem[li].x_bytes_per_image));
+        Tensor &d = tensors[layers[li + 1].dst];
+        if (!d.external) d.offset_per_image = alloc(round256(d.bytes_per_image));
+        release(stem[li].x_off_per_image, round256(stem[li].x_bytes_per_image));
+        Tensor &t = tensors[layers[li].src];
+        if (!t.external && t.last_use == (int)li) release(t.offset_per_image, round256(t.bytes_per_image));
+        continue;
+      }
       if (use_fusion() && fused[li].role == 2) continue;
       if (use_fusion() && fused[li].role == 1) {
         // one kernel: reads the block input, writes the third layer's output
@@ -215,6 +235,24 @@ struct f8_chain {
     const f8_layer_desc &L = layers[i];
     Geom g = geom[i];
     g.B = batch;
+    if (pool_role(i) == 2) return F8_OK;
+    if (pool_role(i) == 1) {
+      const void *src = tensor_ptr(L.src, x, out, workspace, batch);
+      void *xp = arena(workspace) + stem[i].x_off_per_image * (size_t)batch;
+      if (launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s) != 0)
+        return F8_ERR_DEVICE;
+      StemPoolParams sp;
+      sp.xp = static_cast<const uint8_t *>(xp);
+      sp.wp = conv_weights(i, workspace);
+      sp.acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
+      sp.y = static_cast<uint8_t *>(tensor_ptr(layers[i + 1].dst, x, out, workspace, batch));
+      sp.B = batch; sp.Hp = stem[i].Hp; sp.Wp = stem[i].Wp;
+      sp.P = g.P; sp.Q = g.Q; sp.PP = geom[i + 1].P; sp.QP = geom[i + 1].Q;
+      sp.shift = L.q.fl_x + L.q.fl_w - L.q.fl_y; sp.lo = L.q.clip_lo; sp.hi = L.q.clip_hi;
+      sp.x_xor = L.q.x_type == F8_U8 ? 0x80808080u : 0u;
+      sp.ntiles = 0;
+      return launch_stem_pool(sp, s) == 0 ? F8_OK : F8_ERR_DEVICE;
+    }
     if (use_fusion() && fused[i].role == 2) return F8_OK;
     if (use_fusion() && fused[i].role == 1) {
       const BlockParams bp = block_params(i, x, out, workspace, batch);
@@ -362,6 +400,21 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   if (st != F8_OK) { delete c; return st; }
   c->last_tensor = c->layers.back().dst;
   c->tensors[c->last_tensor].external = true;
+  { const char *e = getenv("F8_STEM_POOL"); c->stem_pool = !(e && atoi(e) == 0); }
+  // a stem whose only reader is a 3x3 stride-2 pad-1 max pool: both in one kernel
+  for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
+    const f8_layer_desc &L = c->layers[i], &M = c->layers[i + 1];
+    const Stem &sm = c->stem[i];
+    if (L.op != F8_OP_CONV || !sm.on || sm.Cp != 4 || L.Cin != 3 || L.res >= 0 || L.dst2 > 0) continue;
+    if (!stem_pool_applicable(L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, sm.Sp)) continue;
+    if (L.q.y_type != F8_U8 || L.q.clip_lo < 0 || L.q.fl_x + L.q.fl_w - L.q.fl_y < 0) continue;
+    if (M.op != F8_OP_MAXPOOL || M.src != L.dst || M.R != 3 || M.S != 3 || M.stride_h != 2 || M.stride_w != 2 ||
+        M.pad_h != 1 || M.pad_w != 1)
+      continue;
+    if (c->tensors[L.dst].last_use != (int)i + 1 || L.dst == c->last_tensor) continue;
+    c->stem[i].pool = 1;
+    c->stem[i + 1].pool = 2;
+  }
   // inverted-residual blocks that can run as one kernel
   for (size_t i = 0; i + 2 < c->layers.size(); ++i) {
     const f8_layer_desc &L0 = c->layers[i], &L1 = c->layers[i + 1], &L2 = c->layers[i + 2];
@@ -497,8 +550,9 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
   if (!c->planned) const_cast<f8_chain *>(c)->plan();
   const Tensor &t = c->tensors[id];
   // tensors inside a fused block are never materialised
-  const bool elided = c->use_fusion() && t.producer >= 0 && c->fused[t.producer].role != 0 &&
-                      !(c->fused[t.producer].role == 2 && t.producer >= 2 && c->fused[t.producer - 2].role == 1);
+  const bool elided = (t.producer >= 0 && c->pool_role((size_t)t.producer) == 1) ||
+                      (c->use_fusion() && t.producer >= 0 && c->fused[t.producer].role != 0 &&
+                       !(c->fused[t.producer].role == 2 && t.producer >= 2 && c->fused[t.producer - 2].role == 1));
   if (ptr) *ptr = (t.external || !workspace || elided) ? nullptr : c->tensor_ptr(id, nullptr, nullptr, workspace, batch);
   if (h) *h = t.h;
   if (w) *w = t.w;
@@ -543,6 +597,23 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
   const Geom &g = c->geom[layer];
   const char *name = "?";
   double ops = 0.0;
+  if (c->pool_role((size_t)layer) != 0) {
+    // stem and pool are accounted to the stem: image in, pooled tensor out, weights
+    const bool first = c->pool_role((size_t)layer) == 1;
+    const char *fname = first ? "stem_pool_fused" : "(fused)";
+    if (kernel_name && name_len > 0) {
+      int i = 0;
+      for (; fname[i] && i < name_len - 1; ++i) kernel_name[i] = fname[i];
+      kernel_name[i] = 0;
+    }
+    const Geom &gp = c->geom[first ? layer + 1 : layer];
+    if (alg_ops) *alg_ops = first ? 2.0 * batch * g.P * g.Q * (double)g.R * g.S * g.Cin * g.Cout : 0.0;
+    if (alg_bytes)
+      *alg_bytes = first ? (double)batch * g.H * g.W * g.Cin + (double)batch * gp.P * gp.Q * g.Cout +
+                               (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout
+                         : 0.0;
+    return F8_OK;
+  }
   if (c->use_fusion() && c->fused[layer].role != 0) {
     // the whole block is accounted to its first layer: block input + output (+ shortcut read
     // from the same input), all weights

@@ -181,6 +181,45 @@ def test_resnet50_private_fractional_lengths(oracle):
     assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
 
 
+def test_fused_stem_and_pool(oracle):
+    """The 7x7 stride-2 stem and the 3x3 stride-2 max pool behind it run as one kernel (when the
+    tensor between them has no other reader): odd and tiny image sizes, ragged tiles, signed and
+    unsigned images, a clip below 255, against the oracle and the two-kernel path."""
+    for k, (hw, batch, x_type, hi) in enumerate(((31, 3, "s8", 255), (64, 2, "u8", 255), (75, 5, "s8", 140),
+                                                 (113, 2, "u8", 201), (9, 4, "s8", 255), (224, 3, "s8", 255))):
+        rng = np.random.default_rng(500 + k)
+        b = wl._NetBuilder("stem%d" % hw, rng, hw, 3, x_type, 5, (5, 9), (2, 6), False)
+        t = b.conv("conv1", 0, 64, 7, 2, 3)
+        b.net.layers[-1].clip_hi = hi
+        t = b.maxpool("maxpool", t)
+        b.conv("head", t, 32, 1, 1, 0)
+        net = b.net
+        x = wl.draw_u8(rng, (batch, hw, hw, 3)) if x_type == "u8" else wl.draw_s8_normal(rng, (batch, hw, hw, 3), 5)
+        want = oracle.run_network(net, x, keep_all=True)
+        xt = torch.from_numpy(x).to(DEV)
+        fused = f8.Chain(net).prepare(batch)
+        assert fused.layer_info(0, batch)[0] == "stem_pool_fused"
+        got = fused.run(xt)
+        torch.cuda.synchronize()
+        assert_same(got.cpu().numpy(), want[net.layers[-1].dst], "fused stem %d" % hw)
+        assert fused.tensor(net.layers[0].dst) is None                   # never materialised
+        assert_same(fused.tensor(net.layers[1].dst).cpu().numpy(), want[net.layers[1].dst], "pooled tensor %d" % hw)
+        plain = f8.Chain(net, keep_all=True).prepare(batch)
+        assert plain.layer_info(0, batch)[0] != "stem_pool_fused"
+        assert torch.equal(plain.run(xt), got)
+    # a second reader of the stem's output keeps the two kernels apart
+    rng = np.random.default_rng(77)
+    b = wl._NetBuilder("stem_two_readers", rng, 40, 3, "s8", 5, (5, 9), (2, 6), False)
+    t = b.conv("conv1", 0, 64, 7, 2, 3)
+    u = b.maxpool("maxpool", t)
+    v = b.conv("side", t, 64, 3, 2, 1, relu=False)
+    b.conv("join", u, 64, 1, 1, 0, res=v)
+    x = wl.draw_s8_normal(rng, (2, 40, 40, 3), 5)
+    chain = f8.Chain(b.net).prepare(2)
+    assert chain.layer_info(0, 2)[0] != "stem_pool_fused"
+    assert_same(chain.run(torch.from_numpy(x).to(DEV)).cpu().numpy(), oracle.run_network(b.net, x), "two readers")
+
+
 def test_small_networks_full_compare(oracle):
     for cfg, batch in ((wl.config3, 5), (wl.config4, 3), (wl.mobilenet_v2_forward, 3), (wl.mobilenet_v1_forward, 2),
                        (wl.resnet50_private_fl, 3)):
@@ -451,10 +490,12 @@ def test_profile_graph_replay_and_copy(oracle):
     want = oracle.run_network_parallel(net, x, host_threads())
     assert_same(eager.cpu().numpy(), want, "eager")
     ms = chain.profile(xt, out, repeats=2)
-    assert len(ms) == len(net.layers) and all(t > 0 for t in ms)
+    assert len(ms) == len(net.layers) and all(t >= 0 for t in ms) and sum(ms) > 0
     assert torch.equal(out, eager)
-    name, ops, nbytes = chain.layer_info(1, 4)
-    assert name and nbytes > 0
+    # the stem and the max pool behind it run as one kernel, accounted to the stem
+    assert chain.layer_info(0, 4)[0] == "stem_pool_fused" and chain.layer_info(1, 4) == ("(fused)", 0.0, 0.0)
+    name, ops, nbytes = chain.layer_info(2, 4)
+    assert name and ops > 0 and nbytes > 0
     graph = chain.capture(xt, out)
     for i in range(4):
         out.fill_(i)                                   # eager work between the replays
