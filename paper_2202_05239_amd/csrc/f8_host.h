@@ -7,6 +7,7 @@
 
 #include "../../include/f8.h"
 #include "conv_igemm.h"
+#include "conv_ws.h"
 #include "dwconv_pool.h"
 
 namespace f8 {

@@ -181,6 +181,31 @@ def test_resnet50_private_fractional_lengths(oracle):
     assert out.shape == (64, 1, 1, 1000) and out.dtype == torch.int32
 
 
+def test_weights_stationary_3x3_64(oracle):
+    """The 3x3 64 -> 64 stride-1 layers take a kernel of their own (weights in registers, input rows
+    in LDS): image widths from 8 to 64, heights that leave ragged last tiles, one-row images, every
+    input / output type, a shift of zero, clips inside the range."""
+    rng = np.random.default_rng(640)
+    # batches large enough for the library to pick this kernel (at least 2048 tiles of 128 pixels)
+    for B, H, W, xt, yt, shift, clip in ((85, 56, 56, "u8", "u8", 9, None), (2048, 13, 8, "s8", "s8", 7, (-50, 90)),
+                                         (2051, 1, 64, "u8", "s8", 8, None), (1030, 7, 33, "s8", "u8", 0, (3, 200)),
+                                         (410, 31, 17, "u8", "u8", 11, (0, 1)), (411, 9, 64, "u8", "u8", 6, None),
+                                         (256, 100, 9, "s8", "u8", 10, None), (2, 56, 56, "u8", "u8", 9, None)):
+        x, L, _ = wl.random_conv_case(rng, B, H, W, 64, 64, 3, 3, 1, 1, xt, yt, None, shift=shift, clip=clip)
+        # images are independent: the single-threaded oracle runs on slices of the batch in host threads
+        from concurrent.futures import ThreadPoolExecutor
+        parts = np.array_split(np.arange(B), min(B, host_threads()))
+        with ThreadPoolExecutor(len(parts)) as ex:
+            outs = list(ex.map(lambda idx: oracle.conv2d_fixed(np.ascontiguousarray(x[idx]), L.w, L.bias, L, (1, 1), (1, 1)), parts))
+        want = np.concatenate(outs)
+        assert_same(gpu_layer(L, x), want, "ws 3x3 %s" % str((B, H, W, xt, yt, shift)))
+    # in a chain the kernel's name shows: chosen at batch 256 of the full-size network, not for a few images
+    _, net = wl.config4(batch=1)
+    chain = f8.Chain(net)
+    assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 3
+    assert [chain.layer_info(i, 4)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
+
+
 def test_fused_stem_and_pool(oracle):
     """The 7x7 stride-2 stem and the 3x3 stride-2 max pool behind it run as one kernel (when the
     tensor between them has no other reader): odd and tiny image sizes, ragged tiles, signed and
