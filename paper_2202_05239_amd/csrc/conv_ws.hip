@@ -134,24 +134,27 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
         acc[mf][4 * g] = s0.x; acc[mf][4 * g + 1] = s0.y; acc[mf][4 * g + 2] = s0.z; acc[mf][4 * g + 3] = s0.w;
       }
     }
-    // 18 K slices (9 taps x 2 halves of the channels); the fragments of slice i + 2 are requested
-    // before the matrix instructions of slice i are issued, so two slices of LDS latency are covered
+    // 18 K slices (9 taps x 2 halves of the channels); the fragments of slice i + 4 are requested
+    // before the matrix instructions of slice i are issued, so four slices of LDS latency are covered
     auto frag = [&](int slice, int mf) {
       const int tap = slice >> 1, k2 = slice & 1;
       return *reinterpret_cast<const v4i *>(&lds[(k2 ? a1[mf][tap % 3] : a0[mf][tap % 3]) + (tap / 3) * p.pitch]);
     };
-    v4i fb[3][MF];
+    constexpr int AHEAD = 4;
+    v4i fb[AHEAD + 1][MF];
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf) { fb[0][mf] = frag(0, mf); fb[1][mf] = frag(1, mf); }
+    for (int i = 0; i < AHEAD; ++i)
+#pragma unroll
+      for (int mf = 0; mf < MF; ++mf) fb[i][mf] = frag(i, mf);
 #pragma unroll
     for (int slice = 0; slice < 18; ++slice) {
-      if (slice + 2 < 18) {
+      if (slice + AHEAD < 18) {
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) fb[(slice + 2) % 3][mf] = frag(slice + 2, mf);
+        for (int mf = 0; mf < MF; ++mf) fb[(slice + AHEAD) % (AHEAD + 1)][mf] = frag(slice + AHEAD, mf);
       }
 #pragma unroll
       for (int mf = 0; mf < MF; ++mf)
-        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice >> 1][slice & 1], fb[slice % 3][mf], acc[mf], 0, 0, 0);
+        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice >> 1][slice & 1], fb[slice % (AHEAD + 1)][mf], acc[mf], 0, 0, 0);
     }
 
     // requantise into the staging tile
