@@ -12,7 +12,7 @@
 // The weights stay in registers for the life of the workgroup, which walks over tiles; the next
 // tile's patch is fetched while the current one is multiplied.  The requantised 17 x 15 x 64 tile
 // goes to LDS, convolution pixels outside the image as 0 (every real value is >= 0, so 0 never wins
-// a max that has at least one real value), and is pooled from there.
+// a max that has at least one real value), and is pooled from there (held as 16-bit values, so that the packed 16-bit maximum needs no unpacking).
 #include "stem_pool.h"
 
 namespace f8 {
@@ -28,7 +28,7 @@ constexpr int PPITCH = PCB + 8;                 // 152: keeps 8-byte alignment, 
 constexpr int PATCH_BYTES = PR * PPITCH;        // 5928
 constexpr int CHUNKS = PR * (PCB / 8);          // 8-byte pieces of a patch: 702
 constexpr int CPT = (CHUNKS + SP_NT - 1) / SP_NT;   // pieces per thread: 3
-constexpr int CT_PITCH = 68;                    // bytes per convolution pixel in the LDS tile (64 + 4)
+constexpr int CT_PITCH = 144;                   // bytes per convolution pixel in the LDS tile: 64 x 16 bits + 16
 constexpr int CT_BYTES = 256 * CT_PITCH;
 static_assert(CR * CC == 255, "the convolution tile fills the 256 GEMM rows but one");
 
@@ -39,18 +39,15 @@ __device__ __forceinline__ int med3(int v, int lo, int hi) {
   return r;
 }
 
-// Bytewise unsigned max of dwords, kept as two running packed 16-bit maxima (even and odd bytes).
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-struct ByteMax {
-  u16x2 e = {0, 0}, o = {0, 0};
-  __device__ __forceinline__ void take(uint32_t v) {
-    e = __builtin_elementwise_max(e, __builtin_bit_cast(u16x2, v & 0x00ff00ffu));
-    o = __builtin_elementwise_max(o, __builtin_bit_cast(u16x2, (v >> 8) & 0x00ff00ffu));
-  }
-  __device__ __forceinline__ uint32_t result() const {
-    return __builtin_bit_cast(uint32_t, e) | (__builtin_bit_cast(uint32_t, o) << 8);
-  }
-};
+// Two 16-bit lanes at a time (the tile in LDS holds every value in 16 bits so that the pool needs
+// no unpacking).
+__device__ __forceinline__ int pk_max(int a, int b) {
+  return __builtin_bit_cast(int, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ v4i pk_max4(v4i a, v4i b) {
+  return v4i{pk_max(a.x, b.x), pk_max(a.y, b.y), pk_max(a.z, b.z), pk_max(a.w, b.w)};
+}
 
 __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParams p) {
   __shared__ __attribute__((aligned(16))) uint8_t lds[2 * PATCH_BYTES + CT_BYTES];
@@ -106,7 +103,10 @@ __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParam
     for (int k = 0; k < CPT; ++k) {
       const int c = tid + k * SP_NT;
       const int row = c / (PCB / 8), col = c - row * (PCB / 8);
-      if (c < CHUNKS) *reinterpret_cast<v2i *>(lds + which * PATCH_BYTES + row * PPITCH + 8 * col) = buf[k];
+      // stored xor 0x80 when the image is unsigned: the form the signed matrix instruction takes
+      if (c < CHUNKS)
+        *reinterpret_cast<v2i *>(lds + which * PATCH_BYTES + row * PPITCH + 8 * col) =
+            v2i{buf[k].x ^ (int)p.x_xor, buf[k].y ^ (int)p.x_xor};
     }
   };
 
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParam
       for (int mf = 0; mf < 2; ++mf) {
         const v2i lo = *reinterpret_cast<const v2i *>(patch + poff[mf] + r * PPITCH);
         const v2i hi = *reinterpret_cast<const v2i *>(patch + poff[mf] + r * PPITCH + 8);
-        fb[mf] = v4i{lo.x ^ (int)p.x_xor, lo.y ^ (int)p.x_xor, hi.x ^ (int)p.x_xor, hi.y ^ (int)p.x_xor};
+        fb[mf] = v4i{lo.x, lo.y, hi.x, hi.y};
       }
 #pragma unroll
       for (int nf = 0; nf < 2; ++nf)
@@ -167,8 +167,9 @@ __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParam
           int v[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = med3(acc[nf][mf][4 * g + j] >> p.shift, p.lo, p.hi);
-          const uint32_t packed = real ? pack4(v[0], v[1], v[2], v[3]) : 0u;
-          *reinterpret_cast<uint32_t *>(ct + m_of[mf] * CT_PITCH + 32 * nf + 8 * g + 4 * half) = packed;
+          // channels 32 nf + 8 g + 4 half + 0..3 as four 16-bit values
+          const v2i packed = real ? v2i{v[0] | (v[1] << 16), v[2] | (v[3] << 16)} : v2i{0, 0};
+          *reinterpret_cast<v2i *>(ct + m_of[mf] * CT_PITCH + 2 * (32 * nf + 8 * g + 4 * half)) = packed;
         }
     }
     if (more) store_patch(which ^ 1, nextbuf);
@@ -176,21 +177,29 @@ __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParam
     __syncthreads();
 
     // 3 x 3 stride-2 max over the tile: pooled pixel (i, j) of the tile covers tile rows 2 i .. 2 i + 2
-    // and columns 2 j .. 2 j + 2; 16 dwords (64 channels) per pooled pixel
-    for (int item = tid; item < TPI * TPJ * 16; item += SP_NT) {
-      const int pp = item >> 4, cq = item & 15;
+    // and columns 2 j .. 2 j + 2; one thread takes 16 channels (32 bytes of 16-bit values) of one pooled
+    // pixel and writes them as 16 bytes
+    if (tid < TPI * TPJ * 4) {
+      const int pp = tid >> 2, q16 = tid & 3;
       const int i = pp / TPJ, j = pp - i * TPJ;
       const int gi = TPI * ti + i, gj = TPJ * tj + j;
-      if (gi >= p.PP || gj >= p.QP) continue;
-      ByteMax best;
+      if (gi < p.PP && gj < p.QP) {
+        v4i lo4 = {0, 0, 0, 0}, hi4 = {0, 0, 0, 0};
 #pragma unroll
-      for (int dy = 0; dy < 3; ++dy)
+        for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
-        for (int dx = 0; dx < 3; ++dx) {
-          const int m = (2 * i + dy) * CC + 2 * j + dx;
-          best.take(*reinterpret_cast<const uint32_t *>(ct + m * CT_PITCH + 4 * cq));
-        }
-      *reinterpret_cast<uint32_t *>(p.y + (((size_t)b * p.PP + gi) * p.QP + gj) * 64 + 4 * cq) = best.result();
+          for (int dx = 0; dx < 3; ++dx) {
+            const uint8_t *src = ct + ((2 * i + dy) * CC + 2 * j + dx) * CT_PITCH + 32 * q16;
+            lo4 = pk_max4(lo4, *reinterpret_cast<const v4i *>(src));
+            hi4 = pk_max4(hi4, *reinterpret_cast<const v4i *>(src + 16));
+          }
+        // low bytes of the sixteen 16-bit values
+        const v4i out = {(int)__builtin_amdgcn_perm((uint32_t)lo4.y, (uint32_t)lo4.x, 0x06040200u),
+                         (int)__builtin_amdgcn_perm((uint32_t)lo4.w, (uint32_t)lo4.z, 0x06040200u),
+                         (int)__builtin_amdgcn_perm((uint32_t)hi4.y, (uint32_t)hi4.x, 0x06040200u),
+                         (int)__builtin_amdgcn_perm((uint32_t)hi4.w, (uint32_t)hi4.z, 0x06040200u)};
+        *reinterpret_cast<v4i *>(p.y + (((size_t)b * p.PP + gi) * p.QP + gj) * 64 + 16 * q16) = out;
+      }
     }
     which ^= 1;
     __syncthreads();       // the tile in LDS is free again; the next patch is complete
@@ -209,7 +218,7 @@ int launch_stem_pool(StemPoolParams p, hipStream_t stream) {
   if (p.P < 1 || p.Q < 1 || p.Hp < 2 * (p.P - 1) + 7 || p.Wp < 2 * (p.Q - 1) + 8 || (p.Wp & 3) != 0 ||
       p.PP != (p.P - 1) / 2 + 1 || p.QP != (p.Q - 1) / 2 + 1 || p.shift < 0 || p.lo < 0 || p.hi > 255 || p.lo > p.hi ||
       (reinterpret_cast<uintptr_t>(p.xp) & 15) || (reinterpret_cast<uintptr_t>(p.wp) & 15) ||
-      (reinterpret_cast<uintptr_t>(p.acc0) & 15) || (reinterpret_cast<uintptr_t>(p.y) & 3))
+      (reinterpret_cast<uintptr_t>(p.acc0) & 15) || (reinterpret_cast<uintptr_t>(p.y) & 15))
     return (int)hipErrorInvalidValue;
   const int tiles_i = (p.PP + TPI - 1) / TPI, tiles_j = (p.QP + TPJ - 1) / TPJ;
   const long long ntiles = (long long)p.B * tiles_i * tiles_j;
