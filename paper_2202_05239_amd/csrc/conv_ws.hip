@@ -1,5 +1,5 @@
-// Weights-stationary 3x3 convolution, 64 -> 64 channels, stride 1, pad 1 (the 3x3 layers of the first
-// ResNet stage), with the shift / clip epilogue of F8Net Eq. 2 / Eq. 9.
+// Weights-stationary 3x3 convolution, 64 -> 64 or 128 -> 128 channels, stride 1, pad 1 (the 3x3 layers of
+// the first two ResNet stages), with the shift / clip epilogue of F8Net Eq. 2 / Eq. 9.
 //
 // With only 64 output channels a tile of the implicit GEMM reuses each activation fragment twice, so
 // the general kernel spends its time moving operands.  Here the 64 x 576 weights stay in registers
@@ -21,10 +21,23 @@ namespace {
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WS_NT = 256;
-constexpr int TILE = 128;           // output pixels per tile
-constexpr int MF = TILE / 64;       // 32-pixel blocks per wave (two waves share the pixels, two the channels)
-constexpr int OPITCH = 80;          // staging pitch per pixel (64 + 16)
+constexpr int OPITCH_PAD = 16;      // staging pitch per pixel = C + 16
 constexpr int MAXCH = 6;            // 16-byte patch pieces per thread
+constexpr int MF = 2;               // 32-pixel blocks per wave
+
+// Per channel count: how the four waves split a tile, and the tile size.
+//   C = 64:  2 waves along the pixels x 2 along the channels, 128 pixels per tile;
+//   C = 128: all 4 waves along the channels (32 each), 64 pixels per tile.
+template <int C> struct WsShape {
+  static constexpr int WN = C / 32, WM = 4 / WN;
+  static constexpr int TILE = 32 * MF * WM;
+  static constexpr int KPT = C / 32;            // K slices per tap
+  static constexpr int KS = 9 * KPT;            // K slices in all
+  static constexpr int PIECES = C / 16;         // 16-byte pieces per pixel
+  static constexpr int KEY_SHIFT = C == 64 ? 2 : 1;   // piece ^= (column >> KEY_SHIFT) & (PIECES - 1)
+  static constexpr int AHEAD = C == 64 ? 4 : 2; // K slices the fragment reads run ahead
+  static constexpr int OPITCH = C + OPITCH_PAD;
+};
 
 __device__ __forceinline__ int med3(int v, int lo, int hi) {
   int r;
@@ -32,43 +45,45 @@ __device__ __forceinline__ int med3(int v, int lo, int hi) {
   return r;
 }
 
+template <int C>
 __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p) {
+  using S = WsShape<C>;
+  constexpr int TILE = S::TILE, KS = S::KS, OPITCH = S::OPITCH;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  __shared__ __attribute__((aligned(16))) int32_t start[64];
-  const int patch_bytes = 64 + p.nrows * p.pitch;          // leading zero pixel, then the rows
+  __shared__ __attribute__((aligned(16))) int32_t start[C];
+  const int patch_bytes = C + p.nrows * p.pitch;            // leading zero pixel, then the rows
   uint8_t *stage = lds + 2 * patch_bytes;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int wm = wave & 1, wn = wave >> 1;                  // TILE / 2 pixels x 32 channels per wave
+  const int wm = wave % S::WM, wn = wave / S::WM;           // 32 MF pixels x 32 channels per wave
   const int HW = p.H * p.W;
 
   int t = blockIdx.x;
   if (t >= p.ntiles) return;
 
-  // weights: fa[tap][k2] = channel 32 wn + l32, bytes 64 tap + 32 k2 + 16 half .. + 16 of its 576
-  v4i fa[9][2];
+  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C
+  v4i fa[KS];
 #pragma unroll
-  for (int tap = 0; tap < 9; ++tap)
-#pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2)
-      fa[tap][k2] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * wn + l32) * 576 + 64 * tap + 32 * k2 + 16 * half);
-  if (tid < 64) start[tid] = p.acc0[tid];
+  for (int sl = 0; sl < KS; ++sl)
+    fa[sl] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * wn + l32) * (9 * C) + 32 * sl + 16 * half);
+  if (tid < C) start[tid] = p.acc0[tid];
   // Both patch buffers start as the value zero in the form the matrix instruction sees it (unsigned
   // activations are stored xor 0x80, which makes them signed); only the pixels between the border
   // pixels are ever rewritten.
   const int zx = (int)p.x_xor;
   for (int i = tid; i < (2 * patch_bytes) >> 4; i += WS_NT) *reinterpret_cast<v4i *>(lds + 16 * i) = v4i{zx, zx, zx, zx};
 
-  // This thread's pieces of a patch: piece c = tid + 256 k is 16 bytes of patch row c / (4 W).  Where it
-  // comes from (relative to the patch's first row in the image) and where it goes in LDS never change.
-  int src_off[MAXCH], dst_off[MAXCH], row_of[MAXCH];
+  // This thread's pieces of a patch: piece c = tid + 256 k is 16 bytes of patch row c / (W C / 16); it lies
+  // 16 c bytes behind the start of the patch's first row in the image.  Where it goes in LDS never changes:
+  // kept with the row number in one register (offset in the low 20 bits).
+  int where[MAXCH];
 #pragma unroll
   for (int k = 0; k < MAXCH; ++k) {
     const int c = tid + k * WS_NT;
-    const int row = (int)p.fd_rowchunks.div((uint32_t)c), piece = c - row * (4 * p.W);
-    row_of[k] = c < p.nchunks ? row : (1 << 20);               // past the end: never inside the image
-    src_off[k] = row * p.W * 64 + 16 * piece;
-    dst_off[k] = 64 + row * p.pitch + 16 * (piece ^ ((piece >> 4) & 3));   // piece = 4 column + part: part ^= (column >> 2) & 3
+    const int row = (int)p.fd_rowchunks.div((uint32_t)c), piece = c - row * (S::PIECES * p.W);
+    const int col = piece / S::PIECES, part = piece % S::PIECES;
+    const int dst = C + row * p.pitch + col * C + 16 * (part ^ ((col >> S::KEY_SHIFT) & (S::PIECES - 1)));
+    where[k] = dst | ((c < p.nchunks ? row : 1024) << 20);      // past the end: never inside the image
   }
   auto tile_coords = [&](int tt, int &b, int &m0, int &row0) {
     const uint32_t bi = p.fd_tpi.div((uint32_t)tt);
@@ -79,18 +94,18 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   auto fetch_patch = [&](int tt, v4i (&buf)[MAXCH]) {
     int b, m0, row0;
     tile_coords(tt, b, m0, row0);
-    const uint8_t *src = p.x + ((long long)b * p.H + row0) * ((long long)p.W * 64);     // may point one row before the image
+    const uint8_t *src = p.x + ((long long)b * p.H + row0) * ((long long)p.W * C);     // may point one row before the image
 #pragma unroll
     for (int k = 0; k < MAXCH; ++k) {
       buf[k] = v4i{0, 0, 0, 0};
-      if ((unsigned)(row0 + row_of[k]) < (unsigned)p.H) buf[k] = *reinterpret_cast<const v4i *>(src + src_off[k]);
+      if ((unsigned)(row0 + (where[k] >> 20)) < (unsigned)p.H) buf[k] = *reinterpret_cast<const v4i *>(src + 16 * (tid + k * WS_NT));
     }
   };
   auto store_patch = [&](int which, const v4i (&buf)[MAXCH]) {
 #pragma unroll
     for (int k = 0; k < MAXCH; ++k)
-      if (row_of[k] < (1 << 20))
-        *reinterpret_cast<v4i *>(lds + which * patch_bytes + dst_off[k]) = v4i{buf[k].x ^ zx, buf[k].y ^ zx, buf[k].z ^ zx, buf[k].w ^ zx};
+      if ((where[k] >> 20) < 1024)
+        *reinterpret_cast<v4i *>(lds + which * patch_bytes + (where[k] & 0xfffff)) = v4i{buf[k].x ^ zx, buf[k].y ^ zx, buf[k].z ^ zx, buf[k].w ^ zx};
   };
 
   v4i nextbuf[MAXCH];
@@ -106,22 +121,21 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
     int b, m0, row0;
     tile_coords(t, b, m0, row0);
 
-    // where the windows of this lane's pixels start in the patch, per window column: the 16 bytes of
-    // this half of the first 32 channels; the other 32 channels are the piece ^ 2, 32 bytes to either
-    // side.  Pixels past the end of the image borrow the tile's first pixel.
-    int a0[MF][3], a1[MF][3];          // byte offsets in LDS
+    // Where the windows of this lane's pixels start in the patch, per window column: the piece that
+    // holds this half of the first 32 channels.  The same half of channels 32 k .. 32 k + 31 is the
+    // piece ^ 2 k, that is the byte offset ^ 32 k.  Pixels past the end of the image borrow the tile's
+    // first pixel.
+    int a0[MF][3];          // byte offsets in LDS
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf) {
-      int m = m0 + (TILE / 2) * wm + 32 * mf + l32;
+      int m = m0 + (32 * MF) * wm + 32 * mf + l32;
       if (m >= HW) m = m0;
       const int y = (int)p.fd_w.div((uint32_t)m), xq = m - y * p.W;
-      const int base = which * patch_bytes + 64 + (y - row0 - 1) * p.pitch;
+      const int base = which * patch_bytes + C + (y - row0 - 1) * p.pitch;
 #pragma unroll
       for (int sx = 0; sx < 3; ++sx) {
         const int cx = xq - 1 + sx;                                   // -1 and W are the border pixels
-        const int off = cx * 64 + 16 * (half ^ ((cx >> 2) & 3));
-        a0[mf][sx] = base + off;
-        a1[mf][sx] = base + (off ^ 32);
+        a0[mf][sx] = base + cx * C + 16 * (half ^ ((cx >> S::KEY_SHIFT) & (S::PIECES - 1)));
       }
     }
     v16i acc[MF];
@@ -134,27 +148,27 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
         acc[mf][4 * g] = s0.x; acc[mf][4 * g + 1] = s0.y; acc[mf][4 * g + 2] = s0.z; acc[mf][4 * g + 3] = s0.w;
       }
     }
-    // 18 K slices (9 taps x 2 halves of the channels); the fragments of slice i + 4 are requested
-    // before the matrix instructions of slice i are issued, so four slices of LDS latency are covered
+    // K slices: 9 taps x C / 32; the fragments of slice i + AHEAD are requested before the matrix
+    // instructions of slice i are issued, so that much LDS latency is covered
     auto frag = [&](int slice, int mf) {
-      const int tap = slice >> 1, k2 = slice & 1;
-      return *reinterpret_cast<const v4i *>(&lds[(k2 ? a1[mf][tap % 3] : a0[mf][tap % 3]) + (tap / 3) * p.pitch]);
+      const int tap = slice / S::KPT, k32 = slice % S::KPT;
+      return *reinterpret_cast<const v4i *>(&lds[(a0[mf][tap % 3] ^ (32 * k32)) + (tap / 3) * p.pitch]);
     };
-    constexpr int AHEAD = 4;
+    constexpr int AHEAD = S::AHEAD;
     v4i fb[AHEAD + 1][MF];
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i)
 #pragma unroll
       for (int mf = 0; mf < MF; ++mf) fb[i][mf] = frag(i, mf);
 #pragma unroll
-    for (int slice = 0; slice < 18; ++slice) {
-      if (slice + AHEAD < 18) {
+    for (int slice = 0; slice < KS; ++slice) {
+      if (slice + AHEAD < KS) {
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) fb[(slice + AHEAD) % (AHEAD + 1)][mf] = frag(slice + AHEAD, mf);
       }
 #pragma unroll
       for (int mf = 0; mf < MF; ++mf)
-        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice >> 1][slice & 1], fb[slice % (AHEAD + 1)][mf], acc[mf], 0, 0, 0);
+        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice], fb[slice % (AHEAD + 1)][mf], acc[mf], 0, 0, 0);
     }
 
     // requantise into the staging tile
@@ -165,18 +179,18 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
         int v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = med3(acc[mf][4 * g + j] >> p.shift, p.lo, p.hi);
-        *reinterpret_cast<uint32_t *>(stage + ((TILE / 2) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 8 * g + 4 * half) =
+        *reinterpret_cast<uint32_t *>(stage + ((32 * MF) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 8 * g + 4 * half) =
             pack4(v[0], v[1], v[2], v[3]);
       }
     if (tn < p.ntiles) store_patch(which ^ 1, nextbuf);
     if (tn + (int)gridDim.x < p.ntiles) fetch_patch(tn + gridDim.x, nextbuf);      // lands during the next tile
     __syncthreads();
 
-    // TILE pixels x 64 bytes, contiguous in the output: 16 bytes per store
-    uint8_t *yt = p.y + ((size_t)b * HW + m0) * 64;
+    // TILE pixels x C bytes, contiguous in the output: 16 bytes per store
+    uint8_t *yt = p.y + ((size_t)b * HW + m0) * C;
 #pragma unroll
-    for (int k = 0; k < TILE * 4 / WS_NT; ++k) {
-      const int c = tid + k * WS_NT, px = c >> 2, part = c & 3;
+    for (int k = 0; k < TILE * S::PIECES / WS_NT; ++k) {
+      const int c = tid + k * WS_NT, px = c / S::PIECES, part = c % S::PIECES;
       if (m0 + px < HW)
         *reinterpret_cast<v4i *>(yt + (size_t)c * 16) = *reinterpret_cast<const v4i *>(stage + px * OPITCH + 16 * part);
     }
@@ -185,52 +199,66 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   }
 }
 
-size_t ws_lds_bytes(int nrows, int pitch) { return 2 * (size_t)(64 + nrows * pitch) + (size_t)TILE * OPITCH; }
+constexpr size_t WS_LDS_MAX = 80 * 1024 - 1024;
 
-}  // namespace
-
-bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int W, int shift,
-                        const void *x, const void *w, const void *y) {
-  if (Cin != 64 || Cout != 64 || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
-  if (W < 8 || W > 64 || shift < 0) return false;
-  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
-  if (bits & 15) return false;
-  const int nrows = (W - 1 + TILE - 1) / W + 1 + 2;
-  return nrows * W * 4 <= MAXCH * WS_NT && ws_lds_bytes(nrows, (W + 1) * 64) <= (80 * 1024 - 512);
+template <int C> int ws_nrows(int W) { return (W - 1 + WsShape<C>::TILE - 1) / W + 1 + 2; }
+template <int C> size_t ws_lds_bytes(int W) {
+  return 2 * (size_t)(C + ws_nrows<C>(W) * (W + 1) * C) + (size_t)WsShape<C>::TILE * WsShape<C>::OPITCH;
+}
+template <int C> bool ws_fits(int W) {
+  return W >= 8 && W <= 64 && ws_nrows<C>(W) * W * (C / 16) <= MAXCH * WS_NT && ws_lds_bytes<C>(W) <= WS_LDS_MAX;
 }
 
-int launch_conv_ws(ConvWsParams p, hipStream_t stream) {
-  if (p.B <= 0) return 0;
-  if (p.H < 1 || p.W < 8 || p.W > 64 || p.shift < 0 || p.lo > p.hi ||
-      ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w) | reinterpret_cast<uintptr_t>(p.y) |
-        reinterpret_cast<uintptr_t>(p.acc0)) & 15))
-    return (int)hipErrorInvalidValue;
+template <int C>
+int launch_ws(ConvWsParams p, hipStream_t stream) {
+  using S = WsShape<C>;
+  if (!ws_fits<C>(p.W)) return (int)hipErrorInvalidValue;
   const int HW = p.H * p.W;
-  p.tiles_per_image = (HW + TILE - 1) / TILE;
+  p.tiles_per_image = (HW + S::TILE - 1) / S::TILE;
   const long long ntiles = (long long)p.B * p.tiles_per_image;
   if (ntiles > 0x7fffffffLL) return (int)hipErrorInvalidValue;
   p.ntiles = (int)ntiles;
-  p.nrows = (p.W - 1 + TILE - 1) / p.W + 1 + 2;       // rows TILE consecutive pixels can touch, plus one above and below
-  p.pitch = (p.W + 1) * 64;
-  p.nchunks = p.nrows * p.W * 4;
-  if (p.nchunks > MAXCH * WS_NT) return (int)hipErrorInvalidValue;
+  p.nrows = ws_nrows<C>(p.W);          // rows TILE consecutive pixels can touch, plus one above and below
+  p.pitch = (p.W + 1) * C;
+  p.nchunks = p.nrows * p.W * S::PIECES;
   p.fd_tpi = FastDiv((uint32_t)p.tiles_per_image);
   p.fd_w = FastDiv((uint32_t)p.W);
-  p.fd_rowchunks = FastDiv((uint32_t)(4 * p.W));
-  const size_t smem = ws_lds_bytes(p.nrows, p.pitch);
-  if (smem > (80 * 1024 - 512)) return (int)hipErrorInvalidValue;
+  p.fd_rowchunks = FastDiv((uint32_t)(S::PIECES * p.W));
+  const size_t smem = ws_lds_bytes<C>(p.W);
   static unsigned long long done_mask = 0;       // raising the dynamic LDS limit is per device and idempotent
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
   if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv_ws_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (80 * 1024 - 512));
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv_ws_kernel<C>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_MAX);
     if (e != hipSuccess) return (int)e;
     if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
   }
   const int grid = (int)(ntiles < 512 ? ntiles : 512);       // two workgroups per CU walk over the tiles
-  hipLaunchKernelGGL(conv_ws_kernel, dim3(grid), dim3(WS_NT), smem, stream, p);
+  hipLaunchKernelGGL(conv_ws_kernel<C>, dim3(grid), dim3(WS_NT), smem, stream, p);
   return (int)hipGetLastError();
+}
+
+}  // namespace
+
+int conv_ws_tile_pixels(int C) { return C == 64 ? WsShape<64>::TILE : WsShape<128>::TILE; }
+
+bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int W, int shift,
+                        const void *x, const void *w, const void *y) {
+  if (Cin != Cout || (Cin != 64 && Cin != 128) || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
+  if (shift < 0) return false;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
+  if (bits & 15) return false;
+  return Cin == 64 ? ws_fits<64>(W) : ws_fits<128>(W);
+}
+
+int launch_conv_ws(ConvWsParams p, hipStream_t stream) {
+  if (p.B <= 0) return 0;
+  if (p.H < 1 || p.shift < 0 || p.lo > p.hi || (p.C != 64 && p.C != 128) ||
+      ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w) | reinterpret_cast<uintptr_t>(p.y) |
+        reinterpret_cast<uintptr_t>(p.acc0)) & 15))
+    return (int)hipErrorInvalidValue;
+  return p.C == 64 ? launch_ws<64>(p, stream) : launch_ws<128>(p, stream);
 }
 
 }  // namespace f8

@@ -76,7 +76,8 @@ static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const voi
   if (!on || res || y2 || q.y_type == F8_S32) return false;
   // it pays once a workgroup walks over several tiles (measured: level with the general kernel at
   // 800 and 1600 tiles of 128 pixels, 15-20 % ahead at 6400)
-  if ((long long)g.B * ((g.H * g.W + 127) / 128) < 2048) return false;
+  const int tile = conv_ws_tile_pixels(g.Cin);
+  if ((long long)g.B * ((g.H * g.W + tile - 1) / tile) < 2048) return false;
   return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
@@ -89,7 +90,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
     wp.w = w;
     wp.acc0 = acc0;
     wp.y = static_cast<uint8_t *>(y);
-    wp.B = g.B; wp.H = g.H; wp.W = g.W;
+    wp.B = g.B; wp.H = g.H; wp.W = g.W; wp.C = g.Cin;
     wp.shift = q.fl_x + q.fl_w - q.fl_y; wp.lo = q.clip_lo; wp.hi = q.clip_hi;
     wp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
     wp.tiles_per_image = wp.ntiles = wp.nrows = wp.pitch = wp.nchunks = 0;
@@ -147,7 +148,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
 }
 
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
-  if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return "conv3x3_ws<64x64>";
+  if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
   p.y2 = nullptr; p.shift2 = 0;

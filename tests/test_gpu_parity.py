@@ -182,27 +182,33 @@ def test_resnet50_private_fractional_lengths(oracle):
 
 
 def test_weights_stationary_3x3_64(oracle):
-    """The 3x3 64 -> 64 stride-1 layers take a kernel of their own (weights in registers, input rows
-    in LDS): image widths from 8 to 64, heights that leave ragged last tiles, one-row images, every
-    input / output type, a shift of zero, clips inside the range."""
+    """The 3x3 64 -> 64 and 128 -> 128 stride-1 layers take a kernel of their own (weights in registers,
+    input rows in LDS): image widths from 8 to 64, heights that leave ragged last tiles, one-row images,
+    every input / output type, a shift of zero, clips inside the range."""
     rng = np.random.default_rng(640)
-    # batches large enough for the library to pick this kernel (at least 2048 tiles of 128 pixels)
-    for B, H, W, xt, yt, shift, clip in ((85, 56, 56, "u8", "u8", 9, None), (2048, 13, 8, "s8", "s8", 7, (-50, 90)),
-                                         (2051, 1, 64, "u8", "s8", 8, None), (1030, 7, 33, "s8", "u8", 0, (3, 200)),
-                                         (410, 31, 17, "u8", "u8", 11, (0, 1)), (411, 9, 64, "u8", "u8", 6, None),
-                                         (256, 100, 9, "s8", "u8", 10, None), (2, 56, 56, "u8", "u8", 9, None)):
-        x, L, _ = wl.random_conv_case(rng, B, H, W, 64, 64, 3, 3, 1, 1, xt, yt, None, shift=shift, clip=clip)
+    # batches large enough for the library to pick this kernel (at least 2048 tiles of 128 pixels at
+    # 64 channels, of 64 pixels at 128)
+    for C, B, H, W, xt, yt, shift, clip in ((64, 85, 56, 56, "u8", "u8", 9, None), (64, 2048, 13, 8, "s8", "s8", 7, (-50, 90)),
+                                            (64, 2051, 1, 64, "u8", "s8", 8, None), (64, 1030, 7, 33, "s8", "u8", 0, (3, 200)),
+                                            (64, 410, 31, 17, "u8", "u8", 11, (0, 1)), (64, 411, 9, 64, "u8", "u8", 6, None),
+                                            (64, 256, 100, 9, "s8", "u8", 10, None), (64, 2, 56, 56, "u8", "u8", 9, None),
+                                            (128, 158, 28, 28, "u8", "u8", 10, None), (128, 2048, 5, 8, "s8", "s8", 8, (-50, 90)),
+                                            (128, 1030, 3, 38, "s8", "u8", 0, (3, 200)), (128, 700, 14, 14, "u8", "s8", 9, None),
+                                            (128, 2049, 1, 33, "u8", "u8", 7, None), (128, 90, 47, 31, "s8", "u8", 11, (0, 1)),
+                                            (128, 2, 28, 28, "u8", "u8", 10, None)):
+        x, L, _ = wl.random_conv_case(rng, B, H, W, C, C, 3, 3, 1, 1, xt, yt, None, shift=shift, clip=clip)
         # images are independent: the single-threaded oracle runs on slices of the batch in host threads
         from concurrent.futures import ThreadPoolExecutor
         parts = np.array_split(np.arange(B), min(B, host_threads()))
         with ThreadPoolExecutor(len(parts)) as ex:
             outs = list(ex.map(lambda idx: oracle.conv2d_fixed(np.ascontiguousarray(x[idx]), L.w, L.bias, L, (1, 1), (1, 1)), parts))
         want = np.concatenate(outs)
-        assert_same(gpu_layer(L, x), want, "ws 3x3 %s" % str((B, H, W, xt, yt, shift)))
+        assert_same(gpu_layer(L, x), want, "ws 3x3 %s" % str((C, B, H, W, xt, yt, shift)))
     # in a chain the kernel's name shows: chosen at batch 256 of the full-size network, not for a few images
     _, net = wl.config4(batch=1)
     chain = f8.Chain(net)
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 3
+    assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<128x128>") == 3
     assert [chain.layer_info(i, 4)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
 
 
