@@ -28,11 +28,12 @@ MEASURED_TRAFFIC_MB = {
     "conv_fast<128x128,k64,s2>": 174.97,
     "conv_fast<128x128,k64,s3>": 205.96,
     "conv_fast<128x64,k64,s2>": 205.78,
-    "conv3x3_ws<64x64>": 184.81,
-    "stem_pool_fused": 272.16,        # re-layout pass 94.70 + fused stem and pool 177.46
-    "conv_fast<128x128,k128,s2>": 74.90,
+    "conv3x3_ws<64x64>": 184.83,
+    "conv3x3_ws<128x128>": 97.42,
+    "stem_pool_fused": 272.19,        # re-layout pass 94.70 + fused stem and pool 177.49
+    "conv_fast<128x128,k128,s2>": 141.18,
     "conv_fast<256x256,k128,s2,w4x2>": 57.18,
-    "conv_fast<256x128,k128,s2,w4x2>": 41.71,
+    "conv_fast<256x128,k128,s2,w4x2>": 41.72,
 }
 
 
