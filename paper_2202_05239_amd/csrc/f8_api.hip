@@ -81,9 +81,43 @@ static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const voi
   return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
+// So do the 1x1 64 -> 256 layers (weights in registers, every wave streams pixels on its own).
+static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
+                      const f8_quant &q, const void *y2) {
+  static const int on = [] { const char *e = getenv("F8_PW_WS"); return e ? atoi(e) : 1; }();   // tuning aid
+  if (!on || y2 || q.y_type == F8_S32 || (res && q.res_type == F8_S32)) return false;
+  // it pays once every workgroup walks over several blocks of pixels
+  if ((long long)g.B * g.H * g.W < 131072) return false;
+  return pw_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
+}
+
 f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
                        const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
-                       const f8_requant2 *q2, void *y2) {
+                       const f8_requant2 *q2, void *y2, const ConvTail *tail) {
+  const bool pw_ws = use_pw_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0;
+  if (tail && !(pw_ws && tail->Cout == 64 && tail->q.y_type != F8_S32)) return F8_ERR_UNSUPPORTED;
+  if (pw_ws) {
+    PwWsParams pp;
+    pp.t_w = nullptr; pp.t_acc0 = nullptr; pp.t_y = nullptr;
+    pp.t_shift = pp.t_lo = pp.t_hi = 0; pp.t_xor = 0;
+    if (tail) {
+      pp.t_w = tail->w; pp.t_acc0 = tail->acc0; pp.t_y = static_cast<uint8_t *>(tail->y);
+      pp.t_shift = tail->q.fl_x + tail->q.fl_w - tail->q.fl_y;
+      pp.t_lo = tail->q.clip_lo; pp.t_hi = tail->q.clip_hi;
+      pp.t_xor = tail->q.x_type == F8_U8 ? 0x80808080u : 0u;
+    }
+    pp.x = static_cast<const uint8_t *>(x);
+    pp.w = w;
+    pp.acc0 = acc0;
+    pp.res = static_cast<const uint8_t *>(res);
+    pp.y = static_cast<uint8_t *>(y);
+    pp.M = (long long)g.B * g.H * g.W;
+    pp.shift = q.fl_x + q.fl_w - q.fl_y; pp.lo = q.clip_lo; pp.hi = q.clip_hi;
+    pp.res_signed = q.res_type == F8_S8;
+    pp.res_d = res ? q.fl_x + q.fl_w - q.fl_res : 0;
+    pp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
+    return launch_pw_ws(pp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+  }
   if (use_conv_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0) {
     ConvWsParams wp;
     wp.x = static_cast<const uint8_t *>(x);
@@ -147,7 +181,12 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   return launch_conv_igemm(p, vec, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
 }
 
+bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
+  return Cout2 == 64 && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr);
+}
+
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
+  if (use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins

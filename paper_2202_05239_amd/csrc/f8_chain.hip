@@ -83,6 +83,19 @@ struct f8_chain {
   bool use_fusion() const { return fusion && !keep_all; }
   bool stem_pool = true;
   int pool_role(size_t i) const { return stem_pool && !keep_all ? stem[i].pool : 0; }
+  // A dense layer and the 1x1 layer that reads its output in one launch: tail[i] = 1 for the first,
+  // 2 for the 1x1 layer behind it (candidates; both tensors are still written).  Whether the
+  // kernel that can do this is chosen depends on the batch.
+  std::vector<int> tail;               // per layer
+  bool conv_tail = true;
+  int tail_role(size_t i, int batch) const {
+    if (!conv_tail || tail[i] == 0) return 0;
+    const size_t head = tail[i] == 1 ? i : i - 1;
+    if (use_fusion() && (fused[head].role != 0 || fused[head + 1].role != 0)) return 0;
+    Geom g = geom[head];
+    g.B = batch;
+    return conv_tail_ok(g, layers[head].q, layers[head + 1].Cout) ? tail[i] : 0;
+  }
   std::vector<Tensor> tensors;
   std::vector<size_t> acc0_off;        // per layer: byte offset in the constants region
   size_t const_bytes = 0;
@@ -133,6 +146,13 @@ struct f8_chain {
         free_list.erase(free_list.begin() + i);
       }
     };
+    // tail candidates as the planner sees them: any batch, but not inside a fused block
+    auto tail_plan = [&](size_t li) {
+      if (tail[li] == 0) return 0;
+      const size_t head = tail[li] == 1 ? li : li - 1;
+      if (use_fusion() && (fused[head].role != 0 || fused[head + 1].role != 0)) return 0;
+      return tail[li];
+    };
     for (size_t li = 0; li < layers.size(); ++li) {
       if (pool_role(li) == 2) continue;
       if (pool_role(li) == 1) {
@@ -156,7 +176,13 @@ struct f8_chain {
       }
       if (stem[li].on) stem[li].x_off_per_image = alloc(round256(stem[li].x_bytes_per_image));
       Tensor &d = tensors[layers[li].dst];
-      if (!d.external) d.offset_per_image = alloc(round256(d.bytes_per_image));
+      // (the output of a 1x1 layer that may run inside the previous launch got its place there)
+      if (!d.external && tail_plan(li) != 2) d.offset_per_image = alloc(round256(d.bytes_per_image));
+      if (tail_plan(li) == 1) {
+        // written by this launch too: must not share memory with what this layer reads
+        Tensor &dt = tensors[layers[li + 1].dst];
+        if (!dt.external) dt.offset_per_image = alloc(round256(dt.bytes_per_image));
+      }
       if (layers[li].dst2 > 0) {
         Tensor &d2 = tensors[layers[li].dst2];
         d2.offset_per_image = alloc(round256(d2.bytes_per_image));
@@ -258,6 +284,7 @@ struct f8_chain {
       const BlockParams bp = block_params(i, x, out, workspace, batch);
       return launch_block_fused(bp, s) == 0 ? F8_OK : F8_ERR_DEVICE;
     }
+    if (tail_role(i, batch) == 2) return F8_OK;
     const void *src = tensor_ptr(L.src, x, out, workspace, batch);
     void *dst = tensor_ptr(L.dst, x, out, workspace, batch);
     const void *res = L.res >= 0 ? tensor_ptr(L.res, x, out, workspace, batch) : nullptr;
@@ -273,8 +300,18 @@ struct f8_chain {
           src = xp;
         }
         void *dst2 = L.dst2 > 0 ? tensor_ptr(L.dst2, x, out, workspace, batch) : nullptr;
+        ConvTail ct;
+        const bool with_tail = tail_role(i, batch) == 1;
+        if (with_tail) {
+          const f8_layer_desc &T = layers[i + 1];
+          ct.w = T.w;
+          ct.acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i + 1]);
+          ct.y = tensor_ptr(T.dst, x, out, workspace, batch);
+          ct.Cout = T.Cout;
+          ct.q = T.q;
+        }
         return enqueue_conv(src, conv_weights(i, workspace), acc0, workspace, dst, res, conv_geom(i, batch), L.q, s,
-                            dst2 ? &L.q2 : nullptr, dst2);
+                            dst2 ? &L.q2 : nullptr, dst2, with_tail ? &ct : nullptr);
       }
       case F8_OP_DWCONV: return enqueue_dwconv(src, L.w, L.bias, dst, res, g, L.q, s);
       case F8_OP_MAXPOOL: return enqueue_maxpool(src, dst, g, L.q.x_type, s);
@@ -396,6 +433,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     }
     c->stem.push_back(sm);
     c->fused.push_back(Fused());
+    c->tail.push_back(0);
   }
   if (st != F8_OK) { delete c; return st; }
   c->last_tensor = c->layers.back().dst;
@@ -414,6 +452,27 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     if (c->tensors[L.dst].last_use != (int)i + 1 || L.dst == c->last_tensor) continue;
     c->stem[i].pool = 1;
     c->stem[i + 1].pool = 2;
+  }
+  { const char *e = getenv("F8_CONV_TAIL"); c->conv_tail = !(e && atoi(e) == 0); }      // tuning aid
+  // a 1x1 64 -> 256 layer followed by a 1x1 256 -> 64 layer that reads it (the hand-over between two
+  // bottleneck blocks): the second can run on each block of the first one's output while it is in LDS.
+  // Every tensor involved lives in the arena (aligned); weights must be 16-byte aligned.
+  for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
+    const f8_layer_desc &L = c->layers[i], &T = c->layers[i + 1];
+    if (c->stem[i].pool != 0 || c->stem[i].on || c->stem[i + 1].on) continue;
+    if (L.op != F8_OP_CONV || T.op != F8_OP_CONV || L.dst2 > 0 || T.dst2 > 0 || T.res >= 0 || T.src != L.dst) continue;
+    if (L.Cin != 64 || L.Cout != 256 || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h != 0 || L.pad_w != 0) continue;
+    if (T.Cout != 64 || T.R != 1 || T.S != 1 || T.stride_h != 1 || T.stride_w != 1 || T.pad_h != 0 || T.pad_w != 0) continue;
+    if (L.q.y_type == F8_S32 || (L.res >= 0 && L.q.res_type == F8_S32) || L.q.fl_x + L.q.fl_w - L.q.fl_y < 0) continue;
+    if (T.q.y_type == F8_S32 || T.q.fl_x + T.q.fl_w - T.q.fl_y < 0) continue;
+    if ((reinterpret_cast<uintptr_t>(L.w) | reinterpret_cast<uintptr_t>(T.w)) & 15) continue;
+    const int ids[4] = {L.src, L.res, L.dst, T.dst};
+    bool arena_only = true;
+    for (int id : ids) arena_only = arena_only && (id < 0 || !c->tensors[id].external);
+    if (!arena_only) continue;
+    c->tail[i] = 1;
+    c->tail[i + 1] = 2;
+    ++i;
   }
   // inverted-residual blocks that can run as one kernel
   for (size_t i = 0; i + 2 < c->layers.size(); ++i) {
@@ -636,6 +695,19 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
     if (alg_bytes) *alg_bytes = fb;
     return F8_OK;
   }
+  if (c->tail_role((size_t)layer, batch) == 2) {
+    // accounted to the layer in front, whose launch computes this one
+    const char *fname = "(fused)";
+    if (kernel_name && name_len > 0) {
+      int i = 0;
+      for (; fname[i] && i < name_len - 1; ++i) kernel_name[i] = fname[i];
+      kernel_name[i] = 0;
+    }
+    if (alg_ops) *alg_ops = 0.0;
+    if (alg_bytes) *alg_bytes = 0.0;
+    return F8_OK;
+  }
+  const bool with_tail = c->tail_role((size_t)layer, batch) == 1;
   const double M = (double)batch * g.P * g.Q;
   // input pixels a strided window actually touches
   const double rows = g.sh >= g.R ? (double)g.P * g.R : (double)std::min(g.H, (g.P - 1) * g.sh + g.R);
@@ -650,6 +722,13 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       name = conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
+      if (with_tail) {
+        // plus the 1x1 layer behind it: its output and weights; its input never leaves the chip
+        const f8_layer_desc &T = c->layers[layer + 1];
+        name = "pw1x1_ws<64x256>+1x1<64>";
+        ops += 2.0 * M * (double)T.Cin * T.Cout;
+        bytes += M * T.Cout + (double)T.Cin * T.Cout + 4.0 * T.Cout;
+      }
       break;
     }
     case F8_OP_DWCONV:

@@ -8,6 +8,7 @@
 #include "../../include/f8.h"
 #include "conv_igemm.h"
 #include "conv_ws.h"
+#include "pw_ws.h"
 #include "dwconv_pool.h"
 
 namespace f8 {
@@ -41,9 +42,21 @@ f8_status check_align(const int32_t *bias, const void *y, const f8_quant &q, con
 // Enqueue the dense layer with a ready acc0 vector (device, acc0_padded(Cout) ints) and a
 // device pointer to at least 64 bytes of zeros.
 // q2 / y2: optional second output format and tensor (both null for none).
+// tail: optional 1x1 stride-1 layer that reads y, computed by the same launch (the pair must have
+// passed conv_tail_ok; the call fails otherwise).
+struct ConvTail {
+  const int8_t *w;          // [Cout2][Cout]
+  const int32_t *acc0;      // its folded start values
+  void *y;                  // [B][P][Q][Cout2], 8-bit
+  int Cout;
+  f8_quant q;
+};
 f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
                        const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
-                       const f8_requant2 *q2 = nullptr, void *y2 = nullptr);
+                       const f8_requant2 *q2 = nullptr, void *y2 = nullptr, const ConvTail *tail = nullptr);
+// Whether enqueue_conv can take a tail of Cout2 channels behind this layer at this batch (operands
+// assumed 16-byte aligned, one output format, 8-bit residual if any).
+bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2);
 // Checks of a second output format against the first (8-bit types, clip range, shift limits).
 f8_status check_requant2(const f8_quant &q, const f8_requant2 *q2);
 // Name of the kernel enqueue_conv launches for this layer (operands assumed 16-byte aligned).

@@ -114,7 +114,7 @@ def test_config2_mbv2_block(oracle, with_residual):
 
 # ------------------------------------------------------------------------- whole networks
 
-def check_network(oracle, x, net, oracle_images, what):
+def check_network(oracle, x, net, oracle_images, what, lean_is_smaller=True):
     """GPU runs the full batch; the oracle runs the listed images (images are independent)."""
     xt = torch.from_numpy(x).to(DEV)
     chain = f8.Chain(net, keep_all=True).prepare(x.shape[0])
@@ -135,7 +135,10 @@ def check_network(oracle, x, net, oracle_images, what):
     b = lean.run(xt)
     torch.cuda.synchronize()
     assert torch.equal(a, out) and torch.equal(b, out), what + " lean plan / rerun"
-    assert lean.workspace_bytes(x.shape[0]) < chain.workspace_bytes(x.shape[0])
+    if lean_is_smaller:          # (a net of a few layers may have nothing to reuse)
+        assert lean.workspace_bytes(x.shape[0]) < chain.workspace_bytes(x.shape[0])
+    else:
+        assert lean.workspace_bytes(x.shape[0]) <= chain.workspace_bytes(x.shape[0])
     # fused inverted-residual blocks (where the network has any): the same logits again
     fused = f8.Chain(net, fusion=True).prepare(x.shape[0])
     if any(fused.layer_info(i, x.shape[0])[0] == "block_fused" for i in range(len(net.layers))):
@@ -210,6 +213,68 @@ def test_weights_stationary_3x3_64(oracle):
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 3
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<128x128>") == 3
     assert [chain.layer_info(i, 4)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
+
+
+def test_weights_stationary_1x1_64_to_256(oracle):
+    """The 1x1 64 -> 256 layers at large batch take a kernel of their own (weights in registers, every
+    wave streams 32-pixel blocks): with and without residual, residual scales above and below the
+    accumulator's, every type combination, pixel counts that leave a ragged last block, a shift of
+    zero, clips inside the range."""
+    from concurrent.futures import ThreadPoolExecutor
+    rng = np.random.default_rng(6400)
+    for B, H, W, xt, yt, rt, shift, clip in ((43, 56, 56, "u8", "u8", "u8", 9, None), (2049, 8, 8, "s8", "s8", "s8", 7, (-50, 90)),
+                                             (131073, 1, 1, "u8", "s8", None, 8, None), (1031, 7, 19, "s8", "u8", "u8", 0, (3, 200)),
+                                             (410, 31, 11, "u8", "u8", "s8", 11, (0, 1)), (300, 21, 21, "u8", "u8", None, 6, None),
+                                             (2, 56, 56, "u8", "u8", "u8", 9, None)):
+        for rep in range(2 if rt else 1):      # two draws of the residual's fractional length
+            x, L, res = wl.random_conv_case(rng, B, H, W, 64, 256, 1, 1, 1, 0, xt, yt, rt, shift=shift, clip=clip)
+            parts = np.array_split(np.arange(B), min(B, host_threads()))
+            with ThreadPoolExecutor(len(parts)) as ex:
+                outs = list(ex.map(lambda idx: oracle.conv2d_fixed(np.ascontiguousarray(x[idx]), L.w, L.bias, L, (1, 1), (0, 0),
+                                                                   None if res is None else np.ascontiguousarray(res[idx])), parts))
+            assert_same(gpu_layer(L, x, res), np.concatenate(outs), "pw ws %s" % str((B, H, W, xt, yt, rt, shift, L.fl_res)))
+    _, net = wl.config4(batch=1)
+    chain = f8.Chain(net)
+    # the shortcut projection and the last block's closing layer; the other two closing layers also
+    # compute the layer that opens the next block
+    names = [chain.layer_info(i, 256)[0] for i in range(len(net.layers))]
+    assert names.count("pw1x1_ws<64x256>") == 2 and names.count("pw1x1_ws<64x256>+1x1<64>") == 2
+    assert not any(chain.layer_info(i, 4)[0].startswith("pw1x1_ws") for i in range(len(net.layers)))
+
+
+def test_1x1_layer_computed_behind_the_64_to_256_layer(oracle):
+    """A 1x1 64 -> 256 layer followed by a 1x1 256 -> 64 layer that reads its output (the hand-over
+    between two bottleneck blocks): at large batch one launch computes both, the second from each
+    block of the first one's output while it is on chip; both tensors are still written.  Every
+    tensor against the oracle; the one-launch path against the two-launch path; small batches keep
+    two launches."""
+    cases = ((32, 128, 48, True, True, True),      # unsigned in between, residual
+             (23, 250, 16, False, True, False),    # signed tensor in between, no residual, ragged last block
+             (19, 370, 32, True, False, True),     # signed output behind
+             (37, 97, 16, False, False, True))     # signed everywhere, ragged
+    for k, (hw, batch, cin, relu1, relu2, with_res) in enumerate(cases):
+        rng = np.random.default_rng(900 + k)
+        b = wl._NetBuilder("tail%d" % k, rng, hw, cin, "u8", 6, (5, 9), (2, 6), True)
+        r = b.conv("short", 0, 256, 1, 1, 0, relu=(k % 2 == 0))
+        m = b.conv("mid", 0, 64, 1, 1, 0)
+        h = b.conv("front", m, 256, 1, 1, 0, relu=relu1, res=r if with_res else -1)
+        t = b.conv("behind", h, 64, 1, 1, 0, relu=relu2)
+        e = b.conv("other_reader", h, 64, 1, 1, 0, relu=False)
+        b.conv("join", t, 64, 1, 1, 0, res=e)
+        net = b.net
+        x = wl.draw_u8(rng, (batch, hw, hw, cin))
+        names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(len(net.layers))]
+        assert names[2] == "pw1x1_ws<64x256>+1x1<64>" and names[3] == "(fused)", names
+        assert "(fused)" not in [f8.Chain(net).layer_info(i, 8)[0] for i in range(len(net.layers))]
+        imgs = sorted(set([0, 1, batch // 2, batch - 2, batch - 1]))
+        out = check_network(oracle, x, net, imgs, "1x1 behind 64->256, case %d" % k, lean_is_smaller=False)
+        # the two-launch path: the same chain below the batch where one launch pays
+        small = f8.Chain(net).prepare(8)
+        xt = torch.from_numpy(x).to(DEV)
+        for i0 in (0, batch - 8):
+            part = small.run(xt[i0:i0 + 8].contiguous())
+            torch.cuda.synchronize()
+            assert torch.equal(part, out[i0:i0 + 8]), "two launches, case %d" % k
 
 
 def test_fused_stem_and_pool(oracle):
