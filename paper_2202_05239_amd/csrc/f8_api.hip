@@ -95,13 +95,13 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
                        const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
                        const f8_requant2 *q2, void *y2, const ConvTail *tail) {
   const bool pw_ws = use_pw_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0;
-  if (tail && !(pw_ws && tail->Cout == 64 && tail->q.y_type != F8_S32)) return F8_ERR_UNSUPPORTED;
+  if (tail && !(pw_ws && (tail->Cout == 64 || tail->Cout == 128) && tail->q.y_type != F8_S32)) return F8_ERR_UNSUPPORTED;
   if (pw_ws) {
     PwWsParams pp;
     pp.t_w = nullptr; pp.t_acc0 = nullptr; pp.t_y = nullptr;
-    pp.t_shift = pp.t_lo = pp.t_hi = 0; pp.t_xor = 0;
+    pp.t_n = pp.t_shift = pp.t_lo = pp.t_hi = 0; pp.t_xor = 0;
     if (tail) {
-      pp.t_w = tail->w; pp.t_acc0 = tail->acc0; pp.t_y = static_cast<uint8_t *>(tail->y);
+      pp.t_w = tail->w; pp.t_acc0 = tail->acc0; pp.t_y = static_cast<uint8_t *>(tail->y); pp.t_n = tail->Cout;
       pp.t_shift = tail->q.fl_x + tail->q.fl_w - tail->q.fl_y;
       pp.t_lo = tail->q.clip_lo; pp.t_hi = tail->q.clip_hi;
       pp.t_xor = tail->q.x_type == F8_U8 ? 0x80808080u : 0u;
@@ -182,7 +182,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
 }
 
 bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
-  return Cout2 == 64 && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr);
+  return (Cout2 == 64 || Cout2 == 128) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr);
 }
 
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {

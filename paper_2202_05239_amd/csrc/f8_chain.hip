@@ -84,17 +84,20 @@ struct f8_chain {
   bool stem_pool = true;
   int pool_role(size_t i) const { return stem_pool && !keep_all ? stem[i].pool : 0; }
   // A dense layer and the 1x1 layer that reads its output in one launch: tail[i] = 1 for the first,
-  // 2 for the 1x1 layer behind it (candidates; both tensors are still written).  Whether the
-  // kernel that can do this is chosen depends on the batch.
-  std::vector<int> tail;               // per layer
+  // 2 for the 1x1 layer behind it, tail_peer[i] = the other layer of the pair (candidates; both
+  // tensors are still written).  Whether the kernel that can do this is chosen depends on the batch.
+  std::vector<int> tail, tail_peer;    // per layer
   bool conv_tail = true;
+  bool tail_in_fused_block(size_t i) const {
+    const size_t a = tail[i] == 1 ? i : (size_t)tail_peer[i], b = tail[i] == 1 ? (size_t)tail_peer[i] : i;
+    return use_fusion() && (fused[a].role != 0 || fused[b].role != 0);
+  }
   int tail_role(size_t i, int batch) const {
-    if (!conv_tail || tail[i] == 0) return 0;
-    const size_t head = tail[i] == 1 ? i : i - 1;
-    if (use_fusion() && (fused[head].role != 0 || fused[head + 1].role != 0)) return 0;
+    if (!conv_tail || tail[i] == 0 || tail_in_fused_block(i)) return 0;
+    const size_t head = tail[i] == 1 ? i : (size_t)tail_peer[i], behind = tail[i] == 1 ? (size_t)tail_peer[i] : i;
     Geom g = geom[head];
     g.B = batch;
-    return conv_tail_ok(g, layers[head].q, layers[head + 1].Cout) ? tail[i] : 0;
+    return conv_tail_ok(g, layers[head].q, layers[behind].Cout) ? tail[i] : 0;
   }
   std::vector<Tensor> tensors;
   std::vector<size_t> acc0_off;        // per layer: byte offset in the constants region
@@ -147,12 +150,7 @@ struct f8_chain {
       }
     };
     // tail candidates as the planner sees them: any batch, but not inside a fused block
-    auto tail_plan = [&](size_t li) {
-      if (tail[li] == 0) return 0;
-      const size_t head = tail[li] == 1 ? li : li - 1;
-      if (use_fusion() && (fused[head].role != 0 || fused[head + 1].role != 0)) return 0;
-      return tail[li];
-    };
+    auto tail_plan = [&](size_t li) { return tail[li] == 0 || tail_in_fused_block(li) ? 0 : tail[li]; };
     for (size_t li = 0; li < layers.size(); ++li) {
       if (pool_role(li) == 2) continue;
       if (pool_role(li) == 1) {
@@ -180,7 +178,7 @@ struct f8_chain {
       if (!d.external && tail_plan(li) != 2) d.offset_per_image = alloc(round256(d.bytes_per_image));
       if (tail_plan(li) == 1) {
         // written by this launch too: must not share memory with what this layer reads
-        Tensor &dt = tensors[layers[li + 1].dst];
+        Tensor &dt = tensors[layers[tail_peer[li]].dst];
         if (!dt.external) dt.offset_per_image = alloc(round256(dt.bytes_per_image));
       }
       if (layers[li].dst2 > 0) {
@@ -303,9 +301,9 @@ struct f8_chain {
         ConvTail ct;
         const bool with_tail = tail_role(i, batch) == 1;
         if (with_tail) {
-          const f8_layer_desc &T = layers[i + 1];
+          const f8_layer_desc &T = layers[tail_peer[i]];
           ct.w = T.w;
-          ct.acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i + 1]);
+          ct.acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[tail_peer[i]]);
           ct.y = tensor_ptr(T.dst, x, out, workspace, batch);
           ct.Cout = T.Cout;
           ct.q = T.q;
@@ -434,6 +432,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     c->stem.push_back(sm);
     c->fused.push_back(Fused());
     c->tail.push_back(0);
+    c->tail_peer.push_back(-1);
   }
   if (st != F8_OK) { delete c; return st; }
   c->last_tensor = c->layers.back().dst;
@@ -454,25 +453,33 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     c->stem[i + 1].pool = 2;
   }
   { const char *e = getenv("F8_CONV_TAIL"); c->conv_tail = !(e && atoi(e) == 0); }      // tuning aid
-  // a 1x1 64 -> 256 layer followed by a 1x1 256 -> 64 layer that reads it (the hand-over between two
+  // a 1x1 64 -> 256 layer and a 1x1 layer of 64 or 128 channels that reads it (the hand-over between two
   // bottleneck blocks): the second can run on each block of the first one's output while it is in LDS.
-  // Every tensor involved lives in the arena (aligned); weights must be 16-byte aligned.
+  // It is the next layer, or the one after it when the layer between them takes no part in a pair (the
+  // shortcut projection of a new stage).  Every tensor involved lives in the arena (aligned); weights
+  // must be 16-byte aligned.
   for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
-    const f8_layer_desc &L = c->layers[i], &T = c->layers[i + 1];
-    if (c->stem[i].pool != 0 || c->stem[i].on || c->stem[i + 1].on) continue;
-    if (L.op != F8_OP_CONV || T.op != F8_OP_CONV || L.dst2 > 0 || T.dst2 > 0 || T.res >= 0 || T.src != L.dst) continue;
+    const f8_layer_desc &L = c->layers[i];
+    if (c->tail[i] != 0 || c->stem[i].pool != 0 || c->stem[i].on) continue;
+    if (L.op != F8_OP_CONV || L.dst2 > 0) continue;
     if (L.Cin != 64 || L.Cout != 256 || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h != 0 || L.pad_w != 0) continue;
-    if (T.Cout != 64 || T.R != 1 || T.S != 1 || T.stride_h != 1 || T.stride_w != 1 || T.pad_h != 0 || T.pad_w != 0) continue;
     if (L.q.y_type == F8_S32 || (L.res >= 0 && L.q.res_type == F8_S32) || L.q.fl_x + L.q.fl_w - L.q.fl_y < 0) continue;
-    if (T.q.y_type == F8_S32 || T.q.fl_x + T.q.fl_w - T.q.fl_y < 0) continue;
-    if ((reinterpret_cast<uintptr_t>(L.w) | reinterpret_cast<uintptr_t>(T.w)) & 15) continue;
-    const int ids[4] = {L.src, L.res, L.dst, T.dst};
-    bool arena_only = true;
-    for (int id : ids) arena_only = arena_only && (id < 0 || !c->tensors[id].external);
-    if (!arena_only) continue;
-    c->tail[i] = 1;
-    c->tail[i + 1] = 2;
-    ++i;
+    for (size_t j = i + 1; j <= i + 2 && j < c->layers.size(); ++j) {
+      const f8_layer_desc &T = c->layers[j];
+      if (c->tail[j] != 0 || c->stem[j].on || c->stem[j].pool != 0) break;
+      const bool fits = T.op == F8_OP_CONV && T.src == L.dst && T.dst2 <= 0 && T.res < 0 && (T.Cout == 64 || T.Cout == 128) &&
+                        T.R == 1 && T.S == 1 && T.stride_h == 1 && T.stride_w == 1 && T.pad_h == 0 && T.pad_w == 0 &&
+                        T.q.y_type != F8_S32 && T.q.fl_x + T.q.fl_w - T.q.fl_y >= 0 &&
+                        ((reinterpret_cast<uintptr_t>(L.w) | reinterpret_cast<uintptr_t>(T.w)) & 15) == 0;
+      const int ids[4] = {L.src, L.res, L.dst, T.dst};
+      bool arena_only = true;
+      for (int id : ids) arena_only = arena_only && (id < 0 || !c->tensors[id].external);
+      if (fits && arena_only) {
+        c->tail[i] = 1; c->tail_peer[i] = (int)j;
+        c->tail[j] = 2; c->tail_peer[j] = (int)i;
+        break;
+      }
+    }
   }
   // inverted-residual blocks that can run as one kernel
   for (size_t i = 0; i + 2 < c->layers.size(); ++i) {
@@ -724,8 +731,8 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       if (with_tail) {
         // plus the 1x1 layer behind it: its output and weights; its input never leaves the chip
-        const f8_layer_desc &T = c->layers[layer + 1];
-        name = "pw1x1_ws<64x256>+1x1<64>";
+        const f8_layer_desc &T = c->layers[c->tail_peer[layer]];
+        name = T.Cout == 64 ? "pw1x1_ws<64x256>+1x1<64>" : "pw1x1_ws<64x256>+1x1<128>";
         ops += 2.0 * M * (double)T.Cin * T.Cout;
         bytes += M * T.Cout + (double)T.Cin * T.Cout + 4.0 * T.Cout;
       }

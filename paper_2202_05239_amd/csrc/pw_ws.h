@@ -16,12 +16,12 @@ struct PwWsParams {
   int shift, lo, hi;     // requantisation (shift >= 0)
   int res_signed, res_d; // residual type; its shift to the accumulator scale (left if >= 0, rounding right if < 0)
   uint32_t x_xor;        // 0x80808080 when x is unsigned
-  // Optional 1x1 layer of 64 channels that reads y, computed on each block of y while it is in LDS:
-  // t_y[m][n2] = clip((t_acc0[n2] + sum_n y[m][n] t_w[n2][n]) >> t_shift).  t_w == nullptr: none.
-  const int8_t *t_w;     // [64][256]
-  const int32_t *t_acc0; // [64] folded start values
-  uint8_t *t_y;          // [M][64]
-  int t_shift, t_lo, t_hi;
+  // Optional 1x1 layer of t_n = 64 or 128 channels that reads y, computed on each block of y while it
+  // is in LDS: t_y[m][n2] = clip((t_acc0[n2] + sum_n y[m][n] t_w[n2][n]) >> t_shift).  t_w == nullptr: none.
+  const int8_t *t_w;     // [t_n][256]
+  const int32_t *t_acc0; // [t_n] folded start values
+  uint8_t *t_y;          // [M][t_n]
+  int t_n, t_shift, t_lo, t_hi;
   uint32_t t_xor;        // 0x80808080 when y is unsigned
 };
 

@@ -13,9 +13,9 @@
 // writes the result back in place; the finished rows leave as 16-byte pieces, 1 KiB contiguous per
 // store instruction.
 //
-// Optionally the 1x1 layer that reads this layer's output (256 -> 64 channels: the layer that opens
-// the next bottleneck block) is computed from the finished block while it is still in LDS, with its
-// 64 x 256 weights held in LDS for the life of the workgroup: that layer's 256 bytes per pixel are
+// Optionally the 1x1 layer that reads this layer's output (256 -> 64 or 128 channels: the layer that
+// opens the next bottleneck block) is computed from the finished block while it is still in LDS, with
+// its weights held in LDS for the life of the workgroup: that layer's 256 bytes per pixel are
 // then never read back from HBM.
 #include "pw_ws.h"
 
@@ -23,6 +23,23 @@ namespace f8 {
 namespace {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) const v4i lds_v4i;
+typedef __attribute__((address_space(3))) const int32_t lds_i32;
+
+// The same LDS address, made opaque to the optimiser: reads through it stay where they are written
+// (accumulator start values and the second layer's weights never change, so they would otherwise be
+// hoisted out of the block loop and held in registers).
+__device__ __forceinline__ lds_i32 *here(const int32_t *shared_array) {
+  lds_i32 *q = (lds_i32 *)shared_array;
+  asm volatile("" : "+v"(q));
+  return q;
+}
+typedef __attribute__((address_space(3))) const uint8_t lds_u8;
+__device__ __forceinline__ lds_u8 *here(const uint8_t *shared_array) {
+  lds_u8 *q = (lds_u8 *)shared_array;
+  asm volatile("" : "+v"(q));
+  return q;
+}
 
 constexpr int PW_NT = 256;
 constexpr int PW_C = 64, PW_N = 256;
@@ -34,11 +51,15 @@ __device__ __forceinline__ int med3(int v, int lo, int hi) {
   return r;
 }
 
-constexpr int PW_TN = 64;                    // channels of the optional second layer
-constexpr int PW_TPITCH = PW_TN + 16;        // row pitch of its staged result
-
-template <bool HAS_RES, bool TAIL>
+// RK: residual kind (0 none, 1 unsigned, 2 signed); RLEFT: the residual is shifted left to the
+// accumulator's scale (else rounded right); TQ: 32-channel blocks of the optional second layer (0: none,
+// 2: 64 channels, 4: 128 channels).  All uniform, so the per-lane code carries no selects.
+template <int RK, bool RLEFT, int TQ>
 __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
+  constexpr bool TAIL = TQ > 0;
+  constexpr bool HAS_RES = RK != 0;
+  constexpr int PW_TN = TAIL ? 32 * TQ : 32;   // its channels
+  constexpr int PW_TPITCH = PW_TN + 16;        // row pitch of its staged result
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * PW_WAVE_LDS];
   __shared__ __attribute__((aligned(16))) int32_t start[PW_N];
   __shared__ __attribute__((aligned(16))) uint8_t w2[TAIL ? PW_TN * PW_N : 16];
@@ -75,27 +96,31 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
   // piece lane % 16 of row 4 j + lane / 16; in LDS it sits at piece ^ (row % 16).
   const int prow = lane >> 4, ppiece = lane & 15;
   const int zx = (int)p.x_xor;
+  // Rows past the end are not fetched: their lanes compute on stale registers and are never stored
+  // (pixels are independent columns of the matrix product).  One base address per block and role;
+  // the rest are constant offsets.
   auto load_x = [&](long long blk, v4i (&xb)[2]) {
-    long long m = blk * 32 + l32;
-    if (m >= p.M) m = p.M - 1;                   // rows past the end compute on the last pixel; never stored
+    const long long m = blk * 32 + l32;
     const uint8_t *src = p.x + m * PW_C + 16 * half;
-    xb[0] = *reinterpret_cast<const v4i *>(src);
-    xb[1] = *reinterpret_cast<const v4i *>(src + 32);
+    if (m < p.M) {
+      xb[0] = *reinterpret_cast<const v4i *>(src);
+      xb[1] = *reinterpret_cast<const v4i *>(src + 32);
+    }
   };
   auto load_res = [&](long long blk, v4i (&rb)[8]) {
+    const long long m = blk * 32 + prow;
+    const uint8_t *src = p.res + m * PW_N + 16 * ppiece;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      long long m = blk * 32 + 4 * j + prow;
-      if (m >= p.M) m = p.M - 1;
-      rb[j] = *reinterpret_cast<const v4i *>(p.res + m * PW_N + 16 * ppiece);
-    }
+    for (int j = 0; j < 8; ++j)
+      if (m + 4 * j < p.M) rb[j] = *reinterpret_cast<const v4i *>(src + j * (4 * PW_N));
   };
 
   v4i xn[2], rn[8];
   load_x(b, xn);
   if (HAS_RES) load_res(b, rn);
-  const int sh = p.shift, lo = p.lo, hi = p.hi, d = p.res_d;
-  const int rhalf = d < 0 ? (1 << (-d - 1)) : 0;
+  const int sh = p.shift, lo = p.lo, hi = p.hi;
+  const int d = RLEFT ? p.res_d : -p.res_d;            // shift distance, left or right
+  const int rhalf = RLEFT ? 0 : (1 << (d - 1));
 
   for (; b < nblk; b += stride) {
     v4i xb[2];
@@ -113,63 +138,92 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
       load_x(bn, xn);
       if (HAS_RES) load_res(bn, rn);
     }
-    // two halves of 128 channels, so that the accumulators take 64 registers
+    // four parts of 64 channels, so that the accumulators take 32 registers
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      v16i acc[4];
+    for (int h = 0; h < 4; ++h) {
+      lds_i32 *st = here(start);
+      v16i acc[2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          // acc[q][4 g + j] is channel 128 h + 32 q + 8 g + 4 half + j of pixel l32
-          const v4i s0 = *reinterpret_cast<const v4i *>(start + 128 * h + 32 * q + 8 * g + 4 * half);
+          // acc[q][4 g + j] is channel 64 h + 32 q + 8 g + 4 half + j of pixel l32
+          const v4i s0 = *reinterpret_cast<lds_v4i *>(st + 64 * h + 32 * q + 8 * g + 4 * half);
           acc[q][4 * g] = s0.x; acc[q][4 * g + 1] = s0.y; acc[q][4 * g + 2] = s0.z; acc[q][4 * g + 3] = s0.w;
         }
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[4 * h + q][ks], xb[ks], acc[q], 0, 0, 0);
+        for (int q = 0; q < 2; ++q)
+          acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[2 * h + q][ks], xb[ks], acc[q], 0, 0, 0);
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int ch = 128 * h + 32 * q + 8 * g + 4 * half;         // this lane's four channels
+          const int ch = 64 * h + 32 * q + 8 * g + 4 * half;         // this lane's four channels
           uint8_t *slot = tile + l32 * PW_N + 16 * ((ch >> 4) ^ (l32 & 15)) + (ch & 15);
           int v[4] = {acc[q][4 * g], acc[q][4 * g + 1], acc[q][4 * g + 2], acc[q][4 * g + 3]};
           if (HAS_RES) {
             const uint32_t rv = *reinterpret_cast<const uint32_t *>(slot);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const int r = p.res_signed ? (int)__builtin_amdgcn_sbfe((int)rv, 8 * j, 8) : (int)__builtin_amdgcn_ubfe(rv, 8 * j, 8);
-              v[j] += d >= 0 ? (r << d) : ((r + rhalf) >> (-d));
+              const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe((int)rv, 8 * j, 8) : (int)__builtin_amdgcn_ubfe(rv, 8 * j, 8);
+              v[j] += RLEFT ? (r << d) : ((r + rhalf) >> d);
             }
           }
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = med3(v[j] >> sh, lo, hi);
           *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
         }
-      __builtin_amdgcn_sched_barrier(0);       // keep the two halves apart: one set of accumulators at a time
+      __builtin_amdgcn_sched_barrier(0);       // keep the parts apart: one set of accumulators at a time
     }
-    v16i acc2[2];
+    uint32_t pk[TAIL ? TQ : 1][4];      // the second layer's results, four channels per dword
     if (TAIL) {
-      // the finished block is the second layer's activation operand: K = 256 = 8 slices
+      // the finished block is the second layer's activation operand: K = 256 = 8 slices; 64 of its
+      // channels at a time, requantised and packed at once, so that few registers stay occupied
       const int tx = (int)p.t_xor;
+      const int sh2 = p.t_shift, lo2 = p.t_lo, hi2 = p.t_hi;
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const v4i s0 = *reinterpret_cast<const v4i *>(start2 + 32 * q + 8 * g + 4 * half);
-          acc2[q][4 * g] = s0.x; acc2[q][4 * g + 1] = s0.y; acc2[q][4 * g + 2] = s0.z; acc2[q][4 * g + 3] = s0.w;
-        }
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const int off = l32 * PW_N + 16 * ((2 * ks + half) ^ (l32 & 15));
-        v4i yb = *reinterpret_cast<const v4i *>(tile + off);
-        yb = v4i{yb.x ^ tx, yb.y ^ tx, yb.z ^ tx, yb.w ^ tx};
+      for (int th = 0; th < TQ / 2; ++th) {
+        lds_i32 *st2 = here(start2);
+        lds_u8 *w2h = here(w2);
+        v16i acc2[2];
 #pragma unroll
         for (int q = 0; q < 2; ++q)
-          acc2[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const v4i *>(w2 + 32 * q * PW_N + off), yb, acc2[q], 0, 0, 0);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const v4i s0 = *reinterpret_cast<lds_v4i *>(st2 + 64 * th + 32 * q + 8 * g + 4 * half);
+            acc2[q][4 * g] = s0.x; acc2[q][4 * g + 1] = s0.y; acc2[q][4 * g + 2] = s0.z; acc2[q][4 * g + 3] = s0.w;
+          }
+        // fragment reads run two slices ahead of the matrix instructions
+        v4i yb[3], wa[3][2];
+        auto read_slice = [&](int ks) {
+          const int off = l32 * PW_N + 16 * ((2 * ks + half) ^ (l32 & 15));
+          yb[ks % 3] = *reinterpret_cast<const v4i *>(tile + off);
+#pragma unroll
+          for (int q = 0; q < 2; ++q) wa[ks % 3][q] = *reinterpret_cast<lds_v4i *>(w2h + (64 * th + 32 * q) * PW_N + off);
+        };
+        read_slice(0);
+        read_slice(1);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          if (ks + 2 < 8) read_slice(ks + 2);
+          const v4i y = yb[ks % 3];
+          const v4i ys = v4i{y.x ^ tx, y.y ^ tx, y.z ^ tx, y.w ^ tx};
+#pragma unroll
+          for (int q = 0; q < 2; ++q) acc2[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[ks % 3][q], ys, acc2[q], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            int v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = med3(acc2[q][4 * g + j] >> sh2, lo2, hi2);
+            pk[2 * th + q][g] = pack4(v[0], v[1], v[2], v[3]);
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     // 32 rows x 256 bytes are contiguous in the output
@@ -186,32 +240,39 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(rn[j]));
     }
+    {
+      const long long m = b * 32 + prow;
+      uint8_t *dst = p.y + m * PW_N + 16 * ppiece;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const long long m = b * 32 + 4 * j + prow;
-      if (m < p.M) *reinterpret_cast<v4i *>(p.y + m * PW_N + 16 * ppiece) = out[j];
+      for (int j = 0; j < 8; ++j)
+        if (m + 4 * j < p.M) *reinterpret_cast<v4i *>(dst + j * (4 * PW_N)) = out[j];
     }
     if (TAIL) {
-      // the second layer's 32 x 64 results go through the (now free) tile to leave as 16-byte pieces
-      const int sh2 = p.t_shift, lo2 = p.t_lo, hi2 = p.t_hi;
+      // the second layer's 32 x PW_TN results go through the (now free) tile to leave as 16-byte pieces
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+      for (int q = 0; q < TQ; ++q)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          int v[4];
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<uint32_t *>(tile + l32 * PW_TPITCH + 32 * q + 8 * g + 4 * half) = pk[q][g];
+      // piece i = lane + 64 k of the 32 x PW_TN block: rows advance by 64 / (PW_TN / 16) per k
+      constexpr int PPR = PW_TN / 16, RSTEP = 64 / PPR;
+      const int row0 = lane / PPR, pc = lane % PPR;
+      const long long m = b * 32 + row0;
+      uint8_t *dst = p.t_y + m * PW_TN + 16 * pc;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = med3(acc2[q][4 * g + j] >> sh2, lo2, hi2);
-          *reinterpret_cast<uint32_t *>(tile + l32 * PW_TPITCH + 32 * q + 8 * g + 4 * half) = pack4(v[0], v[1], v[2], v[3]);
-        }
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const int i = lane + 64 * k, row = i >> 2, pc = i & 3;
-        const long long m = b * 32 + row;
-        const v4i v = *reinterpret_cast<const v4i *>(tile + row * PW_TPITCH + 16 * pc);
-        if (m < p.M) *reinterpret_cast<v4i *>(p.t_y + m * PW_TN + 16 * pc) = v;
+      for (int k = 0; k < TQ; ++k) {
+        const v4i v = *reinterpret_cast<const v4i *>(tile + (row0 + k * RSTEP) * PW_TPITCH + 16 * pc);
+        if (m + k * RSTEP < p.M) *reinterpret_cast<v4i *>(dst + k * (RSTEP * PW_TN)) = v;
       }
     }
   }
+}
+
+template <int RK, bool RLEFT>
+void launch_kind(const PwWsParams &p, int tq, int grid, hipStream_t stream) {
+  if (tq == 0) hipLaunchKernelGGL((pw_ws_kernel<RK, RLEFT, 0>), dim3(grid), dim3(PW_NT), 0, stream, p);
+  else if (tq == 2) hipLaunchKernelGGL((pw_ws_kernel<RK, RLEFT, 2>), dim3(grid), dim3(PW_NT), 0, stream, p);
+  else hipLaunchKernelGGL((pw_ws_kernel<RK, RLEFT, 4>), dim3(grid), dim3(PW_NT), 0, stream, p);
 }
 
 }  // namespace
@@ -233,16 +294,15 @@ int launch_pw_ws(const PwWsParams &p, hipStream_t stream) {
     return (int)hipErrorInvalidValue;
   const long long nblk = (p.M + 31) / 32, wgs = (nblk + 3) / 4;
   const int grid = (int)(wgs < 512 ? wgs : 512);            // two workgroups per CU walk over the blocks
-  if (p.t_w) {
-    if (p.t_shift < 0 || p.t_lo > p.t_hi ||
-        ((reinterpret_cast<uintptr_t>(p.t_w) | reinterpret_cast<uintptr_t>(p.t_y) | reinterpret_cast<uintptr_t>(p.t_acc0)) & 15))
-      return (int)hipErrorInvalidValue;
-    if (p.res) hipLaunchKernelGGL((pw_ws_kernel<true, true>), dim3(grid), dim3(PW_NT), 0, stream, p);
-    else hipLaunchKernelGGL((pw_ws_kernel<false, true>), dim3(grid), dim3(PW_NT), 0, stream, p);
-  } else {
-    if (p.res) hipLaunchKernelGGL((pw_ws_kernel<true, false>), dim3(grid), dim3(PW_NT), 0, stream, p);
-    else hipLaunchKernelGGL((pw_ws_kernel<false, false>), dim3(grid), dim3(PW_NT), 0, stream, p);
-  }
+  if (p.t_w && ((p.t_n != 64 && p.t_n != 128) || p.t_shift < 0 || p.t_lo > p.t_hi ||
+                ((reinterpret_cast<uintptr_t>(p.t_w) | reinterpret_cast<uintptr_t>(p.t_y) | reinterpret_cast<uintptr_t>(p.t_acc0)) & 15)))
+    return (int)hipErrorInvalidValue;
+  const int tq = !p.t_w ? 0 : p.t_n / 32;
+  const int rk = !p.res ? 0 : (p.res_signed ? 2 : 1);
+  const bool left = p.res_d >= 0;
+  if (rk == 0) launch_kind<0, true>(p, tq, grid, stream);
+  else if (rk == 1) { if (left) launch_kind<1, true>(p, tq, grid, stream); else launch_kind<1, false>(p, tq, grid, stream); }
+  else { if (left) launch_kind<2, true>(p, tq, grid, stream); else launch_kind<2, false>(p, tq, grid, stream); }
   return (int)hipGetLastError();
 }
 

@@ -235,10 +235,10 @@ def test_weights_stationary_1x1_64_to_256(oracle):
             assert_same(gpu_layer(L, x, res), np.concatenate(outs), "pw ws %s" % str((B, H, W, xt, yt, rt, shift, L.fl_res)))
     _, net = wl.config4(batch=1)
     chain = f8.Chain(net)
-    # the shortcut projection and the last block's closing layer; the other two closing layers also
-    # compute the layer that opens the next block
+    # the shortcut projection; the three closing layers also compute the layer that opens the next block
     names = [chain.layer_info(i, 256)[0] for i in range(len(net.layers))]
-    assert names.count("pw1x1_ws<64x256>") == 2 and names.count("pw1x1_ws<64x256>+1x1<64>") == 2
+    assert names.count("pw1x1_ws<64x256>") == 1 and names.count("pw1x1_ws<64x256>+1x1<64>") == 2
+    assert names.count("pw1x1_ws<64x256>+1x1<128>") == 1
     assert not any(chain.layer_info(i, 4)[0].startswith("pw1x1_ws") for i in range(len(net.layers)))
 
 
@@ -248,23 +248,30 @@ def test_1x1_layer_computed_behind_the_64_to_256_layer(oracle):
     block of the first one's output while it is on chip; both tensors are still written.  Every
     tensor against the oracle; the one-launch path against the two-launch path; small batches keep
     two launches."""
-    cases = ((32, 128, 48, True, True, True),      # unsigned in between, residual
-             (23, 250, 16, False, True, False),    # signed tensor in between, no residual, ragged last block
-             (19, 370, 32, True, False, True),     # signed output behind
-             (37, 97, 16, False, False, True))     # signed everywhere, ragged
-    for k, (hw, batch, cin, relu1, relu2, with_res) in enumerate(cases):
+    cases = ((32, 128, 48, True, True, True, 64, False),     # unsigned in between, residual
+             (23, 250, 16, False, True, False, 64, False),   # signed tensor in between, no residual, ragged last block
+             (19, 370, 32, True, False, True, 128, False),   # 128 channels behind, signed output
+             (37, 97, 16, False, False, True, 64, True),     # signed everywhere, ragged, another layer between the two
+             (21, 300, 16, True, True, True, 128, True),     # the hand-over into a new stage: 128 channels, shortcut between
+             (25, 210, 32, True, True, False, 128, False))   # 128 channels, no residual
+    for k, (hw, batch, cin, relu1, relu2, with_res, cout2, between) in enumerate(cases):
         rng = np.random.default_rng(900 + k)
         b = wl._NetBuilder("tail%d" % k, rng, hw, cin, "u8", 6, (5, 9), (2, 6), True)
         r = b.conv("short", 0, 256, 1, 1, 0, relu=(k % 2 == 0))
         m = b.conv("mid", 0, 64, 1, 1, 0)
         h = b.conv("front", m, 256, 1, 1, 0, relu=relu1, res=r if with_res else -1)
-        t = b.conv("behind", h, 64, 1, 1, 0, relu=relu2)
-        e = b.conv("other_reader", h, 64, 1, 1, 0, relu=False)
-        b.conv("join", t, 64, 1, 1, 0, res=e)
+        cj = 32 if between else cout2
+        if between:      # (32 channels: this reader cannot itself be the layer computed behind the front one)
+            e = b.conv("other_reader", h, cj, 1, 1, 0, relu=False)
+            t = b.conv("behind", h, cout2, 1, 1, 0, relu=relu2)
+        else:
+            t = b.conv("behind", h, cout2, 1, 1, 0, relu=relu2)
+            e = b.conv("other_reader", h, cj, 1, 1, 0, relu=False)
+        b.conv("join", t, cj, 1, 1, 0, res=e)
         net = b.net
         x = wl.draw_u8(rng, (batch, hw, hw, cin))
         names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(len(net.layers))]
-        assert names[2] == "pw1x1_ws<64x256>+1x1<64>" and names[3] == "(fused)", names
+        assert names[2] == "pw1x1_ws<64x256>+1x1<%d>" % cout2 and names[4 if between else 3] == "(fused)", names
         assert "(fused)" not in [f8.Chain(net).layer_info(i, 8)[0] for i in range(len(net.layers))]
         imgs = sorted(set([0, 1, batch // 2, batch - 2, batch - 1]))
         out = check_network(oracle, x, net, imgs, "1x1 behind 64->256, case %d" % k, lean_is_smaller=False)
