@@ -25,15 +25,18 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak, GB/s
 # are in profiles/resnet50_b256_hbm_traffic.md.  Counters cannot be read from inside this
 # process, so the figure of the dominant kernel is reported from here.
 MEASURED_TRAFFIC_MB = {
-    "conv_fast<128x128,k64,s2>": 174.97,
-    "conv_fast<128x128,k64,s3>": 205.96,
-    "conv_fast<128x64,k64,s2>": 205.78,
+    "conv_fast<128x128,k64,s2>": 162.81,
+    "conv_fast<128x128,k64,s3>": 103.24,
+    "conv_fast<128x64,k64,s2>": 102.93,
     "conv3x3_ws<64x64>": 184.83,
-    "conv3x3_ws<128x128>": 97.42,
+    "conv3x3_ws<128x128>": 97.41,
+    "pw1x1_ws<64x256>": 257.13,
+    "pw1x1_ws<64x256>+1x1<64>": 514.24,
+    "pw1x1_ws<64x256>+1x1<128>": 668.68,
     "stem_pool_fused": 272.19,        # re-layout pass 94.70 + fused stem and pool 177.49
-    "conv_fast<128x128,k128,s2>": 141.18,
+    "conv_fast<128x128,k128,s2>": 141.85,
     "conv_fast<256x256,k128,s2,w4x2>": 57.18,
-    "conv_fast<256x128,k128,s2,w4x2>": 41.72,
+    "conv_fast<256x128,k128,s2,w4x2>": 41.71,
 }
 
 
