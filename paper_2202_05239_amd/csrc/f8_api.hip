@@ -186,7 +186,7 @@ bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
 }
 
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
-  if (use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
+  if (!(has_res && q.res_type == F8_S32) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins
