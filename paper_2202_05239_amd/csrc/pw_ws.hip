@@ -64,14 +64,27 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
   __shared__ __attribute__((aligned(16))) int32_t start[PW_N];
   __shared__ __attribute__((aligned(16))) uint8_t w2[TAIL ? PW_TN * PW_N : 16];
   __shared__ __attribute__((aligned(16))) int32_t start2[PW_TN];
+  // With the 128-channel second layer the registers do not hold all of this layer's weights: those of
+  // channels 128 .. 255 then live in LDS (rows of 64 bytes, pieces permuted by bits 2-3 of the row).
+  constexpr bool W1_LDS = TQ == 4;
+  constexpr int NB_REG = W1_LDS ? 4 : 8;       // 32-channel blocks of weights held in registers
+  __shared__ __attribute__((aligned(16))) uint8_t w1[W1_LDS ? 128 * PW_C : 16];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   uint8_t *tile = tiles + wave * PW_WAVE_LDS;
 
   // weights: fa[nb][ks] = channel 32 nb + l32, bytes 32 ks + 16 half .. + 16 of its 64
-  v4i fa[8][2];
+  v4i fa[NB_REG][2];
+  if (W1_LDS) {
 #pragma unroll
-  for (int nb = 0; nb < 8; ++nb)
+    for (int k = 0; k < 128 * PW_C / 16 / PW_NT; ++k) {
+      const int i = tid + k * PW_NT, n = i >> 2, pc = i & 3;
+      *reinterpret_cast<v4i *>(w1 + n * PW_C + 16 * (pc ^ ((n >> 2) & 3))) =
+          *reinterpret_cast<const v4i *>(p.w + (size_t)128 * PW_C + (size_t)i * 16);
+    }
+  }
+#pragma unroll
+  for (int nb = 0; nb < NB_REG; ++nb)
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
       fa[nb][ks] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * nb + l32) * PW_C + 32 * ks + 16 * half);
@@ -154,8 +167,16 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-          acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[2 * h + q][ks], xb[ks], acc[q], 0, 0, 0);
+        for (int q = 0; q < 2; ++q) {
+          v4i wf;
+          if (2 * h + q < NB_REG) {
+            wf = fa[(2 * h + q) % NB_REG][ks];
+          } else {
+            const int n = 32 * (2 * h + q - NB_REG) + l32;
+            wf = *reinterpret_cast<lds_v4i *>(here(w1) + n * PW_C + 16 * ((2 * ks + half) ^ ((n >> 2) & 3)));
+          }
+          acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xb[ks], acc[q], 0, 0, 0);
+        }
 #pragma unroll
       for (int q = 0; q < 2; ++q)
 #pragma unroll
