@@ -76,6 +76,11 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   // This thread's pieces of a patch: piece c = tid + 256 k is 16 bytes of patch row c / (W C / 16); it lies
   // 16 c bytes behind the start of the patch's first row in the image.  Where it goes in LDS never changes:
   // kept with the row number in one register (offset in the low 20 bits).
+  // (With 128 channels the registers are full: the table then lives in LDS, read back through an
+  // address the optimiser cannot see through, or it would hoist the reads out of the tile loop and
+  // spill them.)
+  constexpr bool WHERE_LDS = C == 128;
+  __shared__ int where_lds[WHERE_LDS ? MAXCH * WS_NT : 1];
   int where[MAXCH];
 #pragma unroll
   for (int k = 0; k < MAXCH; ++k) {
@@ -84,7 +89,14 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
     const int col = piece / S::PIECES, part = piece % S::PIECES;
     const int dst = C + row * p.pitch + col * C + 16 * (part ^ ((col >> S::KEY_SHIFT) & (S::PIECES - 1)));
     where[k] = dst | ((c < p.nchunks ? row : 1024) << 20);      // past the end: never inside the image
+    if (WHERE_LDS) where_lds[k * WS_NT + tid] = where[k];       // read by this thread only: no barrier needed
   }
+  auto where_of = [&](int k) {
+    if (!WHERE_LDS) return where[k];
+    __attribute__((address_space(3))) const int *q = (__attribute__((address_space(3))) const int *)where_lds;
+    asm volatile("" : "+v"(q));
+    return q[k * WS_NT + tid];
+  };
   auto tile_coords = [&](int tt, int &b, int &m0, int &row0) {
     const uint32_t bi = p.fd_tpi.div((uint32_t)tt);
     b = (int)bi;
@@ -98,14 +110,16 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
 #pragma unroll
     for (int k = 0; k < MAXCH; ++k) {
       buf[k] = v4i{0, 0, 0, 0};
-      if ((unsigned)(row0 + (where[k] >> 20)) < (unsigned)p.H) buf[k] = *reinterpret_cast<const v4i *>(src + 16 * (tid + k * WS_NT));
+      if ((unsigned)(row0 + (where_of(k) >> 20)) < (unsigned)p.H) buf[k] = *reinterpret_cast<const v4i *>(src + 16 * (tid + k * WS_NT));
     }
   };
   auto store_patch = [&](int which, const v4i (&buf)[MAXCH]) {
 #pragma unroll
-    for (int k = 0; k < MAXCH; ++k)
-      if ((where[k] >> 20) < 1024)
-        *reinterpret_cast<v4i *>(lds + which * patch_bytes + (where[k] & 0xfffff)) = v4i{buf[k].x ^ zx, buf[k].y ^ zx, buf[k].z ^ zx, buf[k].w ^ zx};
+    for (int k = 0; k < MAXCH; ++k) {
+      const int wk = where_of(k);
+      if ((wk >> 20) < 1024)
+        *reinterpret_cast<v4i *>(lds + which * patch_bytes + (wk & 0xfffff)) = v4i{buf[k].x ^ zx, buf[k].y ^ zx, buf[k].z ^ zx, buf[k].w ^ zx};
+    }
   };
 
   v4i nextbuf[MAXCH];
