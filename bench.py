@@ -29,10 +29,10 @@ MEASURED_TRAFFIC_MB = {
     "conv_fast<128x128,k64,s3>": 103.24,
     "conv_fast<128x64,k64,s2>": 102.93,
     "conv3x3_ws<64x64>": 184.83,
-    "conv3x3_ws<128x128>": 97.41,
+    "conv3x3_ws<128x128>": 92.17,
     "pw1x1_ws<64x256>": 257.13,
     "pw1x1_ws<64x256>+1x1<64>": 514.24,
-    "pw1x1_ws<64x256>+1x1<128>": 668.68,
+    "pw1x1_ws<64x256>+1x1<128>": 565.78,
     "stem_pool_fused": 272.19,        # re-layout pass 94.70 + fused stem and pool 177.49
     "conv_fast<128x128,k128,s2>": 141.85,
     "conv_fast<256x256,k128,s2,w4x2>": 57.18,
