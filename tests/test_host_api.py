@@ -157,6 +157,48 @@ def test_chain_planner_host_side():
     assert L.f8_chain_create(make_descs(net), len(net.layers), 64, 64, 3, f8.F8_U8, ctypes.byref(h)) == 2
 
 
+def test_chain_pairs_a_1x1_layer_with_the_layer_in_front_host_side():
+    """The 1x1 64 -> 256 layers of the first ResNet stage also compute the 1x1 layer that reads their
+    output (the next block's first layer; at the stage boundary it sits behind the shortcut projection):
+    which layers are paired, at which batch, and that the planner never lets the extra output share
+    memory with anything the launch reads or with the launch's own output (no GPU needed: names and
+    addresses only)."""
+    L = f8.lib()
+    _, net = wl.config4(batch=1)
+    h = ctypes.c_void_p()
+    assert L.f8_chain_create(make_descs(net), len(net.layers), 224, 224, 3, f8.F8_S8, ctypes.byref(h)) == 0
+
+    def name(i, batch):
+        buf = ctypes.create_string_buffer(64)
+        assert L.f8_chain_layer_info(h, i, batch, buf, 64, None, None) == 0
+        return buf.value.decode()
+
+    names = [name(i, 256) for i in range(len(net.layers))]
+    by_name = {S.name: i for i, S in enumerate(net.layers)}
+    pairs = {"s1b1.conv_c": "s1b2.conv_a", "s1b2.conv_c": "s1b3.conv_a", "s1b3.conv_c": "s2b1.conv_a"}
+    for front, behind in pairs.items():
+        width = net.layers[by_name[behind]].Cout
+        assert names[by_name[front]] == "pw1x1_ws<64x256>+1x1<%d>" % width
+        assert names[by_name[behind]] == "(fused)"
+    assert names[by_name["s2b1.ds"]] != "(fused)"                  # the layer between the last pair runs on its own
+    assert names.count("(fused)") == len(pairs) + 1                # + the max pool inside the stem kernel
+    assert not any("+1x1" in name(i, 8) for i in range(len(net.layers)))       # small batches: two launches
+
+    base, batch = 1 << 32, 256
+    def span(tid):
+        p, dims = ctypes.c_void_p(), [ctypes.c_int() for _ in range(5)]
+        assert L.f8_chain_tensor(h, tid, ctypes.c_void_p(base), batch, ctypes.byref(p), *[ctypes.byref(d) for d in dims]) == 0
+        hh, ww, cc = (d.value for d in dims[:3])
+        return p.value, p.value + batch * hh * ww * cc
+    for front, behind in pairs.items():
+        F, T = net.layers[by_name[front]], net.layers[by_name[behind]]
+        spans = [span(t) for t in (F.src, F.res, F.dst, T.dst)]
+        for a in range(4):
+            for b in range(a + 1, 4):
+                assert spans[a][1] <= spans[b][0] or spans[b][1] <= spans[a][0], (front, a, b)
+    L.f8_chain_destroy(h)
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch):
     monkeypatch.setattr(f8, "_lib", None)
     monkeypatch.setattr(f8, "LIB_PATH", "/nonexistent/libf8.so")
