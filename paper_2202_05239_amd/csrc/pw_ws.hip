@@ -128,7 +128,10 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
       if (m + 4 * j < p.M) rb[j] = *reinterpret_cast<const v4i *>(src + j * (4 * PW_N));
   };
 
-  v4i xn[2], rn[8];
+  // (defined values everywhere: lanes whose rows lie past the end never load)
+  v4i xn[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}}, rn[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) rn[j] = v4i{0, 0, 0, 0};
   load_x(b, xn);
   if (HAS_RES) load_res(b, rn);
   const int sh = p.shift, lo = p.lo, hi = p.hi;
