@@ -91,9 +91,30 @@ static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void 
   return pw_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
 }
 
+// And the 1x1 layers with 16 or 32 input and 96 / 144 / 192 output channels (MobileNetV2's first expand layers).
+static bool use_pw_small(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
+                         const f8_quant &q, const void *y2) {
+  static const int on = [] { const char *e = getenv("F8_PW_SMALL"); return e ? atoi(e) : 1; }();   // tuning aid
+  if (!on || res || y2 || q.y_type == F8_S32) return false;
+  if ((long long)g.B * g.H * g.W < 131072) return false;
+  return pw_small_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y);
+}
+
 f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, const void *zero, void *y,
                        const void *res, const Geom &g, const f8_quant &q, hipStream_t stream,
                        const f8_requant2 *q2, void *y2, const ConvTail *tail) {
+  if (!tail && use_pw_small(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0) {
+    PwSmallParams sp;
+    sp.x = static_cast<const uint8_t *>(x);
+    sp.w = w;
+    sp.acc0 = acc0;
+    sp.y = static_cast<uint8_t *>(y);
+    sp.M = (long long)g.B * g.H * g.W;
+    sp.C = g.Cin; sp.N = g.Cout;
+    sp.shift = q.fl_x + q.fl_w - q.fl_y; sp.lo = q.clip_lo; sp.hi = q.clip_hi;
+    sp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
+    return launch_pw_small(sp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+  }
   const bool pw_ws = use_pw_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0;
   if (tail && !(pw_ws && (tail->Cout == 64 || tail->Cout == 128) && tail->q.y_type != F8_S32)) return F8_ERR_UNSUPPORTED;
   if (pw_ws) {
@@ -186,6 +207,11 @@ bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
 }
 
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
+  if (use_pw_small(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) {
+    static const char *const names[2][3] = {{"pw1x1_small<16x96>", "pw1x1_small<16x144>", "pw1x1_small<16x192>"},
+                                            {"pw1x1_small<32x96>", "pw1x1_small<32x144>", "pw1x1_small<32x192>"}};
+    return names[g.Cin == 32][g.Cout == 96 ? 0 : (g.Cout == 144 ? 1 : 2)];
+  }
   if (!(has_res && q.res_type == F8_S32) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";
   ConvParams p;

@@ -9,6 +9,7 @@
 #include "conv_igemm.h"
 #include "conv_ws.h"
 #include "pw_ws.h"
+#include "pw_small.h"
 #include "dwconv_pool.h"
 
 namespace f8 {
