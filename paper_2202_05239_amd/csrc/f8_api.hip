@@ -202,15 +202,20 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   return launch_conv_igemm(p, vec, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
 }
 
+bool conv_reads_narrow_rows(const Geom &g, const f8_quant &q, bool has_res) {
+  return use_pw_small(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr);
+}
+
 bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
   return (Cout2 == 64 || Cout2 == 128) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr);
 }
 
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   if (use_pw_small(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) {
-    static const char *const names[2][3] = {{"pw1x1_small<16x96>", "pw1x1_small<16x144>", "pw1x1_small<16x192>"},
+    static const char *const names[3][3] = {{"pw1x1_small<16x96>", "pw1x1_small<16x144>", "pw1x1_small<16x192>"},
+                                            {"pw1x1_small<24x96>", "pw1x1_small<24x144>", "pw1x1_small<24x192>"},
                                             {"pw1x1_small<32x96>", "pw1x1_small<32x144>", "pw1x1_small<32x192>"}};
-    return names[g.Cin == 32][g.Cout == 96 ? 0 : (g.Cout == 144 ? 1 : 2)];
+    return names[g.Cin == 16 ? 0 : (g.Cin == 24 ? 1 : 2)][g.Cout == 96 ? 0 : (g.Cout == 144 ? 1 : 2)];
   }
   if (!(has_res && q.res_type == F8_S32) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";

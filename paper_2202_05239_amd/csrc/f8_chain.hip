@@ -225,6 +225,18 @@ struct f8_chain {
     return reinterpret_cast<const int8_t *>(static_cast<uint8_t *>(workspace) + stem[i].w_off);
   }
 
+  // A dense layer whose channel count is not a multiple of 16 normally runs on a zero-padded copy;
+  // not when the kernel for few input channels takes it at this batch (its weights 16-byte aligned,
+  // its tensors in the arena).
+  bool narrow_rows(size_t i, int batch) const {
+    const f8_layer_desc &L = layers[i];
+    if (!stem[i].on || stem[i].Cp == 4 || L.op != F8_OP_CONV || L.dst2 > 0 || (reinterpret_cast<uintptr_t>(L.w) & 15)) return false;
+    if (tensors[L.src].external || tensors[L.dst].external) return false;
+    Geom g = geom[i];
+    g.B = batch;
+    return conv_reads_narrow_rows(g, L.q, L.res >= 0);
+  }
+
   // Parameters of the fused block that starts at layer i.
   BlockParams block_params(size_t i, const void *x, void *out, void *workspace, int batch) const {
     const f8_layer_desc &L0 = layers[i], &L1 = layers[i + 1], &L2 = layers[i + 2];
@@ -289,6 +301,10 @@ struct f8_chain {
     switch (L.op) {
       case F8_OP_CONV: {
         const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
+        if (narrow_rows(i, batch)) {
+          // the kernel for few input channels reads the 24-channel rows and weights as they are
+          return enqueue_conv(src, L.w, acc0, workspace, dst, res, g, L.q, s);
+        }
         if (stem[i].on) {
           void *xp = arena(workspace) + stem[i].x_off_per_image * (size_t)batch;
           const int e = stem[i].Cp == 4
@@ -724,7 +740,8 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
   if (L.dst2 > 0) bytes += M * g.Cout;
   switch (L.op) {
     case F8_OP_CONV: {
-      Geom gk = c->conv_geom(layer, batch);
+      Geom gk = c->narrow_rows((size_t)layer, batch) ? g : c->conv_geom(layer, batch);
+      gk.B = batch;
       gk.P = g.P; gk.Q = g.Q;
       name = conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;

@@ -60,6 +60,9 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
 bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2);
 // Checks of a second output format against the first (8-bit types, clip range, shift limits).
 f8_status check_requant2(const f8_quant &q, const f8_requant2 *q2);
+// Whether enqueue_conv takes this layer, as it is (operands 16-byte aligned), with the kernel for few
+// input channels, which also reads rows of 24 channels: the chain then skips its zero-padded copy.
+bool conv_reads_narrow_rows(const Geom &g, const f8_quant &q, bool has_res);
 // Name of the kernel enqueue_conv launches for this layer (operands assumed 16-byte aligned).
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res);
 // Enqueue the fold of (w, bias, rounding addend, sign correction) into acc0.

@@ -1,4 +1,4 @@
-// Weights-stationary 1x1 convolution for few input channels (16 or 32) and 96, 144 or 192 output
+// Weights-stationary 1x1 convolution for few input channels (16, 24 or 32) and 96, 144 or 192 output
 // channels, no residual: the expand layers of the first MobileNetV2 blocks.  See pw_small.hip.
 #pragma once
 

@@ -1,10 +1,11 @@
-// Weights-stationary 1x1 convolution with 16 or 32 input channels and 96, 144 or 192 output channels
+// Weights-stationary 1x1 convolution with 16, 24 or 32 input channels and 96, 144 or 192 output channels
 // (F8Net Eq. 2 / Eq. 9 epilogue), the shape of MobileNetV2's first expand layers.
 //
 // These layers write six times what they read and have one K slice of matrix work per output
 // block: the general tiled kernel spends its time on set-up.  Here, as in pw_ws.hip, every wave keeps
-// the whole weight matrix in registers (N / 32 fragments; one K slice of 32 bytes, the upper half
-// zero when there are 16 channels) and streams blocks of 32 pixels on its own: fragments straight
+// the whole weight matrix in registers (N / 32 fragments; one K slice of 32 bytes, its tail zero when
+// there are 16 or 24 channels; rows of 24 bytes are read in 8-byte pieces) and streams blocks of 32
+// pixels on its own: fragments straight
 // from global memory one block ahead, results requantised into the wave's own LDS tile (32 rows of
 // N bytes, which are contiguous in the output) and written out as 16-byte pieces.
 #include "pw_small.h"
@@ -32,9 +33,24 @@ __device__ __forceinline__ lds_i32 *here(const int32_t *shared_array) {
   return q;
 }
 
+// Bytes 16 half .. 16 half + 15 of a row of C bytes (zeros past C); rows of 24 bytes are only 8-byte aligned.
+template <int C>
+__device__ __forceinline__ void load_half_row(const uint8_t *row, int half, v4i &v) {
+  if (C == 24) {
+    const v2i a = *reinterpret_cast<const v2i *>(row + 16 * half);
+    v.x = a.x; v.y = a.y;
+    if (half == 0) {
+      const v2i b2 = *reinterpret_cast<const v2i *>(row + 8);
+      v.z = b2.x; v.w = b2.y;
+    }
+  } else if (16 * half < C) {
+    v = *reinterpret_cast<const v4i *>(row + 16 * half);
+  }
+}
+
 template <int C, int N>
 __global__ __launch_bounds__(PS_NT, 4) void pw_small_kernel(const PwSmallParams p) {
-  static_assert(C == 16 || C == 32, "one K slice");
+  static_assert(C == 16 || C == 24 || C == 32, "one K slice");
   static_assert(N % 16 == 0 && N <= 192, "rows of whole 16-byte pieces");
   constexpr int NB = (N + 31) / 32;             // 32-channel blocks (the last may be half empty)
   constexpr int PIECES = 2 * N;                 // 16-byte pieces of a block of 32 rows
@@ -51,7 +67,7 @@ __global__ __launch_bounds__(PS_NT, 4) void pw_small_kernel(const PwSmallParams 
   for (int nb = 0; nb < NB; ++nb) {
     fa[nb] = v4i{0, 0, 0, 0};
     const int n = 32 * nb + l32;
-    if (n < N && 16 * half < C) fa[nb] = *reinterpret_cast<const v4i *>(p.w + (size_t)n * C + 16 * half);
+    if (n < N) load_half_row<C>(reinterpret_cast<const uint8_t *>(p.w) + (size_t)n * C, half, fa[nb]);
   }
   if (tid < 32 * NB) start[tid] = tid < N ? p.acc0[tid] : 0;
   __syncthreads();                     // the only barrier: from here on every wave works alone
@@ -62,12 +78,11 @@ __global__ __launch_bounds__(PS_NT, 4) void pw_small_kernel(const PwSmallParams 
   if (b >= nblk) return;
 
   const int zx = (int)p.x_xor;
-  // the upper half of the K slice does not exist with 16 channels: those lanes keep zeros, which meet
-  // zero weights
+  // K positions past C do not exist: those bytes keep zeros, which meet zero weights
   v4i xn = v4i{0, 0, 0, 0};
   auto load_x = [&](long long blk) {
     const long long m = blk * 32 + l32;
-    if (m < p.M && 16 * half < C) xn = *reinterpret_cast<const v4i *>(p.x + m * C + 16 * half);
+    if (m < p.M) load_half_row<C>(p.x + m * C, half, xn);
   };
   load_x(b);
   const int sh = p.shift, lo = p.lo, hi = p.hi;
@@ -116,7 +131,7 @@ void launch_one(const PwSmallParams &p, int grid, hipStream_t stream) {
 
 bool pw_small_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int shift,
                          const void *x, const void *w, const void *y) {
-  if ((Cin != 16 && Cin != 32) || (Cout != 96 && Cout != 144 && Cout != 192)) return false;
+  if ((Cin != 16 && Cin != 24 && Cin != 32) || (Cout != 96 && Cout != 144 && Cout != 192)) return false;
   if (R != 1 || S != 1 || sh != 1 || sw != 1 || ph != 0 || pw != 0 || shift < 0) return false;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
   return (bits & 15) == 0;
@@ -129,7 +144,11 @@ int launch_pw_small(const PwSmallParams &p, hipStream_t stream) {
     return (int)hipErrorInvalidValue;
   const long long nblk = (p.M + 31) / 32, wgs = (nblk + 3) / 4;
   const int grid = (int)(wgs < 1024 ? wgs : 1024);          // four workgroups per CU walk over the blocks
-  if (p.C == 16) {
+  if (p.C == 24) {
+    if (p.N == 96) launch_one<24, 96>(p, grid, stream);
+    else if (p.N == 144) launch_one<24, 144>(p, grid, stream);
+    else launch_one<24, 192>(p, grid, stream);
+  } else if (p.C == 16) {
     if (p.N == 96) launch_one<16, 96>(p, grid, stream);
     else if (p.N == 144) launch_one<16, 144>(p, grid, stream);
     else launch_one<16, 192>(p, grid, stream);
