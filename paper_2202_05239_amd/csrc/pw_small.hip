@@ -1,5 +1,6 @@
 // Weights-stationary 1x1 convolution with 16, 24 or 32 input channels and 96, 144 or 192 output channels
-// (F8Net Eq. 2 / Eq. 9 epilogue), the shape of MobileNetV2's first expand layers.
+// (F8Net Eq. 2 / Eq. 9 epilogue), the shape of MobileNetV2's first expand layers; also 32 -> 16 channels,
+// its first projection.
 //
 // These layers write six times what they read and have one K slice of matrix work per output
 // block: the general tiled kernel spends its time on set-up.  Here, as in pw_ws.hip, every wave keeps
@@ -48,8 +49,11 @@ __device__ __forceinline__ void load_half_row(const uint8_t *row, int half, v4i 
   }
 }
 
+// Workgroups per CU: narrow outputs need few registers, and many waves to keep enough bytes in flight.
+template <int N> constexpr int ps_wgs() { return N <= 16 ? 8 : 4; }
+
 template <int C, int N>
-__global__ __launch_bounds__(PS_NT, 4) void pw_small_kernel(const PwSmallParams p) {
+__global__ __launch_bounds__(PS_NT, ps_wgs<N>()) void pw_small_kernel(const PwSmallParams p) {
   static_assert(C == 16 || C == 24 || C == 32, "one K slice");
   static_assert(N % 16 == 0 && N <= 192, "rows of whole 16-byte pieces");
   constexpr int NB = (N + 31) / 32;             // 32-channel blocks (the last may be half empty)
@@ -123,15 +127,18 @@ __global__ __launch_bounds__(PS_NT, 4) void pw_small_kernel(const PwSmallParams 
 }
 
 template <int C, int N>
-void launch_one(const PwSmallParams &p, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((pw_small_kernel<C, N>), dim3(grid), dim3(PS_NT), 0, stream, p);
+void launch_one(const PwSmallParams &p, long long wgs, hipStream_t stream) {
+  const long long most = 256LL * ps_wgs<N>();                 // the workgroups walk over the blocks
+  hipLaunchKernelGGL((pw_small_kernel<C, N>), dim3((unsigned)(wgs < most ? wgs : most)), dim3(PS_NT), 0, stream, p);
 }
 
 }  // namespace
 
 bool pw_small_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int shift,
                          const void *x, const void *w, const void *y) {
-  if ((Cin != 16 && Cin != 24 && Cin != 32) || (Cout != 96 && Cout != 144 && Cout != 192)) return false;
+  const bool expand = (Cin == 16 || Cin == 24 || Cin == 32) && (Cout == 96 || Cout == 144 || Cout == 192);
+  const bool project = Cin == 32 && Cout == 16;
+  if (!expand && !project) return false;
   if (R != 1 || S != 1 || sh != 1 || sw != 1 || ph != 0 || pw != 0 || shift < 0) return false;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
   return (bits & 15) == 0;
@@ -143,7 +150,7 @@ int launch_pw_small(const PwSmallParams &p, hipStream_t stream) {
       (reinterpret_cast<uintptr_t>(p.acc0) & 15))
     return (int)hipErrorInvalidValue;
   const long long nblk = (p.M + 31) / 32, wgs = (nblk + 3) / 4;
-  const int grid = (int)(wgs < 1024 ? wgs : 1024);          // four workgroups per CU walk over the blocks
+  const long long grid = wgs;
   if (p.C == 24) {
     if (p.N == 96) launch_one<24, 96>(p, grid, stream);
     else if (p.N == 144) launch_one<24, 144>(p, grid, stream);
@@ -152,6 +159,8 @@ int launch_pw_small(const PwSmallParams &p, hipStream_t stream) {
     if (p.N == 96) launch_one<16, 96>(p, grid, stream);
     else if (p.N == 144) launch_one<16, 144>(p, grid, stream);
     else launch_one<16, 192>(p, grid, stream);
+  } else if (p.N == 16) {
+    launch_one<32, 16>(p, grid, stream);
   } else {
     if (p.N == 96) launch_one<32, 96>(p, grid, stream);
     else if (p.N == 144) launch_one<32, 144>(p, grid, stream);

@@ -286,7 +286,7 @@ def test_1x1_layer_computed_behind_the_64_to_256_layer(oracle):
 
 def test_weights_stationary_1x1_few_input_channels(oracle):
     """1x1 layers with 16, 24 or 32 input and 96, 144 or 192 output channels at large batch (MobileNetV2's
-    first expand layers) take a streaming kernel of their own: every shape, input / output types,
+    first expand layers; also 32 -> 16, its first projection) take a streaming kernel of their own: every shape, input / output types,
     pixel counts that leave a ragged last block, a shift of zero, clips inside the range."""
     from concurrent.futures import ThreadPoolExecutor
     rng = np.random.default_rng(1696)
@@ -294,7 +294,8 @@ def test_weights_stationary_1x1_few_input_channels(oracle):
                                                (32, 192, 131073, 1, 1, "u8", "s8", 9, None), (16, 144, 1031, 7, 19, "s8", "s8", 0, (-50, 90)),
                                                (16, 192, 410, 31, 11, "u8", "u8", 10, (0, 1)), (32, 96, 300, 21, 21, "s8", "u8", 6, None),
                                                (24, 144, 45, 56, 56, "s8", "u8", 8, None), (24, 96, 1033, 127, 1, "u8", "s8", 7, (-100, 100)),
-                                               (24, 192, 2050, 8, 8, "u8", "u8", 9, None), (16, 96, 2, 56, 56, "s8", "u8", 8, None)):
+                                               (24, 192, 2050, 8, 8, "u8", "u8", 9, None), (32, 16, 47, 56, 56, "u8", "s8", 9, None),
+                                               (32, 16, 131075, 1, 1, "s8", "u8", 6, (1, 77)), (16, 96, 2, 56, 56, "s8", "u8", 8, None)):
         x, L, _ = wl.random_conv_case(rng, B, H, W, C, N, 1, 1, 1, 0, xt, yt, None, shift=shift, clip=clip)
         parts = np.array_split(np.arange(B), min(B, host_threads()))
         with ThreadPoolExecutor(len(parts)) as ex:
@@ -305,7 +306,7 @@ def test_weights_stationary_1x1_few_input_channels(oracle):
     chain = f8.Chain(net)
     names = [chain.layer_info(i, 256)[0] for i in range(len(net.layers))]
     assert names.count("pw1x1_small<16x96>") == 1 and names.count("pw1x1_small<24x144>") == 2
-    assert names.count("pw1x1_small<32x192>") == 3
+    assert names.count("pw1x1_small<32x192>") == 3 and names.count("pw1x1_small<32x16>") == 1      # + the first projection
     assert not any(chain.layer_info(i, 2)[0].startswith("pw1x1_small") for i in range(len(net.layers)))
 
 
