@@ -96,7 +96,7 @@ static bool use_pw_small(const void *x, const int8_t *w, const void *y, const vo
                          const f8_quant &q, const void *y2) {
   static const int on = [] { const char *e = getenv("F8_PW_SMALL"); return e ? atoi(e) : 1; }();   // tuning aid
   if (!on || res || y2 || q.y_type == F8_S32) return false;
-  if ((long long)g.B * g.H * g.W < 131072) return false;
+  if ((long long)g.B * g.H * g.W < 65536) return false;
   return pw_small_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
