@@ -213,6 +213,7 @@ bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
 const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
   if (use_pw_small(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) {
     if (g.Cout == 16) return "pw1x1_small<32x16>";
+    if (g.Cout == 64) return "pw1x1_small<32x64>";
     static const char *const names[3][3] = {{"pw1x1_small<16x96>", "pw1x1_small<16x144>", "pw1x1_small<16x192>"},
                                             {"pw1x1_small<24x96>", "pw1x1_small<24x144>", "pw1x1_small<24x192>"},
                                             {"pw1x1_small<32x96>", "pw1x1_small<32x144>", "pw1x1_small<32x192>"}};

@@ -1,6 +1,6 @@
 // Weights-stationary 1x1 convolution with 16, 24 or 32 input channels and 96, 144 or 192 output channels
 // (F8Net Eq. 2 / Eq. 9 epilogue), the shape of MobileNetV2's first expand layers; also 32 -> 16 channels,
-// its first projection.
+// its first projection, and 32 -> 64, MobileNetV1's first pointwise layer.
 //
 // These layers write six times what they read and have one K slice of matrix work per output
 // block: the general tiled kernel spends its time on set-up.  Here, as in pw_ws.hip, every wave keeps
@@ -137,7 +137,7 @@ void launch_one(const PwSmallParams &p, long long wgs, hipStream_t stream) {
 bool pw_small_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int shift,
                          const void *x, const void *w, const void *y) {
   const bool expand = (Cin == 16 || Cin == 24 || Cin == 32) && (Cout == 96 || Cout == 144 || Cout == 192);
-  const bool project = Cin == 32 && Cout == 16;
+  const bool project = Cin == 32 && (Cout == 16 || Cout == 64);      // (32 -> 64: MobileNetV1's first pointwise layer)
   if (!expand && !project) return false;
   if (R != 1 || S != 1 || sh != 1 || sw != 1 || ph != 0 || pw != 0 || shift < 0) return false;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
@@ -161,6 +161,8 @@ int launch_pw_small(const PwSmallParams &p, hipStream_t stream) {
     else launch_one<16, 192>(p, grid, stream);
   } else if (p.N == 16) {
     launch_one<32, 16>(p, grid, stream);
+  } else if (p.N == 64) {
+    launch_one<32, 64>(p, grid, stream);
   } else {
     if (p.N == 96) launch_one<32, 96>(p, grid, stream);
     else if (p.N == 144) launch_one<32, 144>(p, grid, stream);

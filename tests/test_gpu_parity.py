@@ -295,7 +295,7 @@ def test_weights_stationary_1x1_few_input_channels(oracle):
                                                (16, 192, 410, 31, 11, "u8", "u8", 10, (0, 1)), (32, 96, 300, 21, 21, "s8", "u8", 6, None),
                                                (24, 144, 45, 56, 56, "s8", "u8", 8, None), (24, 96, 1033, 127, 1, "u8", "s8", 7, (-100, 100)),
                                                (24, 192, 2050, 8, 8, "u8", "u8", 9, None), (32, 16, 47, 56, 56, "u8", "s8", 9, None),
-                                               (32, 16, 131075, 1, 1, "s8", "u8", 6, (1, 77)), (16, 96, 2, 56, 56, "s8", "u8", 8, None)):
+                                               (32, 16, 131075, 1, 1, "s8", "u8", 6, (1, 77)), (32, 64, 83, 28, 29, "u8", "u8", 8, None), (16, 96, 2, 56, 56, "s8", "u8", 8, None)):
         x, L, _ = wl.random_conv_case(rng, B, H, W, C, N, 1, 1, 1, 0, xt, yt, None, shift=shift, clip=clip)
         parts = np.array_split(np.arange(B), min(B, host_threads()))
         with ThreadPoolExecutor(len(parts)) as ex:
