@@ -19,25 +19,36 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 matrix peak, TOP/s
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak, GB/s
 
-# HBM traffic per launch (MB, mean over the launches of one ResNet-50 batch-256 forward) from
-# the rocprofv3 FETCH_SIZE / WRITE_SIZE counters, each scaled by what the same counter reads
-# for the plain copy kernel on 1 GiB (fetch x 2.000, write x 1.000); the runs and the table
-# are in profiles/resnet50_b256_hbm_traffic.md.  Counters cannot be read from inside this
-# process, so the figure of the dominant kernel is reported from here.
-MEASURED_TRAFFIC_MB = {
-    "conv_fast<128x128,k64,s2>": 162.81,
-    "conv_fast<128x128,k64,s3>": 103.24,
-    "conv_fast<128x64,k64,s2>": 102.93,
-    "conv3x3_ws<64x64>": 184.83,
-    "conv3x3_ws<128x128>": 92.17,
-    "pw1x1_ws<64x256>": 257.13,
-    "pw1x1_ws<64x256>+1x1<64>": 514.24,
-    "pw1x1_ws<64x256>+1x1<128>": 565.78,
-    "stem_pool_fused": 272.19,        # re-layout pass 94.70 + fused stem and pool 177.49
-    "conv_fast<128x128,k128,s2>": 141.85,
-    "conv_fast<256x256,k128,s2,w4x2>": 57.18,
-    "conv_fast<256x128,k128,s2,w4x2>": 41.71,
-}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "resnet50_b256_hbm_traffic.md")
+KERNEL_SOURCES = os.path.join(ROOT, "paper_2202_05239_amd", "csrc")
+
+
+def kernel_source_hash():
+    """Short hash over the kernel sources: ties a committed counter profile to the code it measured."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCES)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(KERNEL_SOURCES, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of every kernel of the ResNet-50 batch-256 forward, from the committed
+    rocprofv3 FETCH_SIZE / WRITE_SIZE summary (counters cannot be read from inside this process).
+    Returns ({bench kernel name: MB per launch}, the kernel-source hash the profile was taken at)."""
+    table, src = {}, None
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("kernel sources:"):
+                src = line.split(":", 1)[1].strip()
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 6 and cells[0].startswith("`") and cells[-1].replace(".", "", 1).isdigit():
+                table[cells[0].strip("`")] = float(cells[-1])
+    except OSError:
+        pass
+    return table, src
 
 
 def cpu_baseline(net, x, threads, images):
@@ -101,6 +112,14 @@ def single_layer_figures(torch, f8, wl, repeats):
     e1.record()
     torch.cuda.synchronize()
     out["copy 1 GiB"] = {"GBs_read_plus_write": 2.0 * n * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+    # register-only loop of the int8 matrix instruction: the practical ceiling of the matrix cores
+    sink = torch.empty(f8.F8_YARDSTICK_SINK_INTS, dtype=torch.int32, device="cuda")
+    f8.f8_mfma_i8_yardstick(sink, 2000)
+    e0.record()
+    ops = sum(f8.f8_mfma_i8_yardstick(sink, 20000) for _ in range(5))
+    e1.record()
+    torch.cuda.synchronize()
+    out["mfma i8 register-only loop"] = {"TOPS": ops / (e0.elapsed_time(e1) * 1e-3) / 1e12}
     return out
 
 
@@ -116,6 +135,17 @@ def copy_calibration():
         f8.f8_copy_bytes(a, b)
     torch.cuda.synchronize()
     print(json.dumps({"copy_bytes_per_launch": n}))
+
+
+def mfma_calibration():
+    """Three launches of the register-only int8 matrix-instruction loop: the known-size reference
+    for the matrix-core counters (every SIMD issues matrix instructions back to back)."""
+    import torch
+    from paper_2202_05239_amd import binding as f8
+    sink = torch.empty(f8.F8_YARDSTICK_SINK_INTS, dtype=torch.int32, device="cuda")
+    ops = [f8.f8_mfma_i8_yardstick(sink, 20000) for _ in range(3)]
+    torch.cuda.synchronize()
+    print(json.dumps({"mfma_ops_per_launch": ops[0]}))
 
 
 def quant_tools_figures(repeats=10):
@@ -180,6 +210,8 @@ def main():
     ap.add_argument("--no-single-layer", action="store_true", help="skip the configs[1] / configs[2] layer figures")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (reference for the traffic counters)")
+    ap.add_argument("--mfma-calibration", action="store_true",
+                    help="only run the register-only matrix-instruction loop (reference for the matrix-core counters)")
     ap.add_argument("--quant-tools", action="store_true",
                     help="only time the steps upstream of the integer layers (quantisers, statistics, folding)")
     args = ap.parse_args()
@@ -190,6 +222,9 @@ def main():
 
     if args.copy_calibration:
         copy_calibration()
+        return
+    if args.mfma_calibration:
+        mfma_calibration()
         return
     if args.quant_tools:
         quant_tools_figures()
@@ -236,6 +271,16 @@ def main():
         step(xt, out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the same steps once more with an event between them (on the stream they run on): per-step
+    # device times for the median; `value` above comes from the host clock around all K steps
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        step(xt, out)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
     if not torch.equal(out, eager):
         print("bench.py: graph replay differs from the eager run", file=sys.stderr)
         sys.exit(4)
@@ -258,8 +303,19 @@ def main():
     else:
         ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
-    traffic = MEASURED_TRAFFIC_MB.get(dom) if (args.net == "resnet50" and B == 256) else None
+    # counter traffic: only for the workload the committed profile covers, and only if the kernel
+    # sources are the ones it was measured on (null otherwise, with the reason)
+    table, profiled_src = traffic_from_profile()
+    traffic, note = None, "no counter profile for this workload"
+    if args.net == "resnet50" and B == 256:
+        if profiled_src != kernel_source_hash():
+            note = "profiles/resnet50_b256_hbm_traffic.md was measured on other kernel sources (%s)" % profiled_src
+        elif dom not in table:
+            note = "kernel not in profiles/resnet50_b256_hbm_traffic.md"
+        else:
+            traffic, note = table[dom], "profiles/resnet50_b256_hbm_traffic.md (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the copy kernel)"
     roof.update({"traffic": traffic * 1e6 if traffic is not None else None, "traffic_unit": "bytes per launch",
+                 "traffic_source": note,
                  "alg_bytes_per_launch": d["bytes"] / d["launches"], "kernel": dom, "launches_per_step": d["launches"],
                  "avg_launch_us": d["ms"] * 1e3 / d["launches"],
                  "alg_ops_per_step": d["ops"], "alg_bytes_per_step": d["bytes"],
@@ -274,7 +330,7 @@ def main():
                   % ({"resnet50": "ResNet-50", "resnet18": "ResNet-18", "mobilenetv2": "MobileNetV2", "mobilenetv1": "MobileNetV1",
                       "resnet50_private_fl": "ResNet-50 (two formats per block output)"}[args.net], B),
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "median_ms_per_step": median_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: full %s fixed-point forward, batch %d, 224x224x3, seeded FL per layer"
                                % ({"resnet50": "configs[4]", "resnet18": "configs[3]"}.get(args.net, "extra"),

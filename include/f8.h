@@ -305,6 +305,24 @@ void f8_release_scratch(void);
  * yardstick for what HBM delivers to a kernel that reads and writes every byte once, and the
  * known-size reference against which the memory-traffic counters are scaled. */
 f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream);
+/* Measurement aid: a register-only loop of the int8 matrix instruction the dense kernels use
+ * (32x32x32, eight independent accumulators per wave, two waves per SIMD on every CU, no
+ * memory traffic).  Its rate is the practical ceiling of the matrix cores, quoted next to the
+ * published peak.  `sink` is a device buffer of at least F8_YARDSTICK_SINK_INTS ints (one
+ * checksum per thread, contents meaningless); `iters` is the loop count per wave (1 .. 2^24);
+ * *ops (host pointer, may be NULL) receives the operations one launch performs (2 per
+ * multiply-accumulate). */
+#define F8_YARDSTICK_SINK_INTS (512 * 256)
+f8_status f8_mfma_i8_yardstick(int32_t *sink, int iters, double *ops, void *stream);
+/* Tuning switches: kernel choices only, never results (the parity tests force every tile variant
+ * through them).  Names and defaults: "conv_variant" (-1 = automatic; >= 0 forces that tile
+ * variant of the LDS-direct dense kernel), "conv_ws", "pw_ws", "pw_small", "xcd_remap",
+ * "stem_pool", "conv_tail" (1 = on).  The environment variables F8_<NAME IN CAPITALS> give the
+ * initial values; they are read once, when the library first looks at a switch, never on the
+ * launch path.  f8_tuning_set returns 0, or -1 for an unknown name; the two chain switches are
+ * read by f8_chain_create.  f8_tuning_get returns the value (-1 for an unknown name). */
+int f8_tuning_set(const char *name, int value);
+int f8_tuning_get(const char *name);
 /* Library version, for the binding to check that it loaded what it was built against. */
 int f8_abi_version(void);
 

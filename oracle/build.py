@@ -16,5 +16,17 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(HERE, "libf8ref_san.so")
+
+
+def build_sanitized() -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (bad shifts, signed
+    overflow, out-of-bounds indexing abort the process): for the test that re-runs the pins on it."""
+    cmd = ["gcc", "-O1", "-g", "-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-o", SAN_LIB, SRC]
+    subprocess.run(cmd, check=True)
+    return SAN_LIB
+
+
 if __name__ == "__main__":
     print(build())

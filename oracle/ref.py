@@ -42,7 +42,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # F8REF_LIB selects another build of the same source (the sanitizer build of the tests)
+        path = os.environ.get("F8REF_LIB") or _build.build(force=False)
         L = ctypes.CDLL(path)
         L.f8ref_shift_round.restype = ctypes.c_int64
         L.f8ref_shift_round.argtypes = [ctypes.c_int64, ctypes.c_int]

@@ -24,7 +24,7 @@
 #include <cstdlib>
 #include <type_traits>
 
-#include "conv_igemm.h"
+#include "f8_host.h"
 
 namespace f8 {
 
@@ -32,29 +32,6 @@ namespace {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-
-// Optional timeline of every workgroup (built only with -DF8_TRACE, never in the product
-// library): 8 slots of the 100 MHz wall clock per workgroup, written by thread 0.
-#ifdef F8_TRACE
-#ifndef F8_EXP_BITS
-#define F8_EXP_BITS 0          // timing experiments (results invalid): 1 no refill loads, 2 no fragment reads, 4 no matrix ops, 8 no xor
-#endif
-#define F8_EXP(bit) ((F8_EXP_BITS) & (bit))
-static unsigned long long *g_trace_host = nullptr;    // device buffer handed to the next launches
-#define F8_TRACE_POINT(i)                                                                         \
-  do {                                                                                            \
-    if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64();      \
-  } while (0)
-#define F8_TRACE_HWID()                                                                           \
-  do {                                                                                            \
-    if (threadIdx.x == 0 && p.trace)                                                              \
-      p.trace[(size_t)blockIdx.x * 8 + 7] = (unsigned long long)__builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)); \
-  } while (0)
-#else
-#define F8_EXP(bit) 0
-#define F8_TRACE_POINT(i) do {} while (0)
-#define F8_TRACE_HWID() do {} while (0)
-#endif
 
 // One LDS-direct load per call, whatever the predicate: the source address is selected as
 // data (the empty asm keeps the compiler from turning the select into two loads under
@@ -123,8 +100,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   static_assert(NB + MB <= 15, "fragment reads of half a step must fit lgkmcnt");
 
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  F8_TRACE_POINT(0);
-  F8_TRACE_HWID();
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -287,7 +262,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   // accumulator start values and the residual tile follow them in the queue (loads return in
   // order, so waiting for a later stage also covers these), then the remaining stages.
   __builtin_amdgcn_sched_barrier(0);
-  F8_TRACE_POINT(1);
   {
     const StepCtx c = decode_step(0, 0);
 #pragma unroll
@@ -338,7 +312,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     }
   }
   auto read_frags = [&](int stage, int ks, v4i (&fa)[NB], v4i (&fb)[MB]) {
-    if (F8_EXP(2)) return;
     const uint32_t xs = lds_base + (uint32_t)(stage * STAGE + wm0 * BK);
     const uint32_t ws = lds_base + (uint32_t)(stage * STAGE + BM * BK + wn0 * BK);
 #pragma unroll
@@ -363,7 +336,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       asm volatile("" : "+v"(fb[mb]));
-      if (!F8_EXP(8)) { fb[mb].x ^= xmask; fb[mb].y ^= xmask; fb[mb].z ^= xmask; fb[mb].w ^= xmask; }
+      fb[mb].x ^= xmask; fb[mb].y ^= xmask; fb[mb].z ^= xmask; fb[mb].w ^= xmask;
     }
   };
 
@@ -374,10 +347,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   // passed, is refilled with the loads of K step t + NSTAGE, spread between the matrix
   // instructions.  Three instances of the step body: with refill, without, and the last
   // step (nothing follows).
-  F8_TRACE_POINT(2);
   wait_ahead<NSTAGE - 1, LPS>(min(NSTAGE - 1, ksteps - 1));
   __syncthreads();
-  F8_TRACE_POINT(3);
   v4i fa[2][NB], fb[2][MB];
   read_frags(0, 0, fa[0], fb[0]);
   land_frags(fa[0], fb[0]);
@@ -387,8 +358,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     constexpr bool NEXT = decltype(next_tag)::value;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      constexpr int DUMMY = 0;
-      (void)DUMMY;
       const int cur = ks & 1, nxt = cur ^ 1;
       const bool last_slice = ks == KS - 1;
       StepCtx c{};
@@ -415,13 +384,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
       for (int q = 0; q < NMF; ++q) {
         const int nb = q / MB, mb = q % MB;
         if (q == NMF - 1 && reads) land_frags(fa[nxt], fb[nxt]);
-        if (!F8_EXP(4)) acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
+        acc[nb][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][nb], fb[cur][mb], acc[nb][mb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (SPREAD && reads && q < NB + MB) {
           read_one(rstage, rks, q, fa[nxt], fb[nxt]);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (last_slice && REFILL && !F8_EXP(1)) {
+        if (last_slice && REFILL) {
 #pragma unroll
           for (int j = q * LPM; j < (q + 1) * LPM && j < LPS; ++j) issue_one(c, j);
           __builtin_amdgcn_sched_barrier(0);
@@ -436,7 +405,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     for (; t + 1 < ksteps; ++t) kstep_body(t, std::false_type{}, std::true_type{});
     kstep_body(t, std::false_type{}, std::false_type{});
   }
-  F8_TRACE_POINT(4);
   wait_vm<0>();
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
 
@@ -545,7 +513,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     }
   }
   __syncthreads();
-  F8_TRACE_POINT(5);
   uint8_t *y = static_cast<uint8_t *>(p.y);
   for (int idx = tid; idx < BM * CPR; idx += NT) {
     const int row = idx / CPR, pc = idx - row * CPR;
@@ -571,7 +538,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
       }
     }
   }
-  F8_TRACE_POINT(6);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>
@@ -597,13 +563,7 @@ int launch_fast_tile_ev(const ConvParams &p, hipStream_t stream) {
     if (e != hipSuccess) return (int)e;
     if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
   }
-#ifdef F8_TRACE
-  ConvParams pt = p;
-  pt.trace = g_trace_host;
-  hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(64 * WAVES_M * WAVES_N), smem, stream, pt, tiles_n, (int)ntiles);
-#else
   hipLaunchKernelGGL(k, dim3((unsigned)ntiles), dim3(64 * WAVES_M * WAVES_N), smem, stream, p, tiles_n, (int)ntiles);
-#endif
   return (int)hipGetLastError();
 }
 
@@ -630,20 +590,7 @@ const char *const kVariantNames[N_VARIANTS] = {
     "conv_fast<256x256,k128,s2,w2x4>", "conv_fast<256x256,k128,s2,w4x2>", "conv_fast<256x256,k64,s3,w2x4>",
     "conv_fast<256x128,k128,s2,w4x2>", "conv_fast<256x256,k128,s2,w2x2>", "conv_fast<256x256,k64,s3,w2x2>"};
 
-int forced_variant() {
-  const char *e = getenv("F8_CONV_VARIANT");     // tuning aid: force one tile variant
-  return e ? atoi(e) : -1;
-}
-
 }  // namespace
-
-#ifdef F8_TRACE
-extern "C" int f8_trace_exp(int bits) { return bits == (F8_EXP_BITS) ? 0 : 1; }
-extern "C" int f8_trace_buffer(void *device_ptr) {
-  g_trace_host = static_cast<unsigned long long *>(device_ptr);
-  return 0;
-}
-#endif
 
 bool conv_fast_applicable(const ConvParams &p) {
   const uintptr_t bits = reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w);
@@ -666,7 +613,7 @@ bool conv_fast_applicable(const ConvParams &p) {
 }
 
 int conv_fast_variant(const ConvParams &p) {
-  const int f = forced_variant();
+  const int f = tuning().conv_variant.load(std::memory_order_relaxed);      // tuning aid: force one tile variant
   if (f >= 0 && f < N_VARIANTS) return f;
   // Rules fitted to measurements of every variant on the ResNet-50 (batch 256) and ResNet-18
   // (batch 64) layer shapes on MI355X.  Bigger tiles move fewer bytes from L2 into LDS per

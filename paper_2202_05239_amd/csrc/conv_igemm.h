@@ -33,7 +33,6 @@ struct ConvParams {
   uint32_t x_delta, z_delta;
   int near;
   uint32_t tap_rep;         // bit r * S set for every window row r (R * S <= 32, else unused)
-  unsigned long long *trace;   // per-workgroup timeline buffer; only read by -DF8_TRACE builds, else null
   FastDiv fd_pq, fd_q, fd_c, fd_s, fd_cpt, fd_cpt2;   // by P*Q, Q, C, S, C / 64, C / 128
 };
 

@@ -1,11 +1,33 @@
 // C-ABI entry points of the single-layer calls: validation on the host, then launches.
 #include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <unordered_map>
 
 #include "f8_host.h"
 
 namespace f8 {
+
+namespace {
+struct TuningName { const char *name; const char *env; std::atomic<int> Tuning::*field; };
+const TuningName kTuningNames[] = {
+    {"conv_variant", "F8_CONV_VARIANT", &Tuning::conv_variant}, {"conv_ws", "F8_CONV_WS", &Tuning::conv_ws},
+    {"pw_ws", "F8_PW_WS", &Tuning::pw_ws},                       {"pw_small", "F8_PW_SMALL", &Tuning::pw_small},
+    {"xcd_remap", "F8_XCD_REMAP", &Tuning::xcd_remap},           {"stem_pool", "F8_STEM_POOL", &Tuning::stem_pool},
+    {"conv_tail", "F8_CONV_TAIL", &Tuning::conv_tail},
+};
+}  // namespace
+
+Tuning &tuning() {
+  // the environment is read here, once, the first time any switch is looked at
+  static Tuning *t = [] {
+    Tuning *n = new Tuning();
+    for (const TuningName &k : kTuningNames)
+      if (const char *e = getenv(k.env)) (n->*(k.field)).store(atoi(e));
+    return n;
+  }();
+  return *t;
+}
 
 f8_status check_quant(const f8_quant *q, bool allow_res) {
   if (!q) return F8_ERR_NULL;
@@ -72,8 +94,7 @@ static int widest_vec(int C, const void *a, const void *b) {
 // The 3x3 64 -> 64 layers have a kernel of their own (weights in registers, input patch in LDS).
 static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
                         const f8_quant &q, const void *y2) {
-  static const int on = [] { const char *e = getenv("F8_CONV_WS"); return e ? atoi(e) : 1; }();   // tuning aid
-  if (!on || res || y2 || q.y_type == F8_S32) return false;
+  if (!tuning().conv_ws.load(std::memory_order_relaxed) || res || y2 || q.y_type == F8_S32) return false;
   // it pays once a workgroup walks over several tiles (measured: level with the general kernel at
   // 800 and 1600 tiles of 128 pixels, 15-20 % ahead at 6400)
   const int tile = conv_ws_tile_pixels(g.Cin);
@@ -84,8 +105,7 @@ static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const voi
 // So do the 1x1 64 -> 256 layers (weights in registers, every wave streams pixels on its own).
 static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
                       const f8_quant &q, const void *y2) {
-  static const int on = [] { const char *e = getenv("F8_PW_WS"); return e ? atoi(e) : 1; }();   // tuning aid
-  if (!on || y2 || q.y_type == F8_S32 || (res && q.res_type == F8_S32)) return false;
+  if (!tuning().pw_ws.load(std::memory_order_relaxed) || y2 || q.y_type == F8_S32 || (res && q.res_type == F8_S32)) return false;
   // it pays once every workgroup walks over several blocks of pixels
   if ((long long)g.B * g.H * g.W < 131072) return false;
   return pw_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
@@ -94,8 +114,7 @@ static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void 
 // And the 1x1 layers with 16 or 32 input and 96 / 144 / 192 output channels (MobileNetV2's first expand layers).
 static bool use_pw_small(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
                          const f8_quant &q, const void *y2) {
-  static const int on = [] { const char *e = getenv("F8_PW_SMALL"); return e ? atoi(e) : 1; }();   // tuning aid
-  if (!on || res || y2 || q.y_type == F8_S32) return false;
+  if (!tuning().pw_small.load(std::memory_order_relaxed) || res || y2 || q.y_type == F8_S32) return false;
   if ((long long)g.B * g.H * g.W < 65536) return false;
   return pw_small_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
@@ -191,9 +210,8 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   p.fd_c = FastDiv((uint32_t)g.Cin);
   p.fd_cpt = FastDiv((uint32_t)((g.Cin & 63) == 0 ? g.Cin / 64 : 1));
   p.fd_cpt2 = FastDiv((uint32_t)((g.Cin & 127) == 0 ? g.Cin / 128 : 1));
-  { static const int rm = [] { const char *e = getenv("F8_XCD_REMAP"); return e ? atoi(e) : 1; }(); p.remap = rm != 0; }
+  p.remap = tuning().xcd_remap.load(std::memory_order_relaxed) != 0;
   p.fd_s = FastDiv((uint32_t)g.S);
-  p.trace = nullptr;
   p.tap_rep = 0;
   if (g.R * g.S <= 32)
     for (int r = 0; r < g.R; ++r) p.tap_rep |= 1u << (r * g.S);
@@ -285,14 +303,17 @@ f8_status enqueue_gpool(const void *x, void *y, const Geom &g, const f8_quant &q
 // ---- per-stream scratch for the folded accumulator start values ------------------------
 namespace {
 struct Scratch { int32_t *ptr; size_t ints; };
+// Held from the look-up of a stream's buffer until both kernels of the call (the fold that
+// writes the buffer and the layer that reads it) are enqueued, so that two host threads
+// calling on one stream cannot interleave their folds and layers.
 std::mutex g_mu;
 std::unordered_map<uint64_t, Scratch> g_scratch;   // key: device id, stream handle
 
+// Caller holds g_mu.
 int32_t *scratch_for(hipStream_t stream, size_t ints) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return nullptr;
   const uint64_t key = (reinterpret_cast<uint64_t>(stream) << 4) ^ (uint64_t)dev;
-  std::lock_guard<std::mutex> lock(g_mu);
   Scratch &s = g_scratch[key];
   if (s.ints < ints) {
     // Growing: work already queued on this stream may still read the old buffer.
@@ -316,6 +337,18 @@ int32_t *scratch_for(hipStream_t stream, size_t ints) {
   }
   return s.ptr;
 }
+
+// Fold + layer of one single-layer dense call on the stream's own scratch.
+f8_status dense_on_stream_scratch(const void *x, const int8_t *w, const int32_t *bias, void *y, const Geom &g,
+                                  const f8_quant &q, hipStream_t s, const f8_requant2 *q2, void *y2) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  int32_t *scratch = scratch_for(s, 64 + acc0_padded(g.Cout));
+  if (!scratch) return F8_ERR_DEVICE;
+  int32_t *acc0 = scratch + 64;
+  const f8_status st = enqueue_fold(w, bias, acc0, g, q, s);
+  if (st != F8_OK) return st;
+  return enqueue_conv(x, w, acc0, scratch, y, q.res, g, q, s, q2, y2);
+}
 }  // namespace
 
 }  // namespace f8
@@ -337,13 +370,7 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
   if (st != F8_OK) return st;
   if (q->res == y) return F8_ERR_UNSUPPORTED;
   if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t *scratch = scratch_for(s, 64 + acc0_padded(Cout));
-  if (!scratch) return F8_ERR_DEVICE;
-  int32_t *acc0 = scratch + 64;
-  st = enqueue_fold(w, bias, acc0, g, *q, s);
-  if (st != F8_OK) return st;
-  return enqueue_conv(x, w, acc0, scratch, y, q->res, g, *q, s);
+  return dense_on_stream_scratch(x, w, bias, y, g, *q, static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 f8_status f8_conv2d_fixed_dual(const void *x, const int8_t *w, const int32_t *bias, void *y, void *y2, int B, int H,
@@ -361,13 +388,7 @@ f8_status f8_conv2d_fixed_dual(const void *x, const int8_t *w, const int32_t *bi
   if (st != F8_OK) return st;
   if (q->res == y || q->res == y2 || y == y2) return F8_ERR_UNSUPPORTED;
   if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t *scratch = scratch_for(s, 64 + acc0_padded(Cout));
-  if (!scratch) return F8_ERR_DEVICE;
-  int32_t *acc0 = scratch + 64;
-  st = enqueue_fold(w, bias, acc0, g, *q, s);
-  if (st != F8_OK) return st;
-  return enqueue_conv(x, w, acc0, scratch, y, q->res, g, *q, s, q2, y2);
+  return dense_on_stream_scratch(x, w, bias, y, g, *q, static_cast<hipStream_t>(stream), q2, y2);
 }
 
 f8_status f8_gemm_fixed(const void *x, const int8_t *w, const int32_t *bias, void *y, int M, int K, int N,
@@ -460,6 +481,23 @@ f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream) 
   return launch_copy(src, dst, bytes, static_cast<hipStream_t>(stream)) == 0 ? F8_OK : F8_ERR_DEVICE;
 }
 
-int f8_abi_version(void) { return 2; }
+int f8_tuning_set(const char *name, int value) {
+  if (!name) return -1;
+  for (const TuningName &k : kTuningNames)
+    if (strcmp(name, k.name) == 0) {
+      (tuning().*(k.field)).store(value);
+      return 0;
+    }
+  return -1;
+}
+
+int f8_tuning_get(const char *name) {
+  if (!name) return -1;
+  for (const TuningName &k : kTuningNames)
+    if (strcmp(name, k.name) == 0) return (tuning().*(k.field)).load();
+  return -1;
+}
+
+int f8_abi_version(void) { return 3; }
 
 }  // extern "C"

@@ -453,7 +453,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   if (st != F8_OK) { delete c; return st; }
   c->last_tensor = c->layers.back().dst;
   c->tensors[c->last_tensor].external = true;
-  { const char *e = getenv("F8_STEM_POOL"); c->stem_pool = !(e && atoi(e) == 0); }
+  c->stem_pool = tuning().stem_pool.load() != 0;
   // a stem whose only reader is a 3x3 stride-2 pad-1 max pool: both in one kernel
   for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
     const f8_layer_desc &L = c->layers[i], &M = c->layers[i + 1];
@@ -468,7 +468,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     c->stem[i].pool = 1;
     c->stem[i + 1].pool = 2;
   }
-  { const char *e = getenv("F8_CONV_TAIL"); c->conv_tail = !(e && atoi(e) == 0); }      // tuning aid
+  c->conv_tail = tuning().conv_tail.load() != 0;      // tuning aid
   // a 1x1 64 -> 256 layer and a 1x1 layer of 64 or 128 channels that reads it (the hand-over between two
   // bottleneck blocks): the second can run on each block of the first one's output while it is in LDS.
   // It is the next layer, or the one after it when the layer between them takes no part in a pair (the

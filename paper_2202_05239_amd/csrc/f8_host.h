@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/f8.h"
 #include "conv_igemm.h"
 #include "conv_ws.h"
@@ -13,6 +15,20 @@
 #include "dwconv_pool.h"
 
 namespace f8 {
+
+// Tuning switches (kernel choices only: results never depend on them).  Set once from the
+// environment when the library is loaded (F8_CONV_VARIANT, F8_CONV_WS, ...: see f8_tuning_set in
+// the C header) and afterwards only through f8_tuning_set; the launch paths read these ints.
+struct Tuning {
+  std::atomic<int> conv_variant{-1};   // >= 0: force this tile variant of the LDS-direct dense kernel
+  std::atomic<int> conv_ws{1};         // weights-stationary 3x3 kernel
+  std::atomic<int> pw_ws{1};           // weights-stationary 1x1 kernel (64 -> 256)
+  std::atomic<int> pw_small{1};        // streaming 1x1 kernel for few input channels
+  std::atomic<int> xcd_remap{1};       // XCD-aware tile order
+  std::atomic<int> stem_pool{1};       // chain: stem and max pool as one kernel
+  std::atomic<int> conv_tail{1};       // chain: next block's first 1x1 layer computed behind a closing layer
+};
+Tuning &tuning();
 
 // Geometry of a convolution-like layer.
 struct Geom {

@@ -51,6 +51,13 @@ def gpu_layer(L, x, res=None, offset=0):
     return y.cpu().numpy()
 
 
+@pytest.fixture
+def forced_variant():
+    """Force one tile variant of the LDS-direct dense kernel for the length of a test."""
+    yield lambda v: f8.f8_tuning_set("conv_variant", v)
+    f8.f8_tuning_set("conv_variant", -1)
+
+
 def assert_same(got, want, what=""):
     assert got.shape == want.shape and got.dtype == want.dtype, (what, got.shape, want.shape, got.dtype, want.dtype)
     if not np.array_equal(got, want):
@@ -135,6 +142,15 @@ def check_network(oracle, x, net, oracle_images, what, lean_is_smaller=True):
     b = lean.run(xt)
     torch.cuda.synchronize()
     assert torch.equal(a, out) and torch.equal(b, out), what + " lean plan / rerun"
+    # the tensors of the memory-reusing plan (the one bench.py times) that are still whole after
+    # the run, against the oracle itself
+    survivors = 0
+    for L in net.layers[:-1]:
+        t = lean.tensor(L.dst)
+        if t is not None:
+            survivors += 1
+            assert_same(t.cpu().numpy()[idx], want[L.dst], "%s lean plan, layer %s" % (what, L.name))
+    assert survivors > 0 or len(net.layers) < 3
     if lean_is_smaller:          # (a net of a few layers may have nothing to reuse)
         assert lean.workspace_bytes(x.shape[0]) < chain.workspace_bytes(x.shape[0])
     else:
@@ -159,6 +175,30 @@ def test_config4_resnet50(oracle):
     imgs = [0, 1, 2, 3, 100, 101, 254, 255]
     out = check_network(oracle, x, net, imgs, "config4")
     assert out.shape == (256, 1, 1, 1000)
+
+
+def full_batch_logits(oracle, x, net, what):
+    """Every image of the batch: the logits of the memory-reusing chain (fused stem, paired 1x1
+    layers: the launch configuration bench.py times) against the oracle's, image by image."""
+    xt = torch.from_numpy(x).to(DEV)
+    out = f8.Chain(net).prepare(x.shape[0]).run(xt)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    step = 4 * host_threads()
+    for i0 in range(0, x.shape[0], step):
+        want = oracle.run_network_parallel(net, np.ascontiguousarray(x[i0:i0 + step]), host_threads())
+        assert_same(got[i0:i0 + step], want, "%s logits of images %d.." % (what, i0))
+        print("%s: images %d..%d match" % (what, i0, min(i0 + step, x.shape[0]) - 1), flush=True)
+
+
+def test_config3_resnet18_every_image(oracle):
+    x, net = wl.config3()                                           # batch 64, all 64 x 1000 logits
+    full_batch_logits(oracle, x, net, "config3")
+
+
+def test_config4_resnet50_every_image(oracle):
+    x, net = wl.config4()                                           # batch 256, all 256 x 1000 logits
+    full_batch_logits(oracle, x, net, "config4")
 
 
 def test_mobilenet_v2_forward(oracle):
@@ -528,11 +568,11 @@ SINGLE_STAGE = {8: 64, 9: 128, 10: 64}          # variants that hold the whole K
 
 
 @pytest.mark.parametrize("variant", range(N_TILE_VARIANTS))
-def test_every_tile_variant(oracle, variant, monkeypatch):
+def test_every_tile_variant(oracle, variant, forced_variant):
     """The tile choice is a tuning decision, never a numerical one: every tile variant of the
     fast dense kernel, forced through the tuning knob, gives the oracle's bits on ragged
     shapes (tails in M, N and K, padding, stride, residual, both K-step widths)."""
-    monkeypatch.setenv("F8_CONV_VARIANT", str(variant))
+    forced_variant(variant)
     kmax = SINGLE_STAGE.get(variant)
     cases = [
         (2, 19, 23, 64, 72, 1, 1, 1, 0, "u8", "u8", "u8"),           # K = 64: one step for everyone
@@ -575,11 +615,11 @@ DUAL_CASES = [
 
 
 @pytest.mark.parametrize("variant", [None, 3, 10, 14, 19, 21])
-def test_two_output_formats(oracle, variant, monkeypatch):
+def test_two_output_formats(oracle, variant, forced_variant):
     """One accumulator, two 8-bit outputs with their own fractional lengths and clips: each must be
     the layer evaluated with that format (one rounding each, never a re-rounding of the other)."""
     if variant is not None:
-        monkeypatch.setenv("F8_CONV_VARIANT", str(variant))
+        forced_variant(variant)
     rng = np.random.default_rng(77 + (variant or 0))
     for case in DUAL_CASES:
         B, H, W, Cin, Cout, R, S, st, pd, xt, yt, y2t, rt, sh, sh2, off = case

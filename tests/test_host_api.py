@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(f8.EXPORTS) == names
-    assert L.f8_abi_version() == 2
+    assert L.f8_abi_version() == 3
 
 
 def quant(**kw):

@@ -123,7 +123,77 @@ def test_pact_float32_path_is_within_one_code_of_fp64():
     assert np.mean(np.abs(y32 - y64) > 1e-5) < 1e-3
 
 
+def round_to_f32(fr):
+    """A rational rounded to the nearest float32 (ties to even), returned as a rational: the
+    IEEE-754 rounding every float32 operation applies to its exact result (normal range only)."""
+    if fr == 0:
+        return Fraction(0)
+    sign, a = (-1 if fr < 0 else 1), abs(fr)
+    e = 0
+    while a >= Fraction(2) ** (e + 1):
+        e += 1
+    while a < Fraction(2) ** e:
+        e -= 1
+    assert -126 <= e <= 127
+    ulp = Fraction(2) ** (e - 23)
+    m = a / ulp
+    lo = math.floor(m)
+    if m - lo > Fraction(1, 2) or (m - lo == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return sign * lo * ulp
+
+
+def test_pact_float32_step_order_exact():
+    """The float32 readings of Eq. 3 and Eq. 4 (every operation rounded to float32, in the order
+    of the equation) against that order written out with rationals and an explicit model of
+    float32 rounding: equality on every point, ties included (the value that is rounded to a
+    code is itself a float32, so a tie is a well-defined input)."""
+    rng = np.random.default_rng(151)
+    f32 = lambda v: Fraction(float(np.float32(v)))
+    for trial in range(60):
+        alpha = float(rng.uniform(0.3, 9.0))
+        fl = int(rng.integers(0, 9))
+        x = np.concatenate([wl.fp_tensor(1000 + trial, 40, std=alpha),
+                            np.float32(alpha) * (np.arange(0, 12, dtype=np.float32) + np.float32(0.5)) / np.float32(255)])
+        a = f32(alpha)
+        k_in = round_to_f32(Fraction(255) / a)
+        k_out = round_to_f32(a / 255)
+        eta = f32(2.0 ** fl * alpha / 255)                 # Eq. 5 in fp64, then one rounding to float32
+        got3 = qr.pact(x, alpha, dtype=np.float32)
+        got4 = qr.pact_as_fix_quant(x, alpha, fl, dtype=np.float32)
+        assert got3.dtype == np.float32 and got4.dtype == np.float32
+        for xi, g3, g4 in zip(x, got3, got4):
+            xf = Fraction(float(xi))
+            p3 = round_to_f32(min(max(xf, 0), a) * k_in)
+            want3 = round_to_f32(half_up(p3) * k_out)
+            assert Fraction(float(g3)) == want3, (alpha, float(xi))
+            u = round_to_f32(xf / eta)
+            v = min(max(u * 2 ** fl, 0), 255)               # power-of-two scaling and clip: exact
+            want4 = round_to_f32(half_up(v) * Fraction(1, 2 ** fl) * eta)
+            assert Fraction(float(g4)) == want4, (alpha, fl, float(xi))
+
+
 # --------------------------------------------------------------------------- Eq. 1
+
+def test_opt_fl_next_to_every_threshold():
+    """Eq. 1 is the floor of the exact logarithm.  The neighbours of every threshold c / 2^k are
+    where a floor of a rounded floating-point log2 goes wrong: at least one of these points must
+    defeat that shortcut (so the pin is live), and none may defeat the oracle."""
+    shortcut_fails = 0
+    for is_signed, c, top in ((True, 40.0, 7), (False, 70.0, 8)):
+        for k in range(-3, 12):
+            t = c / 2.0 ** k                                 # exact: c has few bits
+            for s in (np.nextafter(t, 0.0), t, np.nextafter(t, np.inf)):
+                s = float(s)
+                kk = -60
+                while Fraction(s) * Fraction(2) ** (kk + 1) <= Fraction(c):
+                    kk += 1
+                want = min(max(kk, 0), top)
+                assert qr.opt_fl(s, is_signed) == want, (s, is_signed)
+                shortcut = min(max(math.floor(math.log2(c / s)), 0), top)
+                shortcut_fails += shortcut != want
+    assert shortcut_fails > 0
+
 
 def test_opt_fl_is_the_largest_shift_that_keeps_sigma_under_the_constant():
     """floor(log2(c / sigma)) is the largest k with sigma * 2^k <= c; checked with rationals."""
