@@ -97,6 +97,23 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
                           int stride_h, int stride_w, int pad_h, int pad_w,
                           const f8_quant *q, void *stream);
 
+/* f8_conv2d_fixed for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same
+ * kernels; the only difference is where the dense kernels' scratch (256 bytes of zeros + the
+ * folded accumulator start values, 4 bytes per output channel) lives: in a fixed array inside
+ * the library's device code, (64 + F8_NOALLOC_MAX_COUT) * 4 bytes that every GPU the library
+ * runs on holds until the process ends, instead of the per-stream hipMalloc'd buffer.  The call
+ * never allocates, frees or synchronises.  Cout above F8_NOALLOC_MAX_COUT returns
+ * F8_ERR_UNSUPPORTED before anything is launched.  All calls on one GPU share that one array
+ * (each call rewrites the start values it needs; the zeros are never written): calls that may
+ * overlap on one GPU (different streams, or several host threads) race; order them on one
+ * stream. */
+#define F8_NOALLOC_MAX_COUT 4096
+f8_status f8_conv2d_fixed_noalloc(const void *x, const int8_t *w, const int32_t *bias, void *y,
+                                  int B, int H, int W, int Cin, int Cout, int R, int S,
+                                  int stride_h, int stride_w, int pad_h, int pad_w,
+                                  const f8_quant *q, void *stream);
+
 /* A second 8-bit format for the same accumulator (Sec. 4.3, "clipping-level sharing": the
  * children of one layer keep private fractional lengths, so the parent's 32-bit result is
  * quantised once per child format). */

@@ -349,6 +349,31 @@ f8_status dense_on_stream_scratch(const void *x, const int8_t *w, const int32_t 
   if (st != F8_OK) return st;
   return enqueue_conv(x, w, acc0, scratch, y, q.res, g, q, s, q2, y2);
 }
+
+// ---- scratch of the entry point that allocates nothing ----------------------------------
+// 64 ints that are never written (static storage starts as zeros: the kernels' page of zeros)
+// followed by the folded start values of one call.  Every device the library's code object is
+// loaded on holds its own copy at its own address; host code uses the per-device address from
+// hipGetSymbolAddress, never the array's name.
+constexpr int kStaticMaxCout = F8_NOALLOC_MAX_COUT;
+__device__ __align__(256) int32_t scratch[64 + kStaticMaxCout];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+int32_t *g_static_ptr[kMaxDevices] = {};
+
+// Address of this device's copy of `scratch` (looked up once per device, with that device current).
+int32_t *static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_static_ptr[dev] = static_cast<int32_t *>(ptr);
+  }
+  return g_static_ptr[dev];
+}
 }  // namespace
 
 }  // namespace f8
@@ -371,6 +396,29 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
   if (q->res == y) return F8_ERR_UNSUPPORTED;
   if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
   return dense_on_stream_scratch(x, w, bias, y, g, *q, static_cast<hipStream_t>(stream), nullptr, nullptr);
+}
+
+f8_status f8_conv2d_fixed_noalloc(const void *x, const int8_t *w, const int32_t *bias, void *y, int B, int H, int W,
+                                  int Cin, int Cout, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                                  const f8_quant *q, void *stream) {
+  if (!x || !w || !y) return F8_ERR_NULL;
+  f8_status st = check_quant(q, true);
+  if (st != F8_OK) return st;
+  Geom g{B, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  st = check_geom(g, false);
+  if (st != F8_OK) return st;
+  st = check_align(bias, y, *q, q->res);
+  if (st != F8_OK) return st;
+  if (q->res == y) return F8_ERR_UNSUPPORTED;
+  if (Cout > kStaticMaxCout || acc0_padded(Cout) > (size_t)kStaticMaxCout) return F8_ERR_UNSUPPORTED;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  int32_t *base = static_scratch();
+  if (!base) return F8_ERR_DEVICE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t *acc0 = base + 64;
+  st = enqueue_fold(w, bias, acc0, g, *q, s);
+  if (st != F8_OK) return st;
+  return enqueue_conv(x, w, acc0, base, y, q->res, g, *q, s);
 }
 
 f8_status f8_conv2d_fixed_dual(const void *x, const int8_t *w, const int32_t *bias, void *y, void *y2, int B, int H,
