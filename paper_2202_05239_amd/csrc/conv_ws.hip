@@ -22,20 +22,21 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WS_NT = 256;
 constexpr int OPITCH_PAD = 16;      // staging pitch per pixel = C + 16
-constexpr int MAXCH = 6;            // 16-byte patch pieces per thread
-constexpr int MF = 2;               // 32-pixel blocks per wave
 
 // Per channel count: how the four waves split a tile, and the tile size.
-//   C = 64:  2 waves along the pixels x 2 along the channels, 128 pixels per tile;
-//   C = 128: all 4 waves along the channels (32 each), 64 pixels per tile.
+//   C = 64:  2 waves along the pixels x 2 along the channels, four 32-pixel blocks per wave: 256 pixels per tile;
+//   C = 128: all 4 waves along the channels (32 each), two blocks per wave: 64 pixels per tile.
 template <int C> struct WsShape {
   static constexpr int WN = C / 32, WM = 4 / WN;
+  static constexpr int MF = C == 64 ? 4 : 2;    // 32-pixel blocks per wave
+  static constexpr int MAXCH = C == 64 ? 8 : 6; // 16-byte patch pieces per thread
+  static constexpr int WROWS = C == 64 ? 64 : 16;   // weight rows that pass through LDS together at set-up
   static constexpr int TILE = 32 * MF * WM;
   static constexpr int KPT = C / 32;            // K slices per tap
   static constexpr int KS = 9 * KPT;            // K slices in all
   static constexpr int PIECES = C / 16;         // 16-byte pieces per pixel
   static constexpr int KEY_SHIFT = C == 64 ? 2 : 1;   // piece ^= (column >> KEY_SHIFT) & (PIECES - 1)
-  static constexpr int AHEAD = C == 64 ? 4 : 2; // K slices the fragment reads run ahead
+  static constexpr int AHEAD = 2;               // K slices the fragment reads run ahead
   static constexpr int OPITCH = C + OPITCH_PAD;
 };
 
@@ -48,7 +49,7 @@ __device__ __forceinline__ int med3(int v, int lo, int hi) {
 template <int C>
 __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p) {
   using S = WsShape<C>;
-  constexpr int TILE = S::TILE, KS = S::KS, OPITCH = S::OPITCH;
+  constexpr int TILE = S::TILE, KS = S::KS, OPITCH = S::OPITCH, MF = S::MF, MAXCH = S::MAXCH;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   __shared__ __attribute__((aligned(16))) int32_t start[C];
   const int patch_bytes = C + p.nrows * p.pitch;            // leading zero pixel, then the rows
@@ -58,14 +59,52 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   const int wm = wave % S::WM, wn = wave / S::WM;           // 32 MF pixels x 32 channels per wave
   const int HW = p.H * p.W;
 
-  int t = blockIdx.x;
-  if (t >= p.ntiles) return;
+  // Every workgroup walks a contiguous range of tiles (the ranges differ by at most one tile), so the
+  // input rows two neighbouring tiles share are fetched twice by the same CU, a few microseconds
+  // apart: the second fetch is served by that XCD's L2 instead of HBM.
+  const int per = p.ntiles / (int)gridDim.x, rem = p.ntiles % (int)gridDim.x;
+  int t = (int)blockIdx.x * per + min((int)blockIdx.x, rem);
+  const int t_end = t + per + ((int)blockIdx.x < rem ? 1 : 0);
+  if (t >= t_end) return;
 
-  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C
+  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C.  They reach
+  // the registers through LDS (the patch buffers are not in use yet), all 64 channels at once or 16 of 128 at a time: the
+  // global loads are then contiguous (a lane reading its own fragments straight from memory would
+  // touch a different cache line than every other lane, 9 C bytes apart, while every workgroup of the
+  // launch asks for the same lines at the same moment).  Rows sit 9 C + 16 bytes apart in LDS, which
+  // spreads the 16 rows a fragment read touches over all banks.
   v4i fa[KS];
+  {
+    constexpr int ROWB = 9 * C, WPITCH = ROWB + 16, PPR = ROWB / 16;     // bytes, pieces per row
+    constexpr int RPC = S::WROWS;                                        // weight rows per pass
+    constexpr int CHUNK_PIECES = RPC * PPR, PPT = (CHUNK_PIECES + WS_NT - 1) / WS_NT;
+    v4i wbuf[PPT];
+    auto fetch_rows = [&](int j) {
 #pragma unroll
-  for (int sl = 0; sl < KS; ++sl)
-    fa[sl] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * wn + l32) * (9 * C) + 32 * sl + 16 * half);
+      for (int k = 0; k < PPT; ++k) {
+        const int i = tid + k * WS_NT;
+        if (i < CHUNK_PIECES) wbuf[k] = *reinterpret_cast<const v4i *>(p.w + (size_t)j * (RPC * ROWB) + (size_t)i * 16);
+      }
+    };
+    fetch_rows(0);
+#pragma unroll 1
+    for (int j = 0; j < C / RPC; ++j) {
+#pragma unroll
+      for (int k = 0; k < PPT; ++k) {
+        const int i = tid + k * WS_NT, row = i / PPR, col = i - row * PPR;
+        if (i < CHUNK_PIECES) *reinterpret_cast<v4i *>(lds + row * WPITCH + 16 * col) = wbuf[k];
+      }
+      if (j + 1 < C / RPC) fetch_rows(j + 1);
+      __syncthreads();
+      const int r = 32 * wn + l32;                          // this lane's channel
+      if (r / RPC == j) {
+#pragma unroll
+        for (int sl = 0; sl < KS; ++sl)
+          fa[sl] = *reinterpret_cast<const v4i *>(lds + (r % RPC) * WPITCH + 32 * sl + 16 * half);
+      }
+      __syncthreads();
+    }
+  }
   if (tid < C) start[tid] = p.acc0[tid];
   // Both patch buffers start as the value zero in the form the matrix instruction sees it (unsigned
   // activations are stored xor 0x80, which makes them signed); only the pixels between the border
@@ -127,11 +166,11 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   __syncthreads();                     // the fill is complete
   store_patch(0, nextbuf);
   int which = 0;
-  if (t + (int)gridDim.x < p.ntiles) fetch_patch(t + gridDim.x, nextbuf);
+  if (t + 1 < t_end) fetch_patch(t + 1, nextbuf);
   __syncthreads();
 
-  for (; t < p.ntiles; t += gridDim.x) {
-    const int tn = t + gridDim.x;
+  for (; t < t_end; ++t) {
+    const int tn = t + 1;
     int b, m0, row0;
     tile_coords(t, b, m0, row0);
 
@@ -196,8 +235,8 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
         *reinterpret_cast<uint32_t *>(stage + ((32 * MF) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 8 * g + 4 * half) =
             pack4(v[0], v[1], v[2], v[3]);
       }
-    if (tn < p.ntiles) store_patch(which ^ 1, nextbuf);
-    if (tn + (int)gridDim.x < p.ntiles) fetch_patch(tn + gridDim.x, nextbuf);      // lands during the next tile
+    if (tn < t_end) store_patch(which ^ 1, nextbuf);
+    if (tn + 1 < t_end) fetch_patch(tn + 1, nextbuf);      // lands during the next tile
     __syncthreads();
 
     // TILE pixels x C bytes, contiguous in the output: 16 bytes per store
@@ -215,12 +254,14 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
 
 constexpr size_t WS_LDS_MAX = 80 * 1024 - 1024;
 
-template <int C> int ws_nrows(int W) { return (W - 1 + WsShape<C>::TILE - 1) / W + 1 + 2; }
+template <int C> int ws_nrows(int W) { return (W - 1 + WsShape<C>::TILE - 1) / W + 1 + 2; }     // rows a tile can touch, plus one above and below
 template <int C> size_t ws_lds_bytes(int W) {
-  return 2 * (size_t)(C + ws_nrows<C>(W) * (W + 1) * C) + (size_t)WsShape<C>::TILE * WsShape<C>::OPITCH;
+  const size_t tiles = 2 * (size_t)(C + ws_nrows<C>(W) * (W + 1) * C) + (size_t)WsShape<C>::TILE * WsShape<C>::OPITCH;
+  const size_t weights = WsShape<C>::WROWS * (size_t)(9 * C + 16);      // weight rows pass through LDS at set-up
+  return tiles > weights ? tiles : weights;
 }
 template <int C> bool ws_fits(int W) {
-  return W >= 8 && W <= 64 && ws_nrows<C>(W) * W * (C / 16) <= MAXCH * WS_NT && ws_lds_bytes<C>(W) <= WS_LDS_MAX;
+  return W >= 8 && W <= 64 && ws_nrows<C>(W) * W * (C / 16) <= WsShape<C>::MAXCH * WS_NT && ws_lds_bytes<C>(W) <= WS_LDS_MAX;
 }
 
 template <int C>

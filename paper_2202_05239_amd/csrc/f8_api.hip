@@ -96,9 +96,9 @@ static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const voi
                         const f8_quant &q, const void *y2) {
   if (!tuning().conv_ws.load(std::memory_order_relaxed) || res || y2 || q.y_type == F8_S32) return false;
   // it pays once a workgroup walks over several tiles (measured: level with the general kernel at
-  // 800 and 1600 tiles of 128 pixels, 15-20 % ahead at 6400)
-  const int tile = conv_ws_tile_pixels(g.Cin);
-  if ((long long)g.B * ((g.H * g.W + tile - 1) / tile) < 2048) return false;
+  // 800 and 1600 blocks of 128 pixels per image set, 15-20 % ahead at 6400)
+  const int granule = g.Cin == 64 ? 128 : 64;       // pixels
+  if ((long long)g.B * ((g.H * g.W + granule - 1) / granule) < 2048) return false;
   return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
