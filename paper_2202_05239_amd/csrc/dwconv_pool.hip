@@ -80,8 +80,10 @@ __global__ __launch_bounds__(NT) void dwconv_generic_kernel(const DwParams p, co
 // zero weight).  Unsigned activations are fed as x xor 0x80 with 128 * sum(w) added to the
 // start value, as in the dense kernels; padding is zero before the xor.
 struct DwTiling {
-  FastDiv fd_cg, fd_qs, fd_pc;
-  int CG, QS, PC;            // channel dwords, column strips, row chunks
+  FastDiv fd_cg, fd_pc, fd_wpc;
+  int CG, QS, PC, WPC;       // channel dwords, column strips, row chunks, workgroups per (image, chunk)
+  uint32_t x_bytes, y_bytes; // sizes of the two tensors (each below 1 GiB)
+  int lo_scaled, hi_scaled;  // clip bounds at the accumulator's scale: lo << shift, ((hi + 1) << shift) - 1
 };
 
 constexpr int DW_TQ = 4, DW_TP = 8;
@@ -107,6 +109,15 @@ __device__ __forceinline__ int med3(int v, int lo, int hi) {
   return r;
 }
 
+// The same clamp for a value that a packed dot product has just written: a different kind of vector
+// instruction may read such a result only three wait states later, and the compiler, which inserts
+// those waits for its own instructions, cannot see into an asm statement.
+__device__ __forceinline__ int med3_after_dot(int v, int lo, int hi) {
+  int r;
+  asm("s_nop 2\n\tv_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+  return r;
+}
+
 // d = dot4(a, b) + c with a destination of its own (the builtin's accumulate-in-place form
 // needs a copy of the start value first)
 __device__ __forceinline__ int dot4_from(uint32_t a, uint32_t b, int c) {
@@ -117,8 +128,26 @@ __device__ __forceinline__ int dot4_from(uint32_t a, uint32_t b, int c) {
 
 constexpr int DW_NT = 64;        // one wave per workgroup: small layers still spread over all CUs
 
+// acc >> shift written into byte BYTE of dst, the other bytes kept: the arithmetic shift and the
+// packing of four results into one dword are one instruction (sub-dword addressing of the
+// destination).  acc has been clamped to [lo << shift, ((hi + 1) << shift) - 1] before, so the
+// shifted value is the clipped output and its low byte is all of it.  A vector instruction that
+// reads a register right after a sub-dword write to it needs one wait state on this chip; the
+// compiler cannot see into the asm statement, so the wait is part of it.  Byte 0 goes first and
+// clears the rest of dst; the shift count is uniform (a scalar register).
+template <int BYTE>
+__device__ __forceinline__ void shift_into_byte(uint32_t &dst, int acc, int shift) {
+  if (BYTE == 0) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0" : "=v"(dst) : "s"(shift), "v"(acc));
+  if (BYTE == 1) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0" : "+v"(dst) : "s"(shift), "v"(acc));
+  if (BYTE == 2) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0" : "+v"(dst) : "s"(shift), "v"(acc));
+  if (BYTE == 3) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0" : "+v"(dst) : "s"(shift), "v"(acc));
+}
+
+// One wave per workgroup.  A workgroup belongs to one image and one chunk of TP output rows, so
+// everything that depends on the row is uniform and lives on the scalar unit; its lanes are 64
+// consecutive (column strip, channel dword) pairs of that chunk.
 template <int STRIDE, bool XS>
-__global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl, const uint32_t total) {
+__global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl) {
   constexpr int TQ = DW_TQ, TP = DW_TP;
   constexpr int NCOL = (TQ - 1) * STRIDE + 3;
   constexpr int NROW = (TP - 1) * STRIDE + 3;
@@ -127,28 +156,29 @@ __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, cons
   // Stride 2: four (columns 0.., 2.., 4.., 6..).
   constexpr int NWIN = STRIDE == 1 ? 2 : 4;
   // neighbouring row chunks share input rows: keep them on one XCD (one L2)
-  const uint32_t gid = xcd_remap(blockIdx.x, gridDim.x) * DW_NT + threadIdx.x;
-  if (gid >= total) return;
-  const uint32_t u1 = tl.fd_cg.div(gid);
-  const int cg = (int)(gid - u1 * (uint32_t)tl.CG);
-  const uint32_t u2 = tl.fd_qs.div(u1);
-  const int strip = (int)(u1 - u2 * (uint32_t)tl.QS);
-  const uint32_t b = tl.fd_pc.div(u2);
-  const int chunk = (int)(u2 - b * (uint32_t)tl.PC);
-  const int c = cg * 4;
-  const int q0 = strip * TQ, p0 = chunk * TP;
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const uint32_t u1 = tl.fd_wpc.div(wg);                  // (image, chunk)
+  const uint32_t part = wg - u1 * (uint32_t)tl.WPC;        // which 64 of the chunk's lanes
+  const uint32_t b = tl.fd_pc.div(u1);
+  const int chunk = (int)(u1 - b * (uint32_t)tl.PC);
+  const uint32_t task = part * DW_NT + threadIdx.x;        // (strip, channel dword) of this lane
+  const bool live = task < (uint32_t)(tl.QS * tl.CG);
+  const uint32_t strip = tl.fd_cg.div(task);
+  const int c = (int)(task - strip * (uint32_t)tl.CG) * 4;
+  const int q0 = (int)strip * TQ, p0 = chunk * TP;
   const int iw0 = q0 * STRIDE - p.pw, ih0 = p0 * STRIDE - p.ph;
+  const int cw = live ? c : 0;                              // idle lanes of the last part read channel 0's weights
 
   // weights: wt[r][ch][0] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0), [1] = the same one byte up
   uint32_t wt[3][4][STRIDE == 1 ? 2 : 1];
   int acc0[4];
 #pragma unroll
-  for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[c + ch] : 0);
+  for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[cw + ch] : 0);
 #pragma unroll
   for (int r = 0; r < 3; ++r) {
-    const uint32_t w0 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 0) * p.C + c);
-    const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + c);
-    const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + c);
+    const uint32_t w0 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 0) * p.C + cw);
+    const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + cw);
+    const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + cw);
     const uint32_t lo = perm(w1, w0, 0x05010400u), hi = perm(w1, w0, 0x07030602u);
     wt[r][0][0] = perm(w2, lo, 0x0c040100u);
     wt[r][1][0] = perm(w2, lo, 0x0c050302u);
@@ -161,33 +191,40 @@ __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, cons
     }
   }
 
-  // which of this strip's input columns lie inside the image
-  uint32_t col_ok = 0;
+  // Loads and stores go through buffer descriptors of the two tensors (both below 1 GiB, checked by
+  // the launcher).  The hardware compares the per-lane offset with the descriptor's size: at or beyond
+  // it a load returns zero and a store is dropped.  The per-lane part of an address is column and
+  // channel, with bit 31 set for a column outside the image, an output column past the row's end or
+  // an idle lane; the uniform part (image and row) is a scalar offset, which that comparison does not
+  // include, so a row outside the image takes a descriptor of size zero instead.  Neither loads nor
+  // stores need a branch, a select or a per-lane add.
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.x), 0, (int)tl.x_bytes, 0x00027000);
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(static_cast<uint8_t *>(p.y), 0, (int)tl.y_bytes, 0x00027000);
+  const __amdgpu_buffer_rsrc_t xnone = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.x), 0, 0, 0x00027000);
+  const __amdgpu_buffer_rsrc_t ynone = __builtin_amdgcn_make_buffer_rsrc(static_cast<uint8_t *>(p.y), 0, 0, 0x00027000);
+  uint32_t col_off[NCOL];
 #pragma unroll
-  for (int j = 0; j < NCOL; ++j) col_ok |= ((unsigned)(iw0 + j) < (unsigned)p.W ? 1u : 0u) << j;
-  // 32-bit byte offsets from p.x (the tensor is below 2 GiB); may wrap for taps outside the
-  // image, which are never dereferenced
-  const uint32_t row_bytes = (uint32_t)(p.W * p.C);
-  const uint32_t xcol = ((b * (uint32_t)p.H + (uint32_t)ih0) * (uint32_t)p.W + (uint32_t)iw0) * (uint32_t)p.C + (uint32_t)c;
-  uint8_t *ycol = static_cast<uint8_t *>(p.y) + ((size_t)b * p.P * p.Q + q0) * p.C + c;
+  for (int j = 0; j < NCOL; ++j)
+    col_off[j] = live && (unsigned)(iw0 + j) < (unsigned)p.W ? (uint32_t)((iw0 + j) * p.C + c) : 0x80000000u;
+  uint32_t out_off[TQ];
+#pragma unroll
+  for (int q = 0; q < TQ; ++q) out_off[q] = live && q0 + q < p.Q ? (uint32_t)((q0 + q) * p.C + c) : 0x80000000u;
+  const uint32_t row_bytes = (uint32_t)(p.W * p.C), orow_bytes = (uint32_t)(p.Q * p.C);
+  const uint32_t ximg = b * (uint32_t)p.H * row_bytes, yimg = b * (uint32_t)p.P * orow_bytes;     // uniform
 
   uint32_t win[3][4][NWIN];     // [input row mod 3][channel][window]
-  // Loads are branch-free (an out-of-image tap reads the tensor's first dword and is then
-  // replaced by zero) and run PF input rows ahead of the arithmetic, so every wave keeps
-  // 2 * NCOL dwords per lane in flight.
+  // Loads run PF input rows ahead of the arithmetic, so every wave keeps 2 * NCOL dwords per lane
+  // in flight.
   constexpr int PF = 2;
   uint32_t ring[PF + 1][NCOL];
   auto load_row = [&](int i, uint32_t (&dst)[NCOL]) {
-    const bool row_ok = (unsigned)(ih0 + i) < (unsigned)p.H;
-    const uint32_t xrow = xcol + (uint32_t)i * row_bytes;
+    const bool row_ok = (unsigned)(ih0 + i) < (unsigned)p.H;                             // uniform
+    const uint32_t xrow = row_ok ? ximg + (uint32_t)(ih0 + i) * row_bytes : 0u;
+    const __amdgpu_buffer_rsrc_t r = row_ok ? xres : xnone;
 #pragma unroll
-    for (int j = 0; j < NCOL; ++j) {
-      const bool ok = row_ok && ((col_ok >> j) & 1u);
-      const uint32_t off = ok ? xrow + (uint32_t)(j * p.C) : 0u;
-      const uint32_t v = *reinterpret_cast<const uint32_t *>(p.x + (size_t)off);
-      dst[j] = ok ? v : 0u;
-    }
+    for (int j = 0; j < NCOL; ++j) dst[j] = __builtin_amdgcn_raw_buffer_load_b32(r, col_off[j], xrow, 0);
   };
+  const int sh = p.shift, lo_s = tl.lo_scaled, hi_s = tl.hi_scaled;
 #pragma unroll
   for (int i = 0; i < PF; ++i) load_row(i, ring[i]);
 #pragma unroll
@@ -221,27 +258,24 @@ __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, cons
     if (i >= 2 && (i - 2) % STRIDE == 0) {
       const int pl = (i - 2) / STRIDE;
       const int pp = p0 + pl;
-      int acc[4][4];
+      const uint32_t yrow = pp < p.P ? yimg + (uint32_t)pp * orow_bytes : 0u;                // uniform
+      const __amdgpu_buffer_rsrc_t yr = pp < p.P ? yres : ynone;
 #pragma unroll
-      for (int ch = 0; ch < 4; ++ch)
+      for (int q = 0; q < 4; ++q) {
+        const int wi = STRIDE == 1 ? q >> 1 : q, wv = STRIDE == 1 ? q & 1 : 0;
+        uint32_t out;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int wi = STRIDE == 1 ? q >> 1 : q, wv = STRIDE == 1 ? q & 1 : 0;
+        for (int ch = 0; ch < 4; ++ch) {
           int a = dot4_from(win[(pl * STRIDE + 0) % 3][ch][wi], wt[0][ch][wv], acc0[ch]);
           a = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + 1) % 3][ch][wi], (int)wt[1][ch][wv], a, false);
-          acc[q][ch] = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + 2) % 3][ch][wi], (int)wt[2][ch][wv], a, false);
+          a = __builtin_amdgcn_sdot4((int)win[(pl * STRIDE + 2) % 3][ch][wi], (int)wt[2][ch][wv], a, false);
+          a = med3_after_dot(a, lo_s, hi_s);
+          if (ch == 0) shift_into_byte<0>(out, a, sh);
+          if (ch == 1) shift_into_byte<1>(out, a, sh);
+          if (ch == 2) shift_into_byte<2>(out, a, sh);
+          if (ch == 3) shift_into_byte<3>(out, a, sh);
         }
-      if (pp < p.P) {
-        uint8_t *yrow = ycol + (size_t)pp * p.Q * p.C;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (q0 + q < p.Q) {
-            int v[4];
-#pragma unroll
-            for (int ch = 0; ch < 4; ++ch) v[ch] = med3(acc[q][ch] >> p.shift, p.lo, p.hi);
-            *reinterpret_cast<uint32_t *>(yrow + (size_t)q * p.C) = pack4(v[0], v[1], v[2], v[3]);
-          }
-        }
+        __builtin_amdgcn_raw_buffer_store_b32(out, yr, out_off[q], yrow, 0);
       }
     }
   }
@@ -506,8 +540,13 @@ bool dwconv_fast_applicable(const DwParams &p, bool vec4) {
   if (!vec4 || p.R != 3 || p.S != 3 || p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
   if (p.res || p.y_type == T_S32 || p.shift < 0) return false;
   if (p.bias && (reinterpret_cast<uintptr_t>(p.bias) & 3)) return false;
-  const long long threads = (long long)p.B * ((p.P + DW_TP - 1) / DW_TP) * ((p.Q + DW_TQ - 1) / DW_TQ) * (p.C / 4);
-  return threads > 0 && threads < (1ll << 31);
+  // the kernel addresses both tensors through 32-bit offsets with two bits to spare
+  if ((long long)p.B * p.H * p.W * p.C >= (1ll << 30) || (long long)p.B * p.P * p.Q * p.C >= (1ll << 30)) return false;
+  // the clip bounds are applied at the accumulator's scale: they must fit 32 bits there
+  if ((((long long)p.hi + 1) << p.shift) - 1 > 0x7fffffffLL || ((long long)p.lo << p.shift) < -0x80000000LL) return false;
+  const long long groups = (long long)p.B * ((p.P + DW_TP - 1) / DW_TP) *
+                           ((((p.Q + DW_TQ - 1) / DW_TQ) * (long long)(p.C / 4) + DW_NT - 1) / DW_NT);
+  return groups > 0 && groups < (1ll << 31);
 }
 
 int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
@@ -518,18 +557,22 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
     tl.CG = p.C / 4;
     tl.QS = (p.Q + DW_TQ - 1) / DW_TQ;
     tl.PC = (p.P + DW_TP - 1) / DW_TP;
+    tl.WPC = (tl.QS * tl.CG + DW_NT - 1) / DW_NT;
     tl.fd_cg = FastDiv((uint32_t)tl.CG);
-    tl.fd_qs = FastDiv((uint32_t)tl.QS);
     tl.fd_pc = FastDiv((uint32_t)tl.PC);
-    const uint32_t threads = (uint32_t)((long long)p.B * tl.PC * tl.QS * tl.CG);
-    const dim3 grid((threads + DW_NT - 1) / DW_NT), block(DW_NT);
+    tl.fd_wpc = FastDiv((uint32_t)tl.WPC);
+    tl.x_bytes = (uint32_t)((long long)p.B * p.H * p.W * p.C);
+    tl.y_bytes = (uint32_t)((long long)p.B * p.P * p.Q * p.C);
+    tl.lo_scaled = (int)((long long)p.lo << p.shift);
+    tl.hi_scaled = (int)((((long long)p.hi + 1) << p.shift) - 1);
+    const dim3 grid((unsigned)((long long)p.B * tl.PC * tl.WPC)), block(DW_NT);
     const bool xs = p.x_type == T_S8;
     if (p.sh == 1) {
-      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<1, true>), grid, block, 0, stream, p, tl, threads);
-      else hipLaunchKernelGGL((dwconv3x3_kernel<1, false>), grid, block, 0, stream, p, tl, threads);
+      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<1, true>), grid, block, 0, stream, p, tl);
+      else hipLaunchKernelGGL((dwconv3x3_kernel<1, false>), grid, block, 0, stream, p, tl);
     } else {
-      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<2, true>), grid, block, 0, stream, p, tl, threads);
-      else hipLaunchKernelGGL((dwconv3x3_kernel<2, false>), grid, block, 0, stream, p, tl, threads);
+      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<2, true>), grid, block, 0, stream, p, tl);
+      else hipLaunchKernelGGL((dwconv3x3_kernel<2, false>), grid, block, 0, stream, p, tl);
     }
     return (int)hipGetLastError();
   }
