@@ -1,6 +1,8 @@
 // Depthwise fixed-point convolution and the two pooling layers for gfx950.
 // These are bandwidth-bound: no matrix cores, NHWC with consecutive lanes on consecutive
 // channels so that every wave access is a run of contiguous bytes.
+#include <type_traits>
+
 #include "dwconv_pool.h"
 
 namespace f8 {
@@ -86,7 +88,7 @@ struct DwTiling {
   int lo_scaled, hi_scaled;  // clip bounds at the accumulator's scale: lo << shift, ((hi + 1) << shift) - 1
 };
 
-constexpr int DW_TQ = 4, DW_TP = 8;
+constexpr int DW_TQ = 4, DW_TP = 8;      // output columns per lane; most output rows per wave
 
 __device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) {
   return __builtin_amdgcn_perm(hi, lo, sel);
@@ -146,9 +148,9 @@ __device__ __forceinline__ void shift_into_byte(uint32_t &dst, int acc, int shif
 // One wave per workgroup.  A workgroup belongs to one image and one chunk of TP output rows, so
 // everything that depends on the row is uniform and lives on the scalar unit; its lanes are 64
 // consecutive (column strip, channel dword) pairs of that chunk.
-template <int STRIDE, bool XS>
+template <int STRIDE, bool XS, int TP>
 __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, const DwTiling tl) {
-  constexpr int TQ = DW_TQ, TP = DW_TP;
+  constexpr int TQ = DW_TQ;
   constexpr int NCOL = (TQ - 1) * STRIDE + 3;
   constexpr int NROW = (TP - 1) * STRIDE + 3;
   // Window dwords kept per input row and channel.  Stride 1: two (columns 0..3 and 2..5), each
@@ -168,28 +170,6 @@ __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, cons
   const int q0 = (int)strip * TQ, p0 = chunk * TP;
   const int iw0 = q0 * STRIDE - p.pw, ih0 = p0 * STRIDE - p.ph;
   const int cw = live ? c : 0;                              // idle lanes of the last part read channel 0's weights
-
-  // weights: wt[r][ch][0] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0), [1] = the same one byte up
-  uint32_t wt[3][4][STRIDE == 1 ? 2 : 1];
-  int acc0[4];
-#pragma unroll
-  for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[cw + ch] : 0);
-#pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    const uint32_t w0 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 0) * p.C + cw);
-    const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + cw);
-    const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + cw);
-    const uint32_t lo = perm(w1, w0, 0x05010400u), hi = perm(w1, w0, 0x07030602u);
-    wt[r][0][0] = perm(w2, lo, 0x0c040100u);
-    wt[r][1][0] = perm(w2, lo, 0x0c050302u);
-    wt[r][2][0] = perm(w2, hi, 0x0c060100u);
-    wt[r][3][0] = perm(w2, hi, 0x0c070302u);
-#pragma unroll
-    for (int ch = 0; ch < 4; ++ch) {
-      if (!XS) acc0[ch] += 128 * __builtin_amdgcn_sdot4((int)wt[r][ch][0], 0x01010101, 0, false);
-      if (STRIDE == 1) wt[r][ch][1] = wt[r][ch][0] << 8;
-    }
-  }
 
   // Loads and stores go through buffer descriptors of the two tensors (both below 1 GiB, checked by
   // the launcher).  The hardware compares the per-lane offset with the descriptor's size: at or beyond
@@ -224,9 +204,33 @@ __global__ __launch_bounds__(DW_NT) void dwconv3x3_kernel(const DwParams p, cons
 #pragma unroll
     for (int j = 0; j < NCOL; ++j) dst[j] = __builtin_amdgcn_raw_buffer_load_b32(r, col_off[j], xrow, 0);
   };
-  const int sh = p.shift, lo_s = tl.lo_scaled, hi_s = tl.hi_scaled;
+  // the first input rows are requested before the weights are fetched and unpacked
 #pragma unroll
   for (int i = 0; i < PF; ++i) load_row(i, ring[i]);
+
+  // weights: wt[r][ch][0] = bytes (w[r][0][ch], w[r][1][ch], w[r][2][ch], 0), [1] = the same one byte up
+  uint32_t wt[3][4][STRIDE == 1 ? 2 : 1];
+  int acc0[4];
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) acc0[ch] = p.rnd + (p.bias ? p.bias[cw + ch] : 0);
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    const uint32_t w0 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 0) * p.C + cw);
+    const uint32_t w1 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 1) * p.C + cw);
+    const uint32_t w2 = *reinterpret_cast<const uint32_t *>(p.w + (size_t)(3 * r + 2) * p.C + cw);
+    const uint32_t lo = perm(w1, w0, 0x05010400u), hi = perm(w1, w0, 0x07030602u);
+    wt[r][0][0] = perm(w2, lo, 0x0c040100u);
+    wt[r][1][0] = perm(w2, lo, 0x0c050302u);
+    wt[r][2][0] = perm(w2, hi, 0x0c060100u);
+    wt[r][3][0] = perm(w2, hi, 0x0c070302u);
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) {
+      if (!XS) acc0[ch] += 128 * __builtin_amdgcn_sdot4((int)wt[r][ch][0], 0x01010101, 0, false);
+      if (STRIDE == 1) wt[r][ch][1] = wt[r][ch][0] << 8;
+    }
+  }
+
+  const int sh = p.shift, lo_s = tl.lo_scaled, hi_s = tl.hi_scaled;
 #pragma unroll
   for (int i = 0; i < NROW; ++i) {
     if (i + PF < NROW) load_row(i + PF, ring[(i + PF) % (PF + 1)]);
@@ -544,7 +548,7 @@ bool dwconv_fast_applicable(const DwParams &p, bool vec4) {
   if ((long long)p.B * p.H * p.W * p.C >= (1ll << 30) || (long long)p.B * p.P * p.Q * p.C >= (1ll << 30)) return false;
   // the clip bounds are applied at the accumulator's scale: they must fit 32 bits there
   if ((((long long)p.hi + 1) << p.shift) - 1 > 0x7fffffffLL || ((long long)p.lo << p.shift) < -0x80000000LL) return false;
-  const long long groups = (long long)p.B * ((p.P + DW_TP - 1) / DW_TP) *
+  const long long groups = (long long)p.B * ((p.P + 5) / 6) *
                            ((((p.Q + DW_TQ - 1) / DW_TQ) * (long long)(p.C / 4) + DW_NT - 1) / DW_NT);
   return groups > 0 && groups < (1ll << 31);
 }
@@ -556,8 +560,21 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
     DwTiling tl;
     tl.CG = p.C / 4;
     tl.QS = (p.Q + DW_TQ - 1) / DW_TQ;
-    tl.PC = (p.P + DW_TP - 1) / DW_TP;
     tl.WPC = (tl.QS * tl.CG + DW_NT - 1) / DW_NT;
+    // Output rows per wave: 8, or 7 or 6 when that spreads the waves more evenly over the chip's
+    // 1024 SIMDs (all waves of such a layer are resident at once, so the SIMD with the most waves
+    // sets the time) by more than the extra input rows cost ((TP + 2) / TP rows loaded per row written).
+    int tp = DW_TP;
+    {
+      double best = 1e30;
+      for (int cand = DW_TP; cand >= 6; --cand) {
+        const double waves = (double)p.B * ((p.P + cand - 1) / cand) * tl.WPC;
+        const double rounds = waves > 16384.0 ? waves / 1024.0 : (double)(((long long)waves + 1023) / 1024);
+        const double cost = rounds * ((cand - 1) * p.sh + 3);  // input rows a SIMD walks through
+        if (cost < best * 0.97) { best = cost; tp = cand; }
+      }
+    }
+    tl.PC = (p.P + tp - 1) / tp;
     tl.fd_cg = FastDiv((uint32_t)tl.CG);
     tl.fd_pc = FastDiv((uint32_t)tl.PC);
     tl.fd_wpc = FastDiv((uint32_t)tl.WPC);
@@ -567,12 +584,20 @@ int launch_dwconv(const DwParams &p, bool vec4, hipStream_t stream) {
     tl.hi_scaled = (int)((((long long)p.hi + 1) << p.shift) - 1);
     const dim3 grid((unsigned)((long long)p.B * tl.PC * tl.WPC)), block(DW_NT);
     const bool xs = p.x_type == T_S8;
+    auto go = [&](auto stride_tag, auto xs_tag) {
+      constexpr int ST = decltype(stride_tag)::value;
+      constexpr bool XSV = decltype(xs_tag)::value;
+      if (tp == 8) hipLaunchKernelGGL((dwconv3x3_kernel<ST, XSV, 8>), grid, block, 0, stream, p, tl);
+      else if (tp == 7) hipLaunchKernelGGL((dwconv3x3_kernel<ST, XSV, 7>), grid, block, 0, stream, p, tl);
+      else hipLaunchKernelGGL((dwconv3x3_kernel<ST, XSV, 6>), grid, block, 0, stream, p, tl);
+    };
+    using std::integral_constant;
     if (p.sh == 1) {
-      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<1, true>), grid, block, 0, stream, p, tl);
-      else hipLaunchKernelGGL((dwconv3x3_kernel<1, false>), grid, block, 0, stream, p, tl);
+      if (xs) go(integral_constant<int, 1>{}, integral_constant<bool, true>{});
+      else go(integral_constant<int, 1>{}, integral_constant<bool, false>{});
     } else {
-      if (xs) hipLaunchKernelGGL((dwconv3x3_kernel<2, true>), grid, block, 0, stream, p, tl);
-      else hipLaunchKernelGGL((dwconv3x3_kernel<2, false>), grid, block, 0, stream, p, tl);
+      if (xs) go(integral_constant<int, 2>{}, integral_constant<bool, true>{});
+      else go(integral_constant<int, 2>{}, integral_constant<bool, false>{});
     }
     return (int)hipGetLastError();
   }
