@@ -333,7 +333,8 @@ f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream);
 f8_status f8_mfma_i8_yardstick(int32_t *sink, int iters, double *ops, void *stream);
 /* Tuning switches: kernel choices only, never results (the parity tests force every tile variant
  * through them).  Names and defaults: "conv_variant" (-1 = automatic; >= 0 forces that tile
- * variant of the LDS-direct dense kernel), "conv_ws", "pw_ws", "pw_small", "xcd_remap",
+ * variant of the LDS-direct dense kernel), "conv_ws", "conv_ws_min" (768: smallest layer, in blocks
+ * of 128 pixels, that takes the weights-stationary 3x3 kernel), "pw_ws", "pw_small", "xcd_remap",
  * "stem_pool", "conv_tail" (1 = on).  The environment variables F8_<NAME IN CAPITALS> give the
  * initial values; they are read once, when the library first looks at a switch, never on the
  * launch path.  f8_tuning_set returns 0, or -1 for an unknown name; the two chain switches are

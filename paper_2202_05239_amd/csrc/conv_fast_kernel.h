@@ -106,7 +106,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   for (int i = 0; i < XR; ++i) {
     const int m = m0 + lrow + i * RPG;
     x_mask[i] = 0;
-    if (m < p.M) {
+    if (m < p.M && p.gemm) {
+      // 1x1, stride 1, no padding: output pixel m reads input pixel m, its one tap is always inside
+      x_ih0[i] = 0;
+      x_iw0[i] = 0;
+      x_off[i] = m * p.C;
+      if (UT) {
+        x_mask[i] = 1u;
+        x_off[i] += (int)p.x_delta + cl * 16;
+      }
+    } else if (m < p.M) {
       const uint32_t b = p.fd_pq.div((uint32_t)m);
       const uint32_t rem = (uint32_t)m - b * p.fd_pq.d;
       const uint32_t pp = p.fd_q.div(rem);
@@ -271,16 +280,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   constexpr int RCH = BM * CPR / NT;              // pieces per thread
   constexpr bool RES_PREFETCH = EV == 16 && RCH <= 4 && (BM * CPR) % NT == 0;
   v4i res_pre[RES_PREFETCH ? RCH : 1];
+  // Residual reads and output stores go through buffer descriptors of exactly the tensors' size
+  // (below 2 GiB): a piece of a row past the last pixel has an offset beyond that size, and a piece
+  // past the last channel gets bit 31 set, so the hardware returns zeros for such loads and drops
+  // such stores: no compares, no branches, 32-bit offsets that advance by a constant per piece.
+  const uint32_t out_bytes = (uint32_t)p.M * (uint32_t)p.N;
+  constexpr int ROWS_PER_PASS = NT / CPR;          // tile rows covered by one piece per thread
+  static_assert(NT % CPR == 0, "a thread keeps its column of pieces");
+  const uint32_t piece_off = (uint32_t)(n0 + (tid % CPR) * EV) < (uint32_t)p.N
+                                 ? (uint32_t)(m0 + tid / CPR) * (uint32_t)p.N + (uint32_t)(n0 + (tid % CPR) * EV)
+                                 : 0x80000000u;
+  const uint32_t pass_step = (uint32_t)(ROWS_PER_PASS * p.N);
   if (RES_PREFETCH && p.res) {
-    const uint8_t *res = static_cast<const uint8_t *>(p.res);
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.res), 0, (int)out_bytes, 0x00027000);
 #pragma unroll
-    for (int i = 0; i < RCH; ++i) {
-      const int idx = tid + i * NT;
-      const int row = idx / CPR, pc = idx - row * CPR;
-      const int m = m0 + row, n = n0 + pc * 16;
-      res_pre[i] = v4i{0, 0, 0, 0};
-      if (m < p.M && n < p.N) res_pre[i] = *reinterpret_cast<const v4i *>(res + (size_t)m * p.N + n);
-    }
+    for (int i = 0; i < RCH; ++i) res_pre[i] = __builtin_amdgcn_raw_buffer_load_b128(rres, piece_off + i * pass_step, 0, 0);
   }
 
   __builtin_amdgcn_sched_barrier(0);
@@ -388,6 +402,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   }
   wait_vm<0>();
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
+  wait_matrix_results();
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[nb][mb][4g+j] is channel n0+wn0+nb*32+8g+4*half+j of pixel m0+wm0+mb*32+l32.
@@ -420,16 +435,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
         *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) = res_pre[i];
       }
     } else {
-      const uint8_t *res = static_cast<const uint8_t *>(p.res);
-      for (int idx = tid; idx < BM * CPR; idx += NT) {
-        const int row = idx / CPR, pc = idx - row * CPR;
-        const int m = m0 + row, n = n0 + pc * EV;
-        if (m < p.M && n < p.N) {
-          if (EV == 16) *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) =
-              *reinterpret_cast<const v4i *>(res + (size_t)m * p.N + n);
-          else *reinterpret_cast<uint32_t *>(epi + row * PITCH + pc * 4) =
-              *reinterpret_cast<const uint32_t *>(res + (size_t)m * p.N + n);
-        }
+      const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.res), 0, (int)out_bytes, 0x00027000);
+#pragma unroll 4
+      for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+        const int row = tid / CPR + i * ROWS_PER_PASS, pc = tid % CPR;
+        if (EV == 16) *reinterpret_cast<v4i *>(epi + row * PITCH + pc * 16) =
+            __builtin_amdgcn_raw_buffer_load_b128(rres, piece_off + i * pass_step, 0, 0);
+        else *reinterpret_cast<uint32_t *>(epi + row * PITCH + pc * 4) =
+            __builtin_amdgcn_raw_buffer_load_b32(rres, piece_off + i * pass_step, 0, 0);
       }
     }
     __syncthreads();
@@ -444,6 +457,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     constexpr bool NEG = decltype(neg_tag)::value;
     const int d = p.res_d, sh = p.shift, lo = p.lo, hi = p.hi;
     const int rhalf = RLEFT ? 0 : (1 << (-d - 1));
+    const ScaledClip c1 = scaled_clip(lo, hi, NEG ? 0 : sh);
+    const int sh2 = p.shift2, a2 = p.add2;
+    const ScaledClip c2 = scaled_clip(p.lo2, p.hi2, p.y2 ? sh2 : 0);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
@@ -464,15 +480,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
           if (p.y2) {
             // second format of the same accumulator (uniform branch): swap the rounding addend,
             // shift (>= 0 on this path), clip; staged behind the first output's tile
-            const int sh2 = p.shift2, lo2 = p.lo2, hi2 = p.hi2, a2 = p.add2;
             int u[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) u[j] = requant<false>(v[j] + a2, sh2, lo2, hi2);
-            *reinterpret_cast<uint32_t *>(slot + BM * PITCH) = pack4(u[0], u[1], u[2], u[3]);
+            for (int j = 0; j < 4; ++j) u[j] = clamp_med3(v[j] + a2, c2.lo, c2.hi);
+            *reinterpret_cast<uint32_t *>(slot + BM * PITCH) = shift_pack4(u[0], u[1], u[2], u[3], sh2);
           }
+          if (NEG) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = requant<NEG>(v[j], sh, lo, hi);
-          *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
+            for (int j = 0; j < 4; ++j) v[j] = requant<true>(v[j], sh, lo, hi);
+            *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
+          } else {
+            // clip at the accumulator's scale, then one shift-and-pack instruction per value
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = clamp_med3(v[j], c1.lo, c1.hi);
+            *reinterpret_cast<uint32_t *>(slot) = shift_pack4(v[0], v[1], v[2], v[3], sh);
+          }
         }
       }
     }
@@ -494,31 +516,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     }
   }
   __syncthreads();
-  uint8_t *y = static_cast<uint8_t *>(p.y);
-  for (int idx = tid; idx < BM * CPR; idx += NT) {
-    const int row = idx / CPR, pc = idx - row * CPR;
-    const int m = m0 + row, n = n0 + pc * EV;
-    if (m < p.M && n < p.N) {
-      if (EV == 16) *reinterpret_cast<v4i *>(y + (size_t)m * p.N + n) =
-          *reinterpret_cast<const v4i *>(epi + row * PITCH + pc * 16);
-      else *reinterpret_cast<uint32_t *>(y + (size_t)m * p.N + n) =
-          *reinterpret_cast<const uint32_t *>(epi + row * PITCH + pc * 4);
+  auto store_tile = [&](void *dst, const uint8_t *staged) {
+    const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(dst, 0, (int)out_bytes, 0x00027000);
+#pragma unroll 4
+    for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+      const int row = tid / CPR + i * ROWS_PER_PASS, pc = tid % CPR;
+      if (EV == 16) __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const v4i *>(staged + row * PITCH + pc * 16), yres,
+                                                           piece_off + i * pass_step, 0, 0);
+      else __builtin_amdgcn_raw_buffer_store_b32(*reinterpret_cast<const uint32_t *>(staged + row * PITCH + pc * 4), yres,
+                                                 piece_off + i * pass_step, 0, 0);
     }
-  }
-  if (p.y2) {
-    uint8_t *y2 = static_cast<uint8_t *>(p.y2);
-    const uint8_t *epi2 = epi + BM * PITCH;
-    for (int idx = tid; idx < BM * CPR; idx += NT) {
-      const int row = idx / CPR, pc = idx - row * CPR;
-      const int m = m0 + row, n = n0 + pc * EV;
-      if (m < p.M && n < p.N) {
-        if (EV == 16) *reinterpret_cast<v4i *>(y2 + (size_t)m * p.N + n) =
-            *reinterpret_cast<const v4i *>(epi2 + row * PITCH + pc * 16);
-        else *reinterpret_cast<uint32_t *>(y2 + (size_t)m * p.N + n) =
-            *reinterpret_cast<const uint32_t *>(epi2 + row * PITCH + pc * 4);
-      }
-    }
-  }
+  };
+  store_tile(p.y, epi);
+  if (p.y2) store_tile(p.y2, epi + BM * PITCH);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int MINB, int EV, bool UT>

@@ -25,6 +25,7 @@ struct ConvParams {
   void *y2;
   int shift2, lo2, hi2, add2;
   int remap;                // 1: XCD-aware tile order
+  int gemm;                 // 1: 1x1 window, stride 1, no padding (output pixel m reads input pixel m)
   // 64 bytes of zeros in device memory that stand in for padding taps and rows outside the
   // tensor (fast path).  If x and zero both lie within 4 GiB above lo_base, near = 1 and
   // x_delta / z_delta are their offsets from it.

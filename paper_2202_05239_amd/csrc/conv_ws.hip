@@ -67,51 +67,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   const int t_end = t + per + ((int)blockIdx.x < rem ? 1 : 0);
   if (t >= t_end) return;
 
-  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C.  They reach
-  // the registers through LDS (the patch buffers are not in use yet), all 64 channels at once or 16 of 128 at a time: the
-  // global loads are then contiguous (a lane reading its own fragments straight from memory would
-  // touch a different cache line than every other lane, 9 C bytes apart, while every workgroup of the
-  // launch asks for the same lines at the same moment).  Rows sit 9 C + 16 bytes apart in LDS, which
-  // spreads the 16 rows a fragment read touches over all banks.
-  v4i fa[KS];
-  {
-    constexpr int ROWB = 9 * C, WPITCH = ROWB + 16, PPR = ROWB / 16;     // bytes, pieces per row
-    constexpr int RPC = S::WROWS;                                        // weight rows per pass
-    constexpr int CHUNK_PIECES = RPC * PPR, PPT = (CHUNK_PIECES + WS_NT - 1) / WS_NT;
-    v4i wbuf[PPT];
-    auto fetch_rows = [&](int j) {
-#pragma unroll
-      for (int k = 0; k < PPT; ++k) {
-        const int i = tid + k * WS_NT;
-        if (i < CHUNK_PIECES) wbuf[k] = *reinterpret_cast<const v4i *>(p.w + (size_t)j * (RPC * ROWB) + (size_t)i * 16);
-      }
-    };
-    fetch_rows(0);
-#pragma unroll 1
-    for (int j = 0; j < C / RPC; ++j) {
-#pragma unroll
-      for (int k = 0; k < PPT; ++k) {
-        const int i = tid + k * WS_NT, row = i / PPR, col = i - row * PPR;
-        if (i < CHUNK_PIECES) *reinterpret_cast<v4i *>(lds + row * WPITCH + 16 * col) = wbuf[k];
-      }
-      if (j + 1 < C / RPC) fetch_rows(j + 1);
-      __syncthreads();
-      const int r = 32 * wn + l32;                          // this lane's channel
-      if (r / RPC == j) {
-#pragma unroll
-        for (int sl = 0; sl < KS; ++sl)
-          fa[sl] = *reinterpret_cast<const v4i *>(lds + (r % RPC) * WPITCH + 32 * sl + 16 * half);
-      }
-      __syncthreads();
-    }
-  }
-  if (tid < C) start[tid] = p.acc0[tid];
-  // Both patch buffers start as the value zero in the form the matrix instruction sees it (unsigned
-  // activations are stored xor 0x80, which makes them signed); only the pixels between the border
-  // pixels are ever rewritten.
   const int zx = (int)p.x_xor;
-  for (int i = tid; i < (2 * patch_bytes) >> 4; i += WS_NT) *reinterpret_cast<v4i *>(lds + 16 * i) = v4i{zx, zx, zx, zx};
-
   // This thread's pieces of a patch: piece c = tid + 256 k is 16 bytes of patch row c / (W C / 16); it lies
   // 16 c bytes behind the start of the patch's first row in the image.  Where it goes in LDS never changes:
   // kept with the row number in one register (offset in the low 20 bits).
@@ -161,10 +117,61 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
     }
   };
 
+  // the first tile's input rows are requested before anything else: they come from HBM, the weights from L2
   v4i nextbuf[MAXCH];
   fetch_patch(t, nextbuf);
-  __syncthreads();                     // the fill is complete
-  store_patch(0, nextbuf);
+
+  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C.  They reach
+  // the registers through LDS (the patch buffers are not in use yet), all 64 channels at once or 16 of 128 at a time: the
+  // global loads are then contiguous (a lane reading its own fragments straight from memory would
+  // touch a different cache line than every other lane, 9 C bytes apart, while every workgroup of the
+  // launch asks for the same lines at the same moment).  Rows sit 9 C + 16 bytes apart in LDS, which
+  // spreads the 16 rows a fragment read touches over all banks.
+  v4i fa[KS];
+  {
+    constexpr int ROWB = 9 * C, WPITCH = ROWB + 16, PPR = ROWB / 16;     // bytes, pieces per row
+    constexpr int RPC = S::WROWS;                                        // weight rows per pass
+    constexpr int CHUNK_PIECES = RPC * PPR, PPT = (CHUNK_PIECES + WS_NT - 1) / WS_NT;
+    v4i wbuf[PPT];
+    auto fetch_rows = [&](int j) {
+#pragma unroll
+      for (int k = 0; k < PPT; ++k) {
+        const int i = tid + k * WS_NT;
+        if (i < CHUNK_PIECES) wbuf[k] = *reinterpret_cast<const v4i *>(p.w + (size_t)j * (RPC * ROWB) + (size_t)i * 16);
+      }
+    };
+    fetch_rows(0);
+#pragma unroll 1
+    for (int j = 0; j < C / RPC; ++j) {
+#pragma unroll
+      for (int k = 0; k < PPT; ++k) {
+        const int i = tid + k * WS_NT, row = i / PPR, col = i - row * PPR;
+        if (i < CHUNK_PIECES) *reinterpret_cast<v4i *>(lds + row * WPITCH + 16 * col) = wbuf[k];
+      }
+      if (j + 1 < C / RPC) fetch_rows(j + 1);
+      __syncthreads();
+      const int r = 32 * wn + l32;                          // this lane's channel
+      if (r / RPC == j) {
+#pragma unroll
+        for (int sl = 0; sl < KS; ++sl)
+          fa[sl] = *reinterpret_cast<const v4i *>(lds + (r % RPC) * WPITCH + 32 * sl + 16 * half);
+      }
+      __syncthreads();
+    }
+  }
+  if (tid < C) start[tid] = p.acc0[tid];
+  // The border pixels of both patch buffers (one before the first row, one behind every row) hold
+  // the value zero in the form the matrix instruction sees it (unsigned activations are stored
+  // xor 0x80, which makes them signed) and are never rewritten; every other pixel of a patch is
+  // written for every tile, rows outside the image as zeros.
+  for (int i = tid; i < 2 * (1 + p.nrows) * S::PIECES; i += WS_NT) {
+    const int which_buf = i / ((1 + p.nrows) * S::PIECES), j = i - which_buf * ((1 + p.nrows) * S::PIECES);
+    const int px = j / S::PIECES, part = j - px * S::PIECES;            // px 0: the leading pixel; px r + 1: behind row r
+    const int off = px == 0 ? 0 : C + (px - 1) * p.pitch + p.W * C;
+    *reinterpret_cast<v4i *>(lds + which_buf * patch_bytes + off + 16 * part) = v4i{zx, zx, zx, zx};
+  }
+
+  store_patch(0, nextbuf);               // (the weight passes ended with a barrier: LDS is free)
   int which = 0;
   if (t + 1 < t_end) fetch_patch(t + 1, nextbuf);
   __syncthreads();

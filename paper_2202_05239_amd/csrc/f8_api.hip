@@ -12,6 +12,7 @@ namespace {
 struct TuningName { const char *name; const char *env; std::atomic<int> Tuning::*field; };
 const TuningName kTuningNames[] = {
     {"conv_variant", "F8_CONV_VARIANT", &Tuning::conv_variant}, {"conv_ws", "F8_CONV_WS", &Tuning::conv_ws},
+    {"conv_ws_min", "F8_CONV_WS_MIN", &Tuning::conv_ws_min},
     {"pw_ws", "F8_PW_WS", &Tuning::pw_ws},                       {"pw_small", "F8_PW_SMALL", &Tuning::pw_small},
     {"xcd_remap", "F8_XCD_REMAP", &Tuning::xcd_remap},           {"stem_pool", "F8_STEM_POOL", &Tuning::stem_pool},
     {"conv_tail", "F8_CONV_TAIL", &Tuning::conv_tail},
@@ -95,10 +96,10 @@ static int widest_vec(int C, const void *a, const void *b) {
 static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
                         const f8_quant &q, const void *y2) {
   if (!tuning().conv_ws.load(std::memory_order_relaxed) || res || y2 || q.y_type == F8_S32) return false;
-  // it pays once a workgroup walks over several tiles (measured: level with the general kernel at
-  // 800 and 1600 blocks of 128 pixels per image set, 15-20 % ahead at 6400)
+  // measured against the general kernel: 10-15 % ahead at 800 blocks (the single 3x3 layer at batch 32),
+  // 20-30 % ahead once every workgroup walks over several tiles
   const int granule = g.Cin == 64 ? 128 : 64;       // pixels
-  if ((long long)g.B * ((g.H * g.W + granule - 1) / granule) < 2048) return false;
+  if ((long long)g.B * ((g.H * g.W + granule - 1) / granule) < tuning().conv_ws_min.load(std::memory_order_relaxed)) return false;
   return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
@@ -211,6 +212,7 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
   p.fd_cpt = FastDiv((uint32_t)((g.Cin & 63) == 0 ? g.Cin / 64 : 1));
   p.fd_cpt2 = FastDiv((uint32_t)((g.Cin & 127) == 0 ? g.Cin / 128 : 1));
   p.remap = tuning().xcd_remap.load(std::memory_order_relaxed) != 0;
+  p.gemm = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
   p.fd_s = FastDiv((uint32_t)g.S);
   p.tap_rep = 0;
   if (g.R * g.S <= 32)

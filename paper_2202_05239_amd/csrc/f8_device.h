@@ -60,6 +60,52 @@ __device__ __forceinline__ int requant(int a, int s, int lo, int hi) {
   return min(max(v, lo), hi);
 }
 
+// The same rounding shift + clip with the two steps swapped, so that the shift can also do the
+// packing: clip(a >> s, lo, hi) == clamp(a, lo << s, ((hi + 1) << s) - 1) >> s for s >= 0 (the shift
+// floors, so a >> s >= lo exactly when a >= lo << s, and a >> s <= hi exactly when a < (hi + 1) << s).
+// The scaled bounds are saturated to the 32-bit range, which keeps the identity (no a lies beyond).
+struct ScaledClip {
+  int lo, hi;
+};
+__host__ __device__ inline ScaledClip scaled_clip(int lo, int hi, int s) {
+  const long long l = (long long)lo << s, h = (((long long)hi + 1) << s) - 1;
+  ScaledClip c;
+  c.lo = l < -2147483647LL - 1 ? (int)(-2147483647LL - 1) : (int)l;
+  c.hi = h > 2147483647LL ? 2147483647 : (int)h;
+  return c;
+}
+
+// clamp with lo <= hi as one instruction.  (The statements below are volatile so that they stay
+// behind the waits their callers place in front of them: the compiler inserts the wait states a
+// matrix-instruction result needs before a vector instruction reads it only for instructions it
+// can see, and would otherwise be free to move these up to the matrix instructions.)
+__device__ __forceinline__ int clamp_med3(int v, int lo, int hi) {
+  int r;
+  asm volatile("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+  return r;
+}
+
+// Enough wait states for the last matrix instruction's result to be readable by any instruction.
+__device__ __forceinline__ void wait_matrix_results() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory"); }
+
+// Four accumulators, each already clamped to scaled bounds, shifted right by s (uniform) and packed
+// into one dword: the arithmetic shift writes its low byte straight into byte j of the result
+// (sub-dword addressing of the destination), so shift and pack are one instruction per value.  A
+// vector instruction that reads a register right after a sub-dword write to it needs one wait state
+// on this chip; the compiler cannot see into an asm statement, so the wait is part of it.
+__device__ __forceinline__ uint32_t shift_pack4(int v0, int v1, int v2, int v3, int s) {
+  uint32_t d;
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "=v"(d) : "s"(s), "v"(v0));
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "+v"(d) : "s"(s), "v"(v1));
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "+v"(d) : "s"(s), "v"(v2));
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "+v"(d) : "s"(s), "v"(v3));
+  return d;
+}
+
 // Four 8-bit results (already clipped into their type's range) into one dword.
 __device__ __forceinline__ uint32_t pack4(int v0, int v1, int v2, int v3) {
   const uint32_t lo = __builtin_amdgcn_perm((uint32_t)v1, (uint32_t)v0, 0x0c0c0400u);  // bytes: v0.b0, v1.b0

@@ -22,6 +22,7 @@ namespace f8 {
 struct Tuning {
   std::atomic<int> conv_variant{-1};   // >= 0: force this tile variant of the LDS-direct dense kernel
   std::atomic<int> conv_ws{1};         // weights-stationary 3x3 kernel
+  std::atomic<int> conv_ws_min{768};    // ... from this many 128-pixel (64 channels) or 64-pixel (128 channels) blocks on
   std::atomic<int> pw_ws{1};           // weights-stationary 1x1 kernel (64 -> 256)
   std::atomic<int> pw_small{1};        // streaming 1x1 kernel for few input channels
   std::atomic<int> xcd_remap{1};       // XCD-aware tile order

@@ -229,7 +229,7 @@ def test_weights_stationary_3x3_64(oracle):
     input rows in LDS): image widths from 8 to 64, heights that leave ragged last tiles, one-row images,
     every input / output type, a shift of zero, clips inside the range."""
     rng = np.random.default_rng(640)
-    # batches large enough for the library to pick this kernel (at least 2048 tiles of 128 pixels at
+    # batches large enough for the library to pick this kernel (at least 768 blocks of 128 pixels at
     # 64 channels, of 64 pixels at 128)
     for C, B, H, W, xt, yt, shift, clip in ((64, 85, 56, 56, "u8", "u8", 9, None), (64, 2048, 13, 8, "s8", "s8", 7, (-50, 90)),
                                             (64, 2051, 1, 64, "u8", "s8", 8, None), (64, 1030, 7, 33, "s8", "u8", 0, (3, 200)),
@@ -252,7 +252,7 @@ def test_weights_stationary_3x3_64(oracle):
     chain = f8.Chain(net)
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 3
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<128x128>") == 3
-    assert [chain.layer_info(i, 4)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
+    assert [chain.layer_info(i, 2)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
 
 
 def test_weights_stationary_1x1_64_to_256(oracle):
