@@ -207,6 +207,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch the chain eagerly instead of replaying a HIP graph")
     ap.add_argument("--layers", default="", help="write the per-layer table (JSON) to this file")
     ap.add_argument("--fusion", action="store_true", help="run inverted-residual blocks as one fused kernel")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2: the two halves of the batch side by side on two streams inside every step (default); 1: one stream")
     ap.add_argument("--no-single-layer", action="store_true", help="skip the configs[1] / configs[2] layer figures")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (reference for the traffic counters)")
@@ -251,7 +253,7 @@ def main():
         x, net = wl.mobilenet_v1_forward(batch=args.batch)
     B = x.shape[0]
     xt = torch.from_numpy(x).to("cuda")
-    chain = f8.Chain(net, fusion=args.fusion).prepare(B)
+    chain = f8.Chain(net, fusion=args.fusion, streams=args.streams).prepare(B)
     out = torch.empty((B,) + chain.out_shape, dtype=chain.out_dtype, device="cuda")
 
     # One step = one replay of the captured chain (all layers, nothing skipped); the eager
@@ -335,7 +337,8 @@ def main():
         "config": {"workload": "%s: full %s fixed-point forward, batch %d, 224x224x3, seeded FL per layer"
                                % ({"resnet50": "configs[4]", "resnet18": "configs[3]"}.get(args.net, "extra"),
                                   net.name, B),
-                   "global_batch": B, "input": "224x224x3 int8", "layers": len(net.layers)},
+                   "global_batch": B, "input": "224x224x3 int8", "layers": len(net.layers),
+                   "streams_per_step": args.streams},
         "whole_net_TOPS": total_ops / (dt / args.steps) / 1e12,
         "roofline": roof,
     }

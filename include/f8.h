@@ -209,6 +209,17 @@ f8_status f8_chain_set_keep_all(f8_chain *c, int keep_all);
  * available through f8_chain_tensor.  Off by default (fusion = 1 switches it on; never used with
  * keep_all).  Call before f8_chain_workspace_bytes. */
 f8_status f8_chain_set_fusion(f8_chain *c, int fusion);
+/* n_streams = 2: f8_chain_run works on the two halves of the batch side by side, the first half on
+ * the caller's stream and the second on a stream the chain owns (created here, default priority,
+ * destroyed with the chain), which waits for what is already queued on the caller's stream and is
+ * waited for by it at the end of the call: to the caller the call still behaves like work on one
+ * stream, and it can still be captured into a HIP graph.  Images are independent (the layers of
+ * Eq. 6 act on each image alone), so the results are the same; layers that leave part of the
+ * chip idle, or that wait on memory, overlap with layers of the other half.  The workspace is
+ * the same size.  Intermediate tensors are then not available through f8_chain_tensor; with
+ * keep_all, or for a batch of one image, the call runs on one stream.  n_streams = 1 (the default)
+ * turns it off. */
+f8_status f8_chain_set_streams(f8_chain *c, int n_streams);
 void f8_chain_destroy(f8_chain *c);
 
 /* Measurement aids for the chain (not on the hot path).

@@ -23,7 +23,7 @@ TORCH_DTYPE = {"u8": torch.uint8, "s8": torch.int8, "s32": torch.int32,
 EXPORTS = [
     "f8_gemm_fixed", "f8_conv2d_fixed", "f8_conv2d_fixed_noalloc", "f8_conv2d_fixed_dual", "f8_dwconv_fixed", "f8_maxpool", "f8_global_pool_fixed",
     "f8_chain_create", "f8_chain_workspace_bytes", "f8_chain_prepare", "f8_chain_run",
-    "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_destroy",
+    "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_set_streams", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
     "f8_clip_from_alpha", "f8_status_str", "f8_release_scratch", "f8_abi_version", "f8_copy_bytes",
     "f8_tuning_set", "f8_tuning_get", "f8_mfma_i8_yardstick",
@@ -101,6 +101,7 @@ def lib():
     L.f8_chain_tensor.argtypes = [vp, i32, vp, i32, ctypes.POINTER(vp)] + [ctypes.POINTER(i32)] * 5
     L.f8_chain_set_keep_all.argtypes = [vp, i32]
     L.f8_chain_set_fusion.argtypes = [vp, i32]
+    L.f8_chain_set_streams.argtypes = [vp, i32]
     L.f8_chain_destroy.argtypes = [vp]
     L.f8_chain_num_layers.argtypes = [vp]
     L.f8_chain_layer_info.argtypes = [vp, i32, i32, ctypes.c_char_p, i32, ctypes.POINTER(ctypes.c_double),
@@ -374,7 +375,7 @@ class Chain:
     Weights and biases are uploaded once and kept alive here; the workspace is a torch
     uint8 tensor allocated by prepare()."""
 
-    def __init__(self, net, device="cuda", keep_all=False, fusion=False):
+    def __init__(self, net, device="cuda", keep_all=False, fusion=False, streams=1):
         L = lib()
         self.net = net
         self.device = device
@@ -409,6 +410,8 @@ class Chain:
             _check(L.f8_chain_set_keep_all(h, 1), "f8_chain_set_keep_all")
         if fusion:
             _check(L.f8_chain_set_fusion(h, 1), "f8_chain_set_fusion")
+        if streams != 1:
+            _check(L.f8_chain_set_streams(h, streams), "f8_chain_set_streams")
         self.workspace = None
         self.batch = None
         last = net.layers[-1]

@@ -201,7 +201,13 @@ struct f8_chain {
     planned = true;
   }
 
-  uint8_t *arena(void *workspace) const { return static_cast<uint8_t *>(workspace) + const_bytes; }
+  // Two halves of a batch can run side by side (f8_chain_set_streams): the second half's tensors lie
+  // behind the first half's, arena_shift bytes into the arena, while its layers are enqueued.
+  size_t arena_shift = 0;
+  int n_streams = 1;
+  hipStream_t side_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  uint8_t *arena(void *workspace) const { return static_cast<uint8_t *>(workspace) + const_bytes + arena_shift; }
 
   void *tensor_ptr(int id, const void *x, void *out, void *workspace, int batch) const {
     if (id == 0) return const_cast<void *>(x);
@@ -618,10 +624,46 @@ f8_status f8_chain_run(f8_chain *c, const void *x, void *out, void *workspace, i
   if (c->tensors[c->last_tensor].type == F8_S32 && (reinterpret_cast<uintptr_t>(out) & 3)) return F8_ERR_ALIGN;
   if (batch == 0) return F8_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (c->n_streams == 2 && !c->keep_all && batch >= 2) {
+    // first half of the images on the caller's stream, second half on the chain's own stream, which
+    // starts behind everything already queued on the caller's stream and is waited for at the end
+    const int b0 = batch / 2, b1 = batch - b0;
+    const Tensor &tin = c->tensors[0], &tout = c->tensors[c->last_tensor];
+    const void *x1 = static_cast<const uint8_t *>(x) + tin.bytes_per_image * (size_t)b0;
+    void *out1 = static_cast<uint8_t *>(out) + tout.bytes_per_image * (size_t)b0;
+    if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->side_stream, c->ev_fork, 0) != hipSuccess)
+      return F8_ERR_DEVICE;
+    f8_status st = F8_OK;
+    for (size_t i = 0; i < c->layers.size() && st == F8_OK; ++i) {
+      c->arena_shift = 0;
+      st = c->launch_layer(i, x, out, workspace, b0, s);
+      if (st != F8_OK) break;
+      c->arena_shift = c->arena_per_image * (size_t)b0;
+      st = c->launch_layer(i, x1, out1, workspace, b1, c->side_stream);
+    }
+    c->arena_shift = 0;
+    // join even after a failed launch, so that a capture in progress is left in a consistent state
+    if (hipEventRecord(c->ev_join, c->side_stream) != hipSuccess || hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess)
+      return F8_ERR_DEVICE;
+    return st;
+  }
   for (size_t i = 0; i < c->layers.size(); ++i) {
     const f8_status st = c->launch_layer(i, x, out, workspace, batch, s);
     if (st != F8_OK) return st;
   }
+  return F8_OK;
+}
+
+f8_status f8_chain_set_streams(f8_chain *c, int n_streams) {
+  if (!c) return F8_ERR_NULL;
+  if (n_streams != 1 && n_streams != 2) return F8_ERR_UNSUPPORTED;
+  if (n_streams == 2 && !c->side_stream) {
+    if (hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking) != hipSuccess) { c->side_stream = nullptr; return F8_ERR_DEVICE; }
+    if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+      return F8_ERR_DEVICE;
+  }
+  c->n_streams = n_streams;
   return F8_OK;
 }
 
@@ -635,7 +677,9 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
   const bool elided = (t.producer >= 0 && c->pool_role((size_t)t.producer) == 1) ||
                       (c->use_fusion() && t.producer >= 0 && c->fused[t.producer].role != 0 &&
                        !(c->fused[t.producer].role == 2 && t.producer >= 2 && c->fused[t.producer - 2].role == 1));
-  if (ptr) *ptr = (t.external || !workspace || elided) ? nullptr : c->tensor_ptr(id, nullptr, nullptr, workspace, batch);
+  // (with two streams the two halves of a tensor lie apart: not reported)
+  const bool halves = c->n_streams == 2 && !c->keep_all && batch >= 2;
+  if (ptr) *ptr = (t.external || !workspace || elided || halves) ? nullptr : c->tensor_ptr(id, nullptr, nullptr, workspace, batch);
   if (h) *h = t.h;
   if (w) *w = t.w;
   if (ch) *ch = t.c;
@@ -665,7 +709,13 @@ f8_status f8_chain_tensor(const f8_chain *c, int id, void *workspace, int batch,
   return F8_OK;
 }
 
-void f8_chain_destroy(f8_chain *c) { delete c; }
+void f8_chain_destroy(f8_chain *c) {
+  if (!c) return;
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
+  delete c;
+}
 
 // ---- measurement aids ---------------------------------------------------------------------
 

@@ -179,10 +179,25 @@ def test_config4_resnet50(oracle):
 
 def full_batch_logits(oracle, x, net, what):
     """Every image of the batch: the logits of the memory-reusing chain (fused stem, paired 1x1
-    layers: the launch configuration bench.py times) against the oracle's, image by image."""
+    layers, the two halves of the batch on two streams: the launch configuration bench.py times)
+    against the oracle's, image by image; the one-stream run and a captured graph of the
+    two-stream run, replayed with eager work in between, must give the same bits."""
     xt = torch.from_numpy(x).to(DEV)
-    out = f8.Chain(net).prepare(x.shape[0]).run(xt)
+    chain = f8.Chain(net, streams=2).prepare(x.shape[0])
+    out = chain.run(xt)
     torch.cuda.synchronize()
+    one = f8.Chain(net).prepare(x.shape[0]).run(xt)
+    torch.cuda.synchronize()
+    assert torch.equal(out, one), what + ": two streams differ from one"
+    buf = torch.zeros_like(out)
+    graph = chain.capture(xt, buf)
+    for rep in range(3):
+        buf.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf, out), what + ": replay %d of the two-stream graph differs" % rep
+        chain.run(xt)                       # eager work between the replays
     got = out.cpu().numpy()
     step = 4 * host_threads()
     for i0 in range(0, x.shape[0], step):
