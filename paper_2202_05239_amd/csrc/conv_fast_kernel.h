@@ -402,7 +402,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   }
   wait_vm<0>();
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
-  wait_matrix_results();
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[nb][mb][4g+j] is channel n0+wn0+nb*32+8g+4*half+j of pixel m0+wm0+mb*32+l32.
@@ -464,6 +463,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
+        settle_matrix_result(acc[nb][mb]);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           uint8_t *slot = epi + (wm0 + mb * 32 + l32) * PITCH + wn0 + nb * 32 + g * 8 + half * 4;

@@ -232,16 +232,20 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
     }
 
     // requantise into the staging tile
+    const ScaledClip sc = scaled_clip(p.lo, p.hi, p.shift);
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf)
+    for (int mf = 0; mf < MF; ++mf) {
+      settle_matrix_result(acc[mf]);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        // clip at the accumulator's scale, then one shift-and-pack instruction per value
         int v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = med3(acc[mf][4 * g + j] >> p.shift, p.lo, p.hi);
+        for (int j = 0; j < 4; ++j) v[j] = clamp_med3(acc[mf][4 * g + j], sc.lo, sc.hi);
         *reinterpret_cast<uint32_t *>(stage + ((32 * MF) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 8 * g + 4 * half) =
-            pack4(v[0], v[1], v[2], v[3]);
+            shift_pack4(v[0], v[1], v[2], v[3], p.shift);
       }
+    }
     if (tn < t_end) store_patch(which ^ 1, nextbuf);
     if (tn + 1 < t_end) fetch_patch(tn + 1, nextbuf);      // lands during the next tile
     __syncthreads();

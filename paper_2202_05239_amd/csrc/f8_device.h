@@ -85,8 +85,13 @@ __device__ __forceinline__ int clamp_med3(int v, int lo, int hi) {
   return r;
 }
 
-// Enough wait states for the last matrix instruction's result to be readable by any instruction.
-__device__ __forceinline__ void wait_matrix_results() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory"); }
+// Enough wait states for a matrix instruction's result to be readable by any instruction.  The
+// accumulator block is an operand of the statement, so the matrix instructions that write it stay in
+// front of it and everything that reads it stays behind, wherever the compiler schedules them.
+typedef int v16i_acc __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ void settle_matrix_result(v16i_acc &acc) {
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(acc));
+}
 
 // Four accumulators, each already clamped to scaled bounds, shifted right by s (uniform) and packed
 // into one dword: the arithmetic shift writes its low byte straight into byte j of the result
