@@ -278,7 +278,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   // so that its latency overlaps the K loop instead of following it.
   constexpr int CPR = BN / EV;                    // EV-byte pieces per tile row
   constexpr int RCH = BM * CPR / NT;              // pieces per thread
-  constexpr bool RES_PREFETCH = EV == 16 && RCH <= 4 && (BM * CPR) % NT == 0;
+  // (not when a 128-channel-wide variant is built for four workgroups per CU: the 16 registers are what keeps it from spilling,
+  // and the fourth workgroup hides the latency better than the prefetch does)
+  constexpr bool RES_PREFETCH = EV == 16 && RCH <= 4 && (BM * CPR) % NT == 0 && !(BN == 128 && MINB >= 4);
   v4i res_pre[RES_PREFETCH ? RCH : 1];
   // Residual reads and output stores go through buffer descriptors of exactly the tensors' size
   // (below 2 GiB): a piece of a row past the last pixel has an offset beyond that size, and a piece
