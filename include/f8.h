@@ -28,21 +28,28 @@
  *     before the call returns.  Activations are NHWC, channel fastest.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued asynchronously; the library does not synchronise (one exception below).
- *   - Arguments are validated on the host before anything is launched; a call that
- *     returns an error has launched nothing.  Errors are status codes, never aborts.
+ *   - Arguments are validated on the host before anything is launched: a call that returns a
+ *     validation error (anything but F8_ERR_DEVICE) has launched nothing.  Errors are status
+ *     codes, never aborts.
  *   - Preconditions the library cannot check (they depend on device data): A and
  *     A + 2^(s-1) fit in int32 (the paper keeps accumulators in 32 bits, Sec. 4.3).
- *     K <= 65536 is enforced so that sum |X*W| alone cannot overflow.
+ *     K <= 65536 is enforced so that sum |X*W| alone cannot overflow; a bias large enough to
+ *     break the precondition makes the accumulator wrap silently (two's complement), where the
+ *     CPU oracle reports an overflow.  F8_ERR_ACC_OVERFLOW is reserved for checkers that see the data.
  *   - x, w, y must not overlap.  q->res may be any tensor of y's shape except y itself.
  *   - The single-layer dense calls keep a small device scratch buffer per (device, stream):
  *     256 bytes of zeros (the kernels' stand-in for padding) plus the folded accumulator
  *     start value, 4 bytes per output channel rounded up to 256 channels, at least 64 KiB.
  *     It is allocated (hipMalloc) on the first call on a stream and when a call needs more
  *     channels than any before it; growing waits for that stream first (the one place the
- *     library synchronises).  f8_release_scratch() frees all of them.  Calls on different
- *     streams never share a buffer; calls on one stream are ordered by the stream.  The
- *     chain runner and the upstream steps allocate nothing: their memory is the caller's
- *     workspace.
+ *     library synchronises; such a call must not be made while the stream is being captured,
+ *     and a graph that captured an earlier call keeps pointing at the freed buffer).
+ *     f8_release_scratch() frees all of them.  Calls on different streams never share a buffer;
+ *     calls on one stream are ordered by the stream, and the buffer's look-up and the two kernel
+ *     launches of a call happen under one lock, so host threads may share a stream.
+ *     f8_conv2d_fixed_ws (caller's workspace) and f8_conv2d_fixed_noalloc (a fixed array in the
+ *     library) are the variants without this state.  The chain runner and the upstream steps
+ *     allocate nothing: their memory is the caller's workspace.
  */
 #ifndef F8_H
 #define F8_H
@@ -96,6 +103,19 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
                           int B, int H, int W, int Cin, int Cout, int R, int S,
                           int stride_h, int stride_w, int pad_h, int pad_w,
                           const f8_quant *q, void *stream);
+
+/* f8_conv2d_fixed with the dense kernels' scratch supplied by the caller: the call keeps no state in
+ * the library, allocates nothing, takes no lock and only enqueues kernels, so it can be captured
+ * into a HIP graph and issued from any number of host threads and streams at once, as long as
+ * calls that may overlap use different workspaces.  `workspace` is device memory, 256-byte
+ * aligned, of at least f8_conv_workspace_bytes(Cout) bytes (F8_ERR_ALIGN / F8_ERR_SHAPE otherwise);
+ * the call overwrites it (256 bytes of zeros, then the folded accumulator start values) and
+ * later calls on the same stream may reuse it. */
+size_t f8_conv_workspace_bytes(int Cout);
+f8_status f8_conv2d_fixed_ws(const void *x, const int8_t *w, const int32_t *bias, void *y,
+                             int B, int H, int W, int Cin, int Cout, int R, int S,
+                             int stride_h, int stride_w, int pad_h, int pad_w,
+                             const f8_quant *q, void *workspace, size_t workspace_bytes, void *stream);
 
 /* f8_conv2d_fixed for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same

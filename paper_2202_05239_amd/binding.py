@@ -21,7 +21,7 @@ TORCH_DTYPE = {"u8": torch.uint8, "s8": torch.int8, "s32": torch.int32,
                F8_U8: torch.uint8, F8_S8: torch.int8, F8_S32: torch.int32}
 
 EXPORTS = [
-    "f8_gemm_fixed", "f8_conv2d_fixed", "f8_conv2d_fixed_noalloc", "f8_conv2d_fixed_dual", "f8_dwconv_fixed", "f8_maxpool", "f8_global_pool_fixed",
+    "f8_gemm_fixed", "f8_conv2d_fixed", "f8_conv2d_fixed_noalloc", "f8_conv2d_fixed_ws", "f8_conv_workspace_bytes", "f8_conv2d_fixed_dual", "f8_dwconv_fixed", "f8_maxpool", "f8_global_pool_fixed",
     "f8_chain_create", "f8_chain_workspace_bytes", "f8_chain_prepare", "f8_chain_run",
     "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_set_streams", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
@@ -89,6 +89,9 @@ def lib():
     L.f8_gemm_fixed.argtypes = [vp, vp, vp, vp, i32, i32, i32, qp, vp]
     L.f8_conv2d_fixed.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [qp, vp]
     L.f8_conv2d_fixed_noalloc.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [qp, vp]
+    L.f8_conv2d_fixed_ws.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [qp, vp, ctypes.c_size_t, vp]
+    L.f8_conv_workspace_bytes.argtypes = [i32]
+    L.f8_conv_workspace_bytes.restype = ctypes.c_size_t
     L.f8_conv2d_fixed_dual.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [qp, ctypes.POINTER(f8_requant2), vp]
     L.f8_dwconv_fixed.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [qp, vp]
     L.f8_maxpool.argtypes = [vp, vp] + [i32] * 11 + [vp]
@@ -203,6 +206,18 @@ def f8_conv2d_fixed(x, w, bias, y, q, stride=(1, 1), pad=(0, 0), res=None):
     _check(lib().f8_conv2d_fixed(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), B, H, W, Cin, Cout, R, S,
                                  stride[0], stride[1], pad[0], pad[1], ctypes.byref(c), _stream()),
            "f8_conv2d_fixed")
+    return y
+
+
+def f8_conv2d_fixed_ws(x, w, bias, y, q, workspace, stride=(1, 1), pad=(0, 0), res=None, stream=None):
+    """f8_conv2d_fixed with caller-supplied scratch (a uint8 tensor of f8_conv_workspace_bytes(Cout) bytes)."""
+    B, H, W, Cin = x.shape
+    Cout, R, S, _ = w.shape
+    c = make_quant(q, res)
+    st = _stream() if stream is None else ctypes.c_void_p(stream.cuda_stream)
+    _check(lib().f8_conv2d_fixed_ws(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), B, H, W, Cin, Cout, R, S, stride[0], stride[1],
+                                    pad[0], pad[1], ctypes.byref(c), _ptr(workspace), workspace.numel(), st),
+           "f8_conv2d_fixed_ws")
     return y
 
 

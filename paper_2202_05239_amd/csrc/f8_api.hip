@@ -400,6 +400,34 @@ f8_status f8_conv2d_fixed(const void *x, const int8_t *w, const int32_t *bias, v
   return dense_on_stream_scratch(x, w, bias, y, g, *q, static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
+size_t f8_conv_workspace_bytes(int Cout) { return Cout < 0 ? 0 : (64 + acc0_padded(Cout)) * sizeof(int32_t); }
+
+f8_status f8_conv2d_fixed_ws(const void *x, const int8_t *w, const int32_t *bias, void *y, int B, int H, int W, int Cin,
+                             int Cout, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w, const f8_quant *q,
+                             void *workspace, size_t workspace_bytes, void *stream) {
+  if (!x || !w || !y || !workspace) return F8_ERR_NULL;
+  f8_status st = check_quant(q, true);
+  if (st != F8_OK) return st;
+  Geom g{B, H, W, Cin, Cout, R, S, stride_h, stride_w, pad_h, pad_w, 0, 0};
+  st = check_geom(g, false);
+  if (st != F8_OK) return st;
+  st = check_align(bias, y, *q, q->res);
+  if (st != F8_OK) return st;
+  if (q->res == y) return F8_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return F8_ERR_ALIGN;
+  if (workspace_bytes < f8_conv_workspace_bytes(Cout)) return F8_ERR_SHAPE;
+  if ((long long)g.B * g.P * g.Q * g.Cout == 0) return F8_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the first 256 bytes are the kernels' page of zeros (cleared by a kernel, so the call can be captured),
+  // the folded start values follow
+  int32_t *base = static_cast<int32_t *>(workspace);
+  if (launch_fold_acc0(nullptr, nullptr, base, 0, 64, 0, 0, 0, s) != 0) return F8_ERR_DEVICE;
+  int32_t *acc0 = base + 64;
+  st = enqueue_fold(w, bias, acc0, g, *q, s);
+  if (st != F8_OK) return st;
+  return enqueue_conv(x, w, acc0, base, y, q->res, g, *q, s);
+}
+
 f8_status f8_conv2d_fixed_noalloc(const void *x, const int8_t *w, const int32_t *bias, void *y, int B, int H, int W,
                                   int Cin, int Cout, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
                                   const f8_quant *q, void *stream) {

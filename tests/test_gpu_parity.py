@@ -576,6 +576,60 @@ def test_repeatable_and_streams(oracle):
         assert_same(o, want, "repeat")
 
 
+def test_caller_workspace_entry_point_from_two_threads_and_streams(oracle):
+    """f8_conv2d_fixed_ws keeps no state in the library: four host threads, each with its own stream
+    and workspace, issue different layers at the same time, repeatedly; every result is the
+    oracle's.  The allocating entry point, called from the same threads on one shared stream,
+    must also stay correct (its scratch look-up and launches are under one lock)."""
+    import threading
+    rng = np.random.default_rng(4242)
+    cases = [(2, 19, 23, 64, 72, 1, 1, 1, 0, "u8", "u8", "u8"), (1, 21, 9, 256, 40, 3, 3, 2, 1, "u8", "s8", None),
+             (2, 15, 17, 32, 272, 3, 3, 1, 1, "u8", "u8", "s8"), (3, 13, 11, 128, 136, 1, 1, 1, 0, "s8", "s8", None)]
+    jobs = []
+    for case in cases:
+        B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt = case
+        x, L, res = wl.random_conv_case(rng, B, H, W, Cin, Cout, R, S, st, pd, xt, yt, rt)
+        want = oracle.conv2d_fixed(x, L.w, L.bias, L, (st, st), (pd, pd), res)
+        dev = [torch.from_numpy(a).to(DEV) if a is not None else None for a in (x, L.w, L.bias, res)]
+        ws = torch.empty(f8.lib().f8_conv_workspace_bytes(Cout) + 256, dtype=torch.uint8, device=DEV)
+        ws = ws[(-ws.data_ptr()) % 256:][:f8.lib().f8_conv_workspace_bytes(Cout)]
+        jobs.append((L, dev, want, ws, torch.cuda.Stream(), (st, st), (pd, pd)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(job, shared):
+        L, (xd, wd, bd, rd), want, ws, stream, stride, pad = job
+        try:
+            for rep in range(6):
+                y = torch.full(want.shape, 77, dtype=f8.TORCH_DTYPE[L.y_type], device=DEV)
+                if shared:
+                    f8.f8_conv2d_fixed(xd, wd, bd, y, L, stride, pad, rd)        # all threads on the default stream
+                    torch.cuda.synchronize()
+                else:
+                    with torch.cuda.stream(stream):
+                        y.fill_(77)
+                        f8.f8_conv2d_fixed_ws(xd, wd, bd, y, L, ws, stride, pad, rd, stream=stream)
+                    stream.synchronize()
+                if not np.array_equal(y.cpu().numpy(), want):
+                    errors.append((L.Cout, rep, shared))
+        except Exception as e:                       # noqa: BLE001 (reported below)
+            errors.append(repr(e))
+
+    for shared in (False, True):
+        threads = [threading.Thread(target=worker, args=(j, shared)) for j in jobs]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+    assert not errors, errors
+    # validation of the workspace arguments happens before any launch
+    L, (xd, wd, bd, rd), want, ws, stream, stride, pad = jobs[0]
+    y = torch.empty(want.shape, dtype=torch.uint8, device=DEV)
+    with pytest.raises(f8.F8Error) as e:
+        f8.f8_conv2d_fixed_ws(xd, wd, bd, y, L, ws[:64], stride, pad, rd)
+    assert e.value.code == 2
+
+
 # ------------------------------------------------------------------------- tile variants
 
 N_TILE_VARIANTS = 24
