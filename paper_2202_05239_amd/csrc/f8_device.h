@@ -111,6 +111,17 @@ __device__ __forceinline__ uint32_t shift_pack4(int v0, int v1, int v2, int v3, 
   return d;
 }
 
+// The same for two values as the two 16-bit halves of a dword (kernels that go on working on the
+// clipped values with packed 16-bit arithmetic).
+__device__ __forceinline__ uint32_t shift_pack2_16(int v0, int v1, int s) {
+  uint32_t d;
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "=v"(d) : "s"(s), "v"(v0));
+  asm volatile("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD\n\ts_nop 0"
+      : "+v"(d) : "s"(s), "v"(v1));
+  return d;
+}
+
 // Four 8-bit results (already clipped into their type's range) into one dword.
 __device__ __forceinline__ uint32_t pack4(int v0, int v1, int v2, int v3) {
   const uint32_t lo = __builtin_amdgcn_perm((uint32_t)v1, (uint32_t)v0, 0x0c0c0400u);  // bytes: v0.b0, v1.b0

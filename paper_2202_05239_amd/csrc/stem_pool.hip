@@ -155,22 +155,28 @@ __global__ __launch_bounds__(SP_NT, 3) void stem_pool_kernel(const StemPoolParam
           acc[nf][mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[nf][r], fb[mf], acc[nf][mf], 0, 0, 0);
     }
 
-    // requantise into the LDS tile; pixels outside the image (and GEMM row 255) as zeros
+    // requantise into the LDS tile; pixels outside the image (and GEMM row 255) as zeros: they take
+    // clip bounds of zero.  Clip at the accumulator's scale, then the shift writes each value straight
+    // into its 16-bit half of the tile's dword.
+    const ScaledClip sc = scaled_clip(p.lo, p.hi, p.shift);
 #pragma unroll
     for (int mf = 0; mf < 2; ++mf) {
       const int pc = 2 * TPI * ti - 1 + py_of[mf], qc = 2 * TPJ * tj - 1 + px_of[mf];
       const bool real = m_of[mf] < CR * CC && pc >= 0 && pc < p.P && qc >= 0 && qc < p.Q;
+      const int lo_s = real ? sc.lo : 0, hi_s = real ? sc.hi : 0;
 #pragma unroll
-      for (int nf = 0; nf < 2; ++nf)
+      for (int nf = 0; nf < 2; ++nf) {
+        settle_matrix_result(acc[nf][mf]);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           int v[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = med3(acc[nf][mf][4 * g + j] >> p.shift, p.lo, p.hi);
+          for (int j = 0; j < 4; ++j) v[j] = clamp_med3(acc[nf][mf][4 * g + j], lo_s, hi_s);
           // channels 32 nf + 8 g + 4 half + 0..3 as four 16-bit values
-          const v2i packed = real ? v2i{v[0] | (v[1] << 16), v[2] | (v[3] << 16)} : v2i{0, 0};
+          const v2i packed = v2i{(int)shift_pack2_16(v[0], v[1], p.shift), (int)shift_pack2_16(v[2], v[3], p.shift)};
           *reinterpret_cast<v2i *>(ct + m_of[mf] * CT_PITCH + 2 * (32 * nf + 8 * g + 4 * half)) = packed;
         }
+      }
     }
     if (more) store_patch(which ^ 1, nextbuf);
     if (tn + (int)gridDim.x < p.ntiles) fetch_patch(tn + gridDim.x, nextbuf);     // lands during the next tile
