@@ -56,6 +56,11 @@ __device__ __forceinline__ void wait_ahead(int ahead) {
 }
 
 // Chunk permutation of an LDS row: 4 chunks (BK 64) or 8 chunks (BK 128).
+// Row r = 8 g + 4 h + j of a 32 x 32 matrix result lies in lane half h, register 4 g + j.  Feeding
+// channel 16 h + 4 g + j as row r of the weight operand makes registers 0..15 of a lane the
+// channels 16 h .. 16 h + 15: one 16-byte piece of an output row after packing.
+__device__ __forceinline__ int frag_channel(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
+
 template <int BK>
 __device__ __forceinline__ int row_swizzle(int row) {
   return BK == 64 ? (row >> 2) & 3 : (row >> 1) & 7;
@@ -146,7 +151,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   int w_inc[WR];
 #pragma unroll
   for (int i = 0; i < WR; ++i) {
-    const int n = n0 + lrow + i * RPG;
+    // LDS row r of a 32-channel block holds channel frag_channel(r) of the block: the matrix
+    // instruction then leaves every lane with 16 consecutive channels of its pixel
+    const int lr = lrow + i * RPG;
+    const int n = n0 + (lr & ~31) + frag_channel(lr & 31);
     w_ok[i] = n < p.N;
     w_row[i] = p.w + (size_t)(w_ok[i] ? n : 0) * p.K + cl * 16;
     w_inc[i] = BK;
@@ -265,7 +273,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const v4i a0 = *reinterpret_cast<const v4i *>(p.acc0 + n0 + wn0 + nb * 32 + g * 8 + half * 4);
+      const v4i a0 = *reinterpret_cast<const v4i *>(p.acc0 + n0 + wn0 + nb * 32 + half * 16 + g * 4);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         acc[nb][mb][4 * g + 0] = a0.x; acc[nb][mb][4 * g + 1] = a0.y;
@@ -406,7 +414,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
   __syncthreads();        // every wave is done with the operand stages: reuse LDS for the epilogue
 
   // ---- epilogue ---------------------------------------------------------------------------
-  // acc[nb][mb][4g+j] is channel n0+wn0+nb*32+8g+4*half+j of pixel m0+wm0+mb*32+l32.
+  // acc[nb][mb][i] is channel n0+wn0+nb*32+16*half+i of pixel m0+wm0+mb*32+l32.
   if (p.y_type == T_S32) {
     // raw int32 accumulators (the classifier's logits): four consecutive channels per store
     int32_t *y32 = static_cast<int32_t *>(p.y);
@@ -417,7 +425,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
       for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn0 + nb * 32 + g * 8 + half * 4;
+          const int n = n0 + wn0 + nb * 32 + half * 16 + g * 4;
           if (m < p.M && n < p.N)
             *reinterpret_cast<v4i *>(y32 + (size_t)m * p.N + n) =
                 v4i{acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
@@ -466,37 +474,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, MINB) void conv_fast_kernel
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         settle_matrix_result(acc[nb][mb]);
+        // the lane's 16 channels are one 16-byte piece of the staged row
+        uint8_t *slot = epi + (wm0 + mb * 32 + l32) * PITCH + wn0 + nb * 32 + half * 16;
+        int v[16];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          uint8_t *slot = epi + (wm0 + mb * 32 + l32) * PITCH + wn0 + nb * 32 + g * 8 + half * 4;
-          int v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
-          if (RK != 0) {
-            const uint32_t rv = *reinterpret_cast<const uint32_t *>(slot);
+        for (int i = 0; i < 16; ++i) v[i] = acc[nb][mb][i];
+        if (RK != 0) {
+          const v4i rv = *reinterpret_cast<const v4i *>(slot);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe((int)rv, 8 * j, 8)
-                                    : (int)__builtin_amdgcn_ubfe(rv, 8 * j, 8);
-              v[j] += RLEFT ? (r << d) : ((r + rhalf) >> (-d));
-            }
+          for (int i = 0; i < 16; ++i) {
+            const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe(rv[i >> 2], 8 * (i & 3), 8)
+                                  : (int)__builtin_amdgcn_ubfe((uint32_t)rv[i >> 2], 8 * (i & 3), 8);
+            v[i] += RLEFT ? (r << d) : ((r + rhalf) >> (-d));
           }
-          if (p.y2) {
-            // second format of the same accumulator (uniform branch): swap the rounding addend,
-            // shift (>= 0 on this path), clip; staged behind the first output's tile
-            int u[4];
+        }
+        if (p.y2) {
+          // second format of the same accumulator (uniform branch): swap the rounding addend,
+          // shift (>= 0 on this path), clip; staged behind the first output's tile
+          int u[16];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) u[j] = clamp_med3(v[j] + a2, c2.lo, c2.hi);
-            *reinterpret_cast<uint32_t *>(slot + BM * PITCH) = shift_pack4(u[0], u[1], u[2], u[3], sh2);
-          }
-          if (NEG) {
+          for (int i = 0; i < 16; ++i) u[i] = clamp_med3(v[i] + a2, c2.lo, c2.hi);
+          *reinterpret_cast<v4i *>(slot + BM * PITCH) = shift_pack16(u, sh2);
+        }
+        if (NEG) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = requant<true>(v[j], sh, lo, hi);
-            *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
-          } else {
-            // clip at the accumulator's scale, then one shift-and-pack instruction per value
+          for (int i = 0; i < 16; ++i) v[i] = requant<true>(v[i], sh, lo, hi);
+          *reinterpret_cast<v4i *>(slot) = v4i{(int)pack4(v[0], v[1], v[2], v[3]), (int)pack4(v[4], v[5], v[6], v[7]),
+                                               (int)pack4(v[8], v[9], v[10], v[11]), (int)pack4(v[12], v[13], v[14], v[15])};
+        } else {
+          // clip at the accumulator's scale, then one shift-and-pack instruction per value
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = clamp_med3(v[j], c1.lo, c1.hi);
-            *reinterpret_cast<uint32_t *>(slot) = shift_pack4(v[0], v[1], v[2], v[3], sh);
-          }
+          for (int i = 0; i < 16; ++i) v[i] = clamp_med3(v[i], c1.lo, c1.hi);
+          *reinterpret_cast<v4i *>(slot) = shift_pack16(v, sh);
         }
       }
     }

@@ -111,6 +111,29 @@ __device__ __forceinline__ uint32_t shift_pack4(int v0, int v1, int v2, int v3, 
   return d;
 }
 
+// Sixteen values into four dwords (v[4 q + j] becomes byte j of dword q).  The four dwords are
+// filled side by side, byte 0 of each, then byte 1 of each, ..., so that three instructions
+// lie between two writes to one register and only the last write needs the wait state.
+__device__ __forceinline__ v4i shift_pack16(const int (&v)[16], int s) {
+  uint32_t d0, d1, d2, d3;
+#define F8_SP(D, V, B, U) "v_ashrrev_i32_sdwa " D ", %4, " V " dst_sel:BYTE_" B " dst_unused:" U " src0_sel:DWORD src1_sel:DWORD\n\t"
+  asm volatile(
+      F8_SP("%0", "%5", "0", "UNUSED_PAD") F8_SP("%1", "%9", "0", "UNUSED_PAD")
+      F8_SP("%2", "%13", "0", "UNUSED_PAD") F8_SP("%3", "%17", "0", "UNUSED_PAD")
+      F8_SP("%0", "%6", "1", "UNUSED_PRESERVE") F8_SP("%1", "%10", "1", "UNUSED_PRESERVE")
+      F8_SP("%2", "%14", "1", "UNUSED_PRESERVE") F8_SP("%3", "%18", "1", "UNUSED_PRESERVE")
+      F8_SP("%0", "%7", "2", "UNUSED_PRESERVE") F8_SP("%1", "%11", "2", "UNUSED_PRESERVE")
+      F8_SP("%2", "%15", "2", "UNUSED_PRESERVE") F8_SP("%3", "%19", "2", "UNUSED_PRESERVE")
+      F8_SP("%0", "%8", "3", "UNUSED_PRESERVE") F8_SP("%1", "%12", "3", "UNUSED_PRESERVE")
+      F8_SP("%2", "%16", "3", "UNUSED_PRESERVE") F8_SP("%3", "%20", "3", "UNUSED_PRESERVE")
+      "s_nop 0"
+      : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3)
+      : "s"(s), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]),
+        "v"(v[8]), "v"(v[9]), "v"(v[10]), "v"(v[11]), "v"(v[12]), "v"(v[13]), "v"(v[14]), "v"(v[15]));
+#undef F8_SP
+  return v4i{(int)d0, (int)d1, (int)d2, (int)d3};
+}
+
 // The same for two values as the two 16-bit halves of a dword (kernels that go on working on the
 // clipped values with packed 16-bit arithmetic).
 __device__ __forceinline__ uint32_t shift_pack2_16(int v0, int v1, int s) {
