@@ -9,8 +9,9 @@
 // fragment is 16 contiguous bytes of one pixel), its residual rows arrive as 16-byte pieces; both
 // are requested one block ahead.  The residual is laid into the wave's own 8 KiB of LDS (pieces of
 // a row permuted by the row number, so that the accumulator-layout accesses below spread over the
-// banks), each lane adds its accumulators to the four residual bytes it owns, requantises, and
-// writes the result back in place; the finished rows leave as 16-byte pieces, 1 KiB contiguous per
+// banks); the weight rows are fed in an order that leaves a lane with 16 consecutive channels of its
+// pixel, so each lane adds its accumulators to one 16-byte piece of the residual, requantises, and
+// writes the piece back in place; the finished rows leave as 16-byte pieces, 1 KiB contiguous per
 // store instruction.
 //
 // Optionally the 1x1 layer that reads this layer's output (256 -> 64 or 128 channels: the layer that
@@ -41,15 +42,15 @@ __device__ __forceinline__ lds_u8 *here(const uint8_t *shared_array) {
   return q;
 }
 
+// Row r = 8 g + 4 h + j of a 32 x 32 matrix result lies in lane half h, register 4 g + j.  With channel
+// 16 h + 4 g + j as row r of the weight operand, registers 0..15 of a lane are the channels
+// 16 h .. 16 h + 15 of its pixel: one 16-byte piece of the row.  frag_row is the inverse map.
+__device__ __forceinline__ int frag_channel(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
+__device__ __forceinline__ int frag_row(int c) { return 8 * ((c >> 2) & 3) + 4 * (c >> 4) + (c & 3); }
+
 constexpr int PW_NT = 256;
 constexpr int PW_C = 64, PW_N = 256;
 constexpr int PW_WAVE_LDS = 32 * PW_N;       // one block of 32 pixels x 256 bytes
-
-__device__ __forceinline__ int med3(int v, int lo, int hi) {
-  int r;
-  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
-  return r;
-}
 
 // RK: residual kind (0 none, 1 unsigned, 2 signed); RLEFT: the residual is shifted left to the
 // accumulator's scale (else rounded right); TQ: 32-channel blocks of the optional second layer (0: none,
@@ -73,12 +74,12 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
   const int l32 = lane & 31, half = lane >> 5;
   uint8_t *tile = tiles + wave * PW_WAVE_LDS;
 
-  // weights: fa[nb][ks] = channel 32 nb + l32, bytes 32 ks + 16 half .. + 16 of its 64
+  // weights: fa[nb][ks] = channel 32 nb + frag_channel(l32), bytes 32 ks + 16 half .. + 16 of its 64
   v4i fa[NB_REG][2];
   if (W1_LDS) {
 #pragma unroll
     for (int k = 0; k < 128 * PW_C / 16 / PW_NT; ++k) {
-      const int i = tid + k * PW_NT, n = i >> 2, pc = i & 3;
+      const int i = tid + k * PW_NT, n = ((i >> 2) & ~31) + frag_row((i >> 2) & 31), pc = i & 3;   // row in fragment order
       *reinterpret_cast<v4i *>(w1 + n * PW_C + 16 * (pc ^ ((n >> 2) & 3))) =
           *reinterpret_cast<const v4i *>(p.w + (size_t)128 * PW_C + (size_t)i * 16);
     }
@@ -87,14 +88,14 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
   for (int nb = 0; nb < NB_REG; ++nb)
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
-      fa[nb][ks] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * nb + l32) * PW_C + 32 * ks + 16 * half);
+      fa[nb][ks] = *reinterpret_cast<const v4i *>(p.w + (size_t)(32 * nb + frag_channel(l32)) * PW_C + 32 * ks + 16 * half);
   start[tid] = p.acc0[tid];
   if (TAIL) {
-    // the second layer's weights, rows of 256 bytes with their pieces permuted like the tile's
+    // the second layer's weights, rows of 256 bytes in fragment order, their pieces permuted like the tile's
     if (tid < PW_TN) start2[tid] = p.t_acc0[tid];
 #pragma unroll
     for (int k = 0; k < PW_TN * PW_N / 16 / PW_NT; ++k) {
-      const int i = tid + k * PW_NT, n2 = i >> 4, pc = i & 15;
+      const int i = tid + k * PW_NT, n2 = ((i >> 4) & ~31) + frag_row((i >> 4) & 31), pc = i & 15;
       *reinterpret_cast<v4i *>(w2 + n2 * PW_N + 16 * (pc ^ (n2 & 15))) = *reinterpret_cast<const v4i *>(p.t_w + (size_t)i * 16);
     }
   }
@@ -134,7 +135,8 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
   for (int j = 0; j < 8; ++j) rn[j] = v4i{0, 0, 0, 0};
   load_x(b, xn);
   if (HAS_RES) load_res(b, rn);
-  const int sh = p.shift, lo = p.lo, hi = p.hi;
+  const int sh = p.shift;
+  const ScaledClip c1 = scaled_clip(p.lo, p.hi, sh);
   const int d = RLEFT ? p.res_d : -p.res_d;            // shift distance, left or right
   const int rhalf = RLEFT ? 0 : (1 << (d - 1));
 
@@ -163,8 +165,8 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
       for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          // acc[q][4 g + j] is channel 64 h + 32 q + 8 g + 4 half + j of pixel l32
-          const v4i s0 = *reinterpret_cast<lds_v4i *>(st + 64 * h + 32 * q + 8 * g + 4 * half);
+          // acc[q][i] is channel 64 h + 32 q + 16 half + i of pixel l32
+          const v4i s0 = *reinterpret_cast<lds_v4i *>(st + 64 * h + 32 * q + 16 * half + 4 * g);
           acc[q][4 * g] = s0.x; acc[q][4 * g + 1] = s0.y; acc[q][4 * g + 2] = s0.z; acc[q][4 * g + 3] = s0.w;
         }
 #pragma unroll
@@ -181,32 +183,36 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
           acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xb[ks], acc[q], 0, 0, 0);
         }
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+      for (int q = 0; q < 2; ++q) {
+        settle_matrix_result(acc[q]);
+        // this lane's 16 channels are piece 4 h + 2 q + half of its row
+        uint8_t *slot = tile + l32 * PW_N + 16 * ((4 * h + 2 * q + half) ^ (l32 & 15));
+        int v[16];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int ch = 64 * h + 32 * q + 8 * g + 4 * half;         // this lane's four channels
-          uint8_t *slot = tile + l32 * PW_N + 16 * ((ch >> 4) ^ (l32 & 15)) + (ch & 15);
-          int v[4] = {acc[q][4 * g], acc[q][4 * g + 1], acc[q][4 * g + 2], acc[q][4 * g + 3]};
-          if (HAS_RES) {
-            const uint32_t rv = *reinterpret_cast<const uint32_t *>(slot);
+        for (int i = 0; i < 16; ++i) v[i] = acc[q][i];
+        if (HAS_RES) {
+          const v4i rv = *reinterpret_cast<const v4i *>(slot);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe((int)rv, 8 * j, 8) : (int)__builtin_amdgcn_ubfe(rv, 8 * j, 8);
-              v[j] += RLEFT ? (r << d) : ((r + rhalf) >> d);
-            }
+          for (int i = 0; i < 16; ++i) {
+            const int r = RK == 2 ? (int)__builtin_amdgcn_sbfe(rv[i >> 2], 8 * (i & 3), 8)
+                                  : (int)__builtin_amdgcn_ubfe((uint32_t)rv[i >> 2], 8 * (i & 3), 8);
+            v[i] += RLEFT ? (r << d) : ((r + rhalf) >> d);
           }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = med3(v[j] >> sh, lo, hi);
-          *reinterpret_cast<uint32_t *>(slot) = pack4(v[0], v[1], v[2], v[3]);
         }
+        // clip at the accumulator's scale, then one shift-and-pack instruction per value
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = clamp_med3(v[i], c1.lo, c1.hi);
+        *reinterpret_cast<v4i *>(slot) = shift_pack16(v, sh);
+      }
       __builtin_amdgcn_sched_barrier(0);       // keep the parts apart: one set of accumulators at a time
     }
-    uint32_t pk[TAIL ? TQ : 1][4];      // the second layer's results, four channels per dword
+    v4i pk[TAIL ? TQ : 1];              // the second layer's results, 16 channels per lane and block
     if (TAIL) {
       // the finished block is the second layer's activation operand: K = 256 = 8 slices; 64 of its
       // channels at a time, requantised and packed at once, so that few registers stay occupied
       const int tx = (int)p.t_xor;
-      const int sh2 = p.t_shift, lo2 = p.t_lo, hi2 = p.t_hi;
+      const int sh2 = p.t_shift;
+      const ScaledClip c2 = scaled_clip(p.t_lo, p.t_hi, sh2);
 #pragma unroll
       for (int th = 0; th < TQ / 2; ++th) {
         lds_i32 *st2 = here(start2);
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
         for (int q = 0; q < 2; ++q)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const v4i s0 = *reinterpret_cast<lds_v4i *>(st2 + 64 * th + 32 * q + 8 * g + 4 * half);
+            const v4i s0 = *reinterpret_cast<lds_v4i *>(st2 + 64 * th + 32 * q + 16 * half + 4 * g);
             acc2[q][4 * g] = s0.x; acc2[q][4 * g + 1] = s0.y; acc2[q][4 * g + 2] = s0.z; acc2[q][4 * g + 3] = s0.w;
           }
         // fragment reads run two slices ahead of the matrix instructions
@@ -239,14 +245,13 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
           __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < 2; ++q) {
+          settle_matrix_result(acc2[q]);
+          int v[16];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            int v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = med3(acc2[q][4 * g + j] >> sh2, lo2, hi2);
-            pk[2 * th + q][g] = pack4(v[0], v[1], v[2], v[3]);
-          }
+          for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc2[q][i], c2.lo, c2.hi);
+          pk[2 * th + q] = shift_pack16(v, sh2);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -274,10 +279,7 @@ __global__ __launch_bounds__(PW_NT, 2) void pw_ws_kernel(const PwWsParams p) {
     if (TAIL) {
       // the second layer's 32 x PW_TN results go through the (now free) tile to leave as 16-byte pieces
 #pragma unroll
-      for (int q = 0; q < TQ; ++q)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<uint32_t *>(tile + l32 * PW_TPITCH + 32 * q + 8 * g + 4 * half) = pk[q][g];
+      for (int q = 0; q < TQ; ++q) *reinterpret_cast<v4i *>(tile + l32 * PW_TPITCH + 32 * q + 16 * half) = pk[q];
       // piece i = lane + 64 k of the 32 x PW_TN block: rows advance by 64 / (PW_TN / 16) per k
       constexpr int PPR = PW_TN / 16, RSTEP = 64 / PPR;
       const int row0 = lane / PPR, pc = lane % PPR;
