@@ -1,0 +1,227 @@
+// Image-stationary 3x3 convolution, 256 -> 256 channels, stride 1, pad 1, images of at most 14 x 14
+// pixels (the 3x3 layers of the third ResNet stage), with the shift / clip epilogue of F8Net
+// Eq. 2 / Eq. 9.
+//
+// A GEMM tile of such a layer moves (rows + columns) x K operand bytes from L2 into LDS, and the nine
+// taps re-fetch every activation nine times; at the matrix pipes' rate that path is as busy as the
+// pipes themselves, and 14 x 14 x batch pixels cut into power-of-two tiles leave a quarter of the
+// CUs without one.  Here a workgroup takes one whole image: its pixels (with a border of zeros) sit
+// in LDS once, 196 output pixels are seven blocks of 32 matrix rows (the last one partly empty), and
+// every tap's activation fragment is read straight from that patch at a constant offset.  The
+// weights never pass through LDS: they are stored beforehand in the order the matrix instruction
+// wants them (a fragment = 1 KiB contiguous), and every wave streams the fragments of its 64 output
+// channels from L2 into registers, one tap ahead of their use.  Nothing in the K loop is shared
+// between waves but the read-only patch, so the loop has no barrier.  One wave per SIMD: 7 x 2
+// accumulator blocks (224 registers) per lane.
+#include "conv_img.h"
+
+namespace f8 {
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) const v4i lds_v4i;
+typedef __attribute__((address_space(3))) const uint8_t lds_u8;
+
+constexpr int IMG_NT = 256;
+constexpr int IMG_C = CONV_IMG_C;
+constexpr int IMG_PW = 16;                          // patch rows and columns (image + border)
+constexpr int IMG_PITCH = IMG_C + 16;               // bytes per patch pixel: 16 neighbouring pixels spread over all banks
+constexpr int IMG_MB = 7;                           // 32-pixel blocks per image
+constexpr int IMG_KPT = IMG_C / 32;                 // K slices per tap
+constexpr int IMG_KS = 9 * IMG_KPT;                 // K slices in all
+constexpr int IMG_LDS = IMG_PW * IMG_PW * IMG_PITCH;
+
+// Row r = 8 g + 4 h + j of a 32 x 32 matrix result lies in lane half h, register 4 g + j.  With channel
+// 16 h + 4 g + j as row r of the weight operand, registers 0..15 of a lane are the channels
+// 16 h .. 16 h + 15 of its pixel: one 16-byte piece of an output row.
+__host__ __device__ inline int frag_channel(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
+
+// Piece i (16 bytes) of the weights in fragment order: fragment (32-channel block nb, K slice t) is
+// 64 pieces, piece `lane` = the 16 bytes lane (l32, half) feeds to the matrix instruction: channel
+// 32 nb + frag_channel(l32), tap t / 8, input channels 32 (t % 8) + 16 half .. + 16.
+__global__ __launch_bounds__(256) void conv_img_weights_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wf) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int)(CONV_IMG_W_BYTES / 16)) return;
+  const int lane = i & 63, t = (i >> 6) % IMG_KS, nb = (i >> 6) / IMG_KS;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int n = 32 * nb + frag_channel(l32), tap = t / IMG_KPT, cs = t % IMG_KPT;
+  *reinterpret_cast<v4i *>(wf + (size_t)i * 16) =
+      *reinterpret_cast<const v4i *>(w + ((size_t)n * 9 + tap) * IMG_C + 32 * cs + 16 * half);
+}
+
+__global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int HW = p.H * p.W;
+  const int image_bytes = HW * IMG_C;
+
+  // Fragment row j * 32 + l32 is output pixel m of the image; its window starts at patch pixel
+  // (oy, ox).  Rows past the last pixel read the patch's first pixels; their results are dropped.
+  lds_u8 *arow[IMG_MB];
+  lds_u8 *patch = (lds_u8 *)lds;
+#pragma unroll
+  for (int j = 0; j < IMG_MB; ++j) {
+    const int m = 32 * j + l32;
+    const int oy = m < HW ? m / p.W : 0, ox = m < HW ? m - oy * p.W : 0;
+    arow[j] = patch + (oy * IMG_PW + ox) * IMG_PITCH + 16 * half;
+  }
+
+  // This wave's weights: channel blocks 2 wave and 2 wave + 1, a fragment per K slice each.
+  // (the descriptor starts at the wave's first fragment, so that the offsets below are constants)
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t *>(p.wf) + (size_t)wave * (2 * IMG_KS * 1024), 0, 2 * IMG_KS * 1024, 0x00027000);
+  const int lane16 = lane * 16;
+  auto load_w = [&](int q, int t) {
+    return __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, (q * IMG_KS + t) * 1024, 0);
+  };
+
+  // Patch role: column tid / 16 of the patch, piece tid % 16 of its pixels, one row per step.
+  const int pcol = tid >> 4, ppiece = tid & 15;
+  const bool col_in = (unsigned)(pcol - 1) < (unsigned)p.W;
+  const int zx = (int)p.x_xor;
+  const ScaledClip c1 = scaled_clip(p.lo, p.hi, p.shift);
+  const int sh = p.shift;
+
+  for (int img = blockIdx.x; img < p.B; img += gridDim.x) {
+    // the first tap's weights are requested before anything else
+    v4i bq[IMG_KPT][2];
+#pragma unroll
+    for (int cs = 0; cs < IMG_KPT; ++cs)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) bq[cs][q] = load_w(q, cs);
+
+    // ---- the image into LDS, stored xor 0x80 when unsigned (border: zero xor 0x80) ---------------
+    {
+      const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint8_t *>(p.x) + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
+      v4i px[IMG_PW];
+#pragma unroll
+      for (int r = 0; r < IMG_PW; ++r) {
+        // outside the image: an offset the descriptor rejects, which reads as zero
+        const bool in = col_in && (unsigned)(r - 1) < (unsigned)p.H;
+        const uint32_t off = in ? (uint32_t)(((r - 1) * p.W + (pcol - 1)) * IMG_C + 16 * ppiece) : 0x80000000u;
+        px[r] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < IMG_PW; ++r)
+        *reinterpret_cast<v4i *>(lds + (r * IMG_PW + pcol) * IMG_PITCH + 16 * ppiece) =
+            v4i{px[r].x ^ zx, px[r].y ^ zx, px[r].z ^ zx, px[r].w ^ zx};
+    }
+
+    // ---- accumulators start at acc0[n] -----------------------------------------------------
+    v16i acc[2][IMG_MB];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const v4i a0 = *reinterpret_cast<const v4i *>(p.acc0 + 32 * (2 * wave + q) + 16 * half + 4 * g);
+#pragma unroll
+        for (int j = 0; j < IMG_MB; ++j) {
+          acc[q][j][4 * g + 0] = a0.x; acc[q][j][4 * g + 1] = a0.y;
+          acc[q][j][4 * g + 2] = a0.z; acc[q][j][4 * g + 3] = a0.w;
+        }
+      }
+    __syncthreads();                    // the patch is complete
+
+    // ---- K loop: 9 taps x 8 slices of 32 channels; activation fragments one slice ahead ------
+    v4i xf[2][IMG_MB];
+#pragma unroll
+    for (int j = 0; j < IMG_MB; ++j) xf[0][j] = *(lds_v4i *)(arow[j]);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+#pragma unroll
+      for (int cs = 0; cs < IMG_KPT; ++cs) {
+        const int t = tap * IMG_KPT + cs;
+        const int cur = t & 1, nxt = cur ^ 1;
+        const int tap1 = (t + 1) / IMG_KPT, cs1 = (t + 1) % IMG_KPT;
+        const int off = ((tap1 / 3) * IMG_PW + tap1 % 3) * IMG_PITCH + 32 * cs1;
+        // One wave per SIMD: whatever is issued between two matrix instructions has to fit into
+        // the 32 cycles the first one runs, so the next slice's fragment reads and this slot's
+        // weight loads for the next tap go one at a time behind the matrix instructions.
+#pragma unroll
+        for (int i = 0; i < 2 * IMG_MB; ++i) {
+          const int q = i / IMG_MB, j = i % IMG_MB;
+          acc[q][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[cs][q], xf[cur][j], acc[q][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (i < IMG_MB) {
+            if (t + 1 < IMG_KS) xf[nxt][i] = *(lds_v4i *)(arow[i] + off);
+          } else if (i >= 2 * IMG_MB - 2) {
+            // (the slot's last use in this tap was the matrix instruction just issued)
+            const int q2 = i - (2 * IMG_MB - 2);
+            if (tap + 1 < 9 && q2 == 0) bq[cs][0] = load_w(0, t + IMG_KPT);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (tap + 1 < 9) bq[cs][1] = load_w(1, t + IMG_KPT);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __syncthreads();                    // every wave is done with the patch: it becomes the staging tile
+
+    // ---- epilogue: clip at the accumulator's scale, shift-and-pack, rows of 256 bytes in LDS ----
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int j = 0; j < IMG_MB; ++j) {
+        settle_matrix_result(acc[q][j]);
+        int v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
+        const v4i pk = shift_pack16(v, sh);
+        const int m = 32 * j + l32;
+        if (m < HW) *reinterpret_cast<v4i *>(lds + m * IMG_PITCH + 32 * (2 * wave + q) + 16 * half) = pk;
+      }
+    __syncthreads();
+    {
+      // the image's output is contiguous: piece i of it is piece i % 16 of staged row i / 16;
+      // pieces past the end have offsets the descriptor rejects
+      const __amdgpu_buffer_rsrc_t yres =
+          __builtin_amdgcn_make_buffer_rsrc(p.y + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
+#pragma unroll
+      for (int k = 0; k < IMG_MB * 32 * 16 / IMG_NT; ++k) {
+        const int i = tid + k * IMG_NT;
+        const v4i v = *reinterpret_cast<const v4i *>(lds + (i >> 4) * IMG_PITCH + 16 * (i & 15));
+        __builtin_amdgcn_raw_buffer_store_b128(v, yres, i * 16, 0, 0);
+      }
+    }
+    __syncthreads();                    // the staging tile is read out before the next image overwrites it
+  }
+}
+
+}  // namespace
+
+bool conv_img_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int H, int W, int shift,
+                         const void *x, const void *y) {
+  if (Cin != IMG_C || Cout != IMG_C || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
+  if (H < 1 || W < 1 || H > IMG_PW - 2 || W > IMG_PW - 2 || shift < 0) return false;
+  return ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
+}
+
+int launch_conv_img_weights(const int8_t *w, int8_t *wf, hipStream_t stream) {
+  if (!w || !wf || ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(wf)) & 15)) return (int)hipErrorInvalidValue;
+  const int pieces = (int)(CONV_IMG_W_BYTES / 16);
+  hipLaunchKernelGGL(conv_img_weights_kernel, dim3((pieces + 255) / 256), dim3(256), 0, stream, w, wf);
+  return (int)hipGetLastError();
+}
+
+int launch_conv_img(const ConvImgParams &p, hipStream_t stream) {
+  if (p.B <= 0) return 0;
+  if (!conv_img_applicable(IMG_C, IMG_C, 3, 3, 1, 1, 1, 1, p.H, p.W, p.shift, p.x, p.y) || p.lo > p.hi ||
+      ((reinterpret_cast<uintptr_t>(p.wf) | reinterpret_cast<uintptr_t>(p.acc0)) & 15))
+    return (int)hipErrorInvalidValue;
+  static unsigned long long done_mask = 0;                 // devices whose LDS limit has been raised
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+  if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv_img_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, IMG_LDS);
+    if (e != hipSuccess) return (int)e;
+    if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
+  }
+  const int grid = p.B < 256 ? p.B : 256;                    // one workgroup per CU, an image at a time
+  hipLaunchKernelGGL(conv_img_kernel, dim3(grid), dim3(IMG_NT), IMG_LDS, stream, p);
+  return (int)hipGetLastError();
+}
+
+}  // namespace f8

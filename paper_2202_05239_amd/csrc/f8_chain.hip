@@ -34,6 +34,7 @@
 
 #include "block_fused.h"
 #include "stem_pool.h"
+#include "conv_img.h"
 #include "f8_host.h"
 
 using namespace f8;
@@ -88,6 +89,11 @@ struct f8_chain {
   // tensors are still written).  Whether the kernel that can do this is chosen depends on the batch.
   std::vector<int> tail, tail_peer;    // per layer
   bool conv_tail = true;
+  // 3x3 layers the image-stationary kernel can take: byte offset of their weights in fragment order
+  // in the constants region (0: not such a layer).
+  std::vector<size_t> img_w_off;       // per layer
+  bool conv_img = true;
+  bool img_role(size_t i) const { return conv_img && img_w_off[i] != 0 && !(use_fusion() && fused[i].role != 0); }
   bool tail_in_fused_block(size_t i) const {
     const size_t a = tail[i] == 1 ? i : (size_t)tail_peer[i], b = tail[i] == 1 ? (size_t)tail_peer[i] : i;
     return use_fusion() && (fused[a].role != 0 || fused[b].role != 0);
@@ -307,6 +313,18 @@ struct f8_chain {
     switch (L.op) {
       case F8_OP_CONV: {
         const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
+        if (img_role(i) && conv_img_applicable(L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, g.H, g.W,
+                                               L.q.fl_x + L.q.fl_w - L.q.fl_y, src, dst)) {
+          ConvImgParams ip;
+          ip.x = static_cast<const uint8_t *>(src);
+          ip.wf = reinterpret_cast<const int8_t *>(static_cast<uint8_t *>(workspace) + img_w_off[i]);
+          ip.acc0 = acc0;
+          ip.y = static_cast<uint8_t *>(dst);
+          ip.B = batch; ip.H = g.H; ip.W = g.W;
+          ip.shift = L.q.fl_x + L.q.fl_w - L.q.fl_y; ip.lo = L.q.clip_lo; ip.hi = L.q.clip_hi;
+          ip.x_xor = L.q.x_type == F8_U8 ? 0x80808080u : 0u;
+          return launch_conv_img(ip, s) == 0 ? F8_OK : F8_ERR_DEVICE;
+        }
         if (narrow_rows(i, batch)) {
           // the kernel for few input channels reads the 24-channel rows and weights as they are
           return enqueue_conv(src, L.w, acc0, workspace, dst, res, g, L.q, s);
@@ -451,6 +469,15 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
         c->const_bytes += round256((size_t)L.Cout * g.R * g.S * sm.Cp);
       }
     }
+    size_t img_off = 0;
+    if (L.op == F8_OP_CONV && !sm.on && L.res < 0 && L.dst2 <= 0 && L.q.y_type != F8_S32 &&
+        (reinterpret_cast<uintptr_t>(L.w) & 15) == 0 &&
+        conv_img_applicable(L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, g.H, g.W,
+                            L.q.fl_x + L.q.fl_w - L.q.fl_y, nullptr, nullptr)) {
+      img_off = c->const_bytes;
+      c->const_bytes += round256(CONV_IMG_W_BYTES);
+    }
+    c->img_w_off.push_back(img_off);
     c->stem.push_back(sm);
     c->fused.push_back(Fused());
     c->tail.push_back(0);
@@ -460,6 +487,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   c->last_tensor = c->layers.back().dst;
   c->tensors[c->last_tensor].external = true;
   c->stem_pool = tuning().stem_pool.load() != 0;
+  c->conv_img = tuning().conv_img.load() != 0;
   // a stem whose only reader is a 3x3 stride-2 pad-1 max pool: both in one kernel
   for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
     const f8_layer_desc &L = c->layers[i], &M = c->layers[i + 1];
@@ -592,6 +620,9 @@ f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream
     int32_t *acc0 = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) + c->acc0_off[i]);
     const f8_status st = enqueue_fold(c->conv_weights(i, workspace), L.bias, acc0, c->conv_geom(i, 1), L.q, s);
     if (st != F8_OK) return st;
+    if (c->img_w_off[i] != 0 &&
+        launch_conv_img_weights(L.w, reinterpret_cast<int8_t *>(static_cast<uint8_t *>(workspace) + c->img_w_off[i]), s) != 0)
+      return F8_ERR_DEVICE;
   }
   for (size_t i = 0; i < c->layers.size(); ++i) {
     const Fused &f = c->fused[i];
@@ -793,7 +824,7 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       Geom gk = c->narrow_rows((size_t)layer, batch) ? g : c->conv_geom(layer, batch);
       gk.B = batch;
       gk.P = g.P; gk.Q = g.Q;
-      name = conv_kernel_name(gk, L.q, L.res >= 0);
+      name = c->img_role((size_t)layer) ? "conv3x3_img<256x256>" : conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       if (with_tail) {
