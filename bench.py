@@ -120,6 +120,13 @@ def single_layer_figures(torch, f8, wl, repeats):
     e1.record()
     torch.cuda.synchronize()
     out["mfma i8 register-only loop"] = {"TOPS": ops / (e0.elapsed_time(e1) * 1e-3) / 1e12}
+    # the same loop on operands whose every bit is pseudo-random, as real tensors' are
+    f8.f8_mfma_i8_yardstick_operands(sink, 2000, 1)
+    e0.record()
+    ops = sum(f8.f8_mfma_i8_yardstick_operands(sink, 20000, 1 + k) for k in range(5))
+    e1.record()
+    torch.cuda.synchronize()
+    out["mfma i8 register-only loop, random operand bytes"] = {"TOPS": ops / (e0.elapsed_time(e1) * 1e-3) / 1e12}
     return out
 
 

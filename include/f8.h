@@ -362,6 +362,11 @@ f8_status f8_copy_bytes(const void *src, void *dst, size_t bytes, void *stream);
  * multiply-accumulate). */
 #define F8_YARDSTICK_SINK_INTS (512 * 256)
 f8_status f8_mfma_i8_yardstick(int32_t *sink, int iters, double *ops, void *stream);
+/* The same loop with chosen operands: seed 0 gives the loop above (a few small constants per lane),
+ * any other seed fills every operand byte with pseudo-random bits, as real weights and activations
+ * would.  The two rates differ on this chip: its clock under matrix load depends on how many
+ * multiplier bits switch.  (Accumulators wrap; the sums mean nothing.) */
+f8_status f8_mfma_i8_yardstick_operands(int32_t *sink, int iters, uint32_t seed, double *ops, void *stream);
 /* Tuning switches: kernel choices only, never results (the parity tests force every tile variant
  * through them).  Names and defaults: "conv_variant" (-1 = automatic; >= 0 forces that tile
  * variant of the LDS-direct dense kernel), "conv_ws", "conv_ws_min" (768: smallest layer, in blocks

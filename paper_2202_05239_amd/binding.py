@@ -26,7 +26,7 @@ EXPORTS = [
     "f8_chain_tensor", "f8_chain_set_keep_all", "f8_chain_set_fusion", "f8_chain_set_streams", "f8_chain_destroy",
     "f8_chain_num_layers", "f8_chain_layer_info", "f8_chain_profile",
     "f8_clip_from_alpha", "f8_status_str", "f8_release_scratch", "f8_abi_version", "f8_copy_bytes",
-    "f8_tuning_set", "f8_tuning_get", "f8_mfma_i8_yardstick",
+    "f8_tuning_set", "f8_tuning_get", "f8_mfma_i8_yardstick", "f8_mfma_i8_yardstick_operands",
     "f8_fix_quant_f32", "f8_fix_quant_code", "f8_pact_f32", "f8_pact_fix_f32", "f8_eta_fix", "f8_opt_fl",
     "f8_tensor_stats_f32", "f8_quant_error_f32", "f8_fold_work_doubles", "f8_fold_conv_bn",
 ]
@@ -131,6 +131,7 @@ def lib():
     L.f8_fold_work_doubles.restype = sz
     L.f8_fold_conv_bn.argtypes = [vp] * 5 + [ctypes.POINTER(f8_fold_desc)] + [vp] * 5
     L.f8_mfma_i8_yardstick.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), vp]
+    L.f8_mfma_i8_yardstick_operands.argtypes = [vp, i32, ctypes.c_uint32, ctypes.POINTER(ctypes.c_double), vp]
     L.f8_tuning_set.argtypes = [ctypes.c_char_p, i32]
     L.f8_tuning_get.argtypes = [ctypes.c_char_p]
     L.f8_abi_version.restype = ctypes.c_int
@@ -148,6 +149,15 @@ def f8_mfma_i8_yardstick(sink, iters):
     assert sink.numel() >= F8_YARDSTICK_SINK_INTS and sink.dtype == torch.int32
     ops = ctypes.c_double()
     _check(lib().f8_mfma_i8_yardstick(_ptr(sink), int(iters), ctypes.byref(ops), _stream()), "f8_mfma_i8_yardstick")
+    return ops.value
+
+
+def f8_mfma_i8_yardstick_operands(sink, iters, seed):
+    """The same loop with pseudo-random operand bytes (seed != 0); returns its operation count."""
+    assert sink.numel() >= F8_YARDSTICK_SINK_INTS and sink.dtype == torch.int32
+    ops = ctypes.c_double()
+    _check(lib().f8_mfma_i8_yardstick_operands(_ptr(sink), int(iters), int(seed), ctypes.byref(ops), _stream()),
+           "f8_mfma_i8_yardstick_operands")
     return ops.value
 
 

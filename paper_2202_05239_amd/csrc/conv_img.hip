@@ -29,7 +29,8 @@ constexpr int IMG_PITCH = IMG_C + 16;               // bytes per patch pixel: 16
 constexpr int IMG_MB = 7;                           // 32-pixel blocks per image
 constexpr int IMG_KPT = IMG_C / 32;                 // K slices per tap
 constexpr int IMG_KS = 9 * IMG_KPT;                 // K slices in all
-constexpr int IMG_LDS = IMG_PW * IMG_PW * IMG_PITCH;
+// (one more patch row than the image needs: the fragment reads issued behind the last slice land there)
+constexpr int IMG_LDS = (IMG_PW + 1) * IMG_PW * IMG_PITCH;
 
 // Row r = 8 g + 4 h + j of a 32 x 32 matrix result lies in lane half h, register 4 g + j.  With channel
 // 16 h + 4 g + j as row r of the weight operand, registers 0..15 of a lane are the channels
@@ -125,17 +126,26 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
     __syncthreads();                    // the patch is complete
 
     // ---- K loop: 9 taps x 8 slices of 32 channels; activation fragments one slice ahead ------
+    // One pass of the loop is a row of the window: 3 taps x 8 slices, unrolled; the fragment
+    // addresses move down one patch row per pass.
     v4i xf[2][IMG_MB];
+    lds_u8 *ar[IMG_MB];
 #pragma unroll
-    for (int j = 0; j < IMG_MB; ++j) xf[0][j] = *(lds_v4i *)(arow[j]);
+    for (int j = 0; j < IMG_MB; ++j) {
+      ar[j] = arow[j];
+      xf[0][j] = *(lds_v4i *)(ar[j]);
+    }
+    constexpr int ROW_SLICES = 3 * IMG_KPT;
+#pragma unroll 1
+    for (int r = 0; r < 3; ++r) {
+      const int wbase = r * ROW_SLICES * 1024;
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-#pragma unroll
-      for (int cs = 0; cs < IMG_KPT; ++cs) {
-        const int t = tap * IMG_KPT + cs;
-        const int cur = t & 1, nxt = cur ^ 1;
-        const int tap1 = (t + 1) / IMG_KPT, cs1 = (t + 1) % IMG_KPT;
-        const int off = ((tap1 / 3) * IMG_PW + tap1 % 3) * IMG_PITCH + 32 * cs1;
+      for (int sc = 0; sc < ROW_SLICES; ++sc) {
+        const int cs = sc % IMG_KPT;
+        const int cur = sc & 1, nxt = cur ^ 1;
+        // the next slice: same row of the window, or the first slice of the next row (after the
+        // last slice of all this reads rows of LDS that exist for the purpose and are not used)
+        const int off = sc + 1 < ROW_SLICES ? ((sc + 1) / IMG_KPT) * IMG_PITCH + 32 * ((sc + 1) % IMG_KPT) : IMG_PW * IMG_PITCH;
         // One wave per SIMD: whatever is issued between two matrix instructions has to fit into
         // the 32 cycles the first one runs, so the next slice's fragment reads and this slot's
         // weight loads for the next tap go one at a time behind the matrix instructions.
@@ -144,18 +154,18 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
           const int q = i / IMG_MB, j = i % IMG_MB;
           acc[q][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[cs][q], xf[cur][j], acc[q][j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
-          if (i < IMG_MB) {
-            if (t + 1 < IMG_KS) xf[nxt][i] = *(lds_v4i *)(arow[i] + off);
-          } else if (i >= 2 * IMG_MB - 2) {
-            // (the slot's last use in this tap was the matrix instruction just issued)
-            const int q2 = i - (2 * IMG_MB - 2);
-            if (tap + 1 < 9 && q2 == 0) bq[cs][0] = load_w(0, t + IMG_KPT);
-          }
+          if (i < IMG_MB) xf[nxt][i] = *(lds_v4i *)(ar[i] + off);
+          // (the slot's last use in this tap was a matrix instruction already issued)
+          if (i == 2 * IMG_MB - 2 && (sc < ROW_SLICES - IMG_KPT || r < 2))
+            bq[cs][0] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (sc + IMG_KPT) * 1024, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (tap + 1 < 9) bq[cs][1] = load_w(1, t + IMG_KPT);
+        if (sc < ROW_SLICES - IMG_KPT || r < 2)
+          bq[cs][1] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (IMG_KS + sc + IMG_KPT) * 1024, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
+#pragma unroll
+      for (int j = 0; j < IMG_MB; ++j) ar[j] += IMG_PW * IMG_PITCH;
     }
     __syncthreads();                    // every wave is done with the patch: it becomes the staging tile
 
