@@ -16,6 +16,7 @@ const TuningName kTuningNames[] = {
     {"pw_ws", "F8_PW_WS", &Tuning::pw_ws},                       {"pw_small", "F8_PW_SMALL", &Tuning::pw_small},
     {"xcd_remap", "F8_XCD_REMAP", &Tuning::xcd_remap},           {"stem_pool", "F8_STEM_POOL", &Tuning::stem_pool},
     {"conv_tail", "F8_CONV_TAIL", &Tuning::conv_tail},         {"conv_img", "F8_CONV_IMG", &Tuning::conv_img},
+    {"pw_wide", "F8_PW_WIDE", &Tuning::pw_wide},
 };
 }  // namespace
 
@@ -112,6 +113,16 @@ static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void 
   return pw_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
 }
 
+// And the 1x1 layers with 256 or 512 input channels and at least as many output channels per workgroup
+// as its four waves hold weights for (the closing layers of the third and fourth ResNet stage).
+static bool use_pw_wide(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
+                        const f8_quant &q, const void *y2) {
+  if (!tuning().pw_wide.load(std::memory_order_relaxed) || y2 || q.y_type == F8_S32 || (res && q.res_type == F8_S32)) return false;
+  // it pays once every workgroup walks over several blocks of 32 pixels: blocks x channel slices >= 4 x 512
+  if ((g.Cin != 256 && g.Cin != 512) || (long long)g.B * g.H * g.W / 32 * (g.Cout / (4 * (16384 / g.Cin))) < 2048) return false;
+  return pw_wide_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
+}
+
 // And the 1x1 layers with 16 or 32 input and 96 / 144 / 192 output channels (MobileNetV2's first expand layers).
 static bool use_pw_small(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
                          const f8_quant &q, const void *y2) {
@@ -158,6 +169,21 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
     pp.res_d = res ? q.fl_x + q.fl_w - q.fl_res : 0;
     pp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
     return launch_pw_ws(pp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+  }
+  if (use_pw_wide(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0) {
+    PwWideParams pp;
+    pp.x = static_cast<const uint8_t *>(x);
+    pp.w = w;
+    pp.acc0 = acc0;
+    pp.res = static_cast<const uint8_t *>(res);
+    pp.y = static_cast<uint8_t *>(y);
+    pp.M = (long long)g.B * g.H * g.W;
+    pp.K = g.Cin; pp.N = g.Cout;
+    pp.shift = q.fl_x + q.fl_w - q.fl_y; pp.lo = q.clip_lo; pp.hi = q.clip_hi;
+    pp.res_signed = q.res_type == F8_S8;
+    pp.res_d = res ? q.fl_x + q.fl_w - q.fl_res : 0;
+    pp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
+    return launch_pw_wide(pp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
   }
   if (use_conv_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0) {
     ConvWsParams wp;
@@ -240,6 +266,8 @@ const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
     return names[g.Cin == 16 ? 0 : (g.Cin == 24 ? 1 : 2)][g.Cout == 96 ? 0 : (g.Cout == 144 ? 1 : 2)];
   }
   if (!(has_res && q.res_type == F8_S32) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
+  if (!(has_res && q.res_type == F8_S32) && use_pw_wide(nullptr, nullptr, nullptr, nullptr, g, q, nullptr))
+    return g.Cin == 256 ? "pw1x1_wide<256>" : "pw1x1_wide<512>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";
   ConvParams p;
   p.x = nullptr; p.w = nullptr; p.y = nullptr; p.res = has_res ? &p : nullptr;   // aligned stand-ins

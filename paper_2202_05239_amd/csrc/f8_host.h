@@ -11,6 +11,7 @@
 #include "conv_igemm.h"
 #include "conv_ws.h"
 #include "pw_ws.h"
+#include "pw_wide.h"
 #include "pw_small.h"
 #include "dwconv_pool.h"
 
@@ -25,6 +26,7 @@ struct Tuning {
   std::atomic<int> conv_ws_min{768};    // ... from this many 128-pixel (64 channels) or 64-pixel (128 channels) blocks on
   std::atomic<int> pw_ws{1};           // weights-stationary 1x1 kernel (64 -> 256)
   std::atomic<int> pw_small{1};        // streaming 1x1 kernel for few input channels
+  std::atomic<int> pw_wide{1};         // weights-stationary 1x1 kernel for 256 / 512 input channels
   std::atomic<int> xcd_remap{1};       // XCD-aware tile order
   std::atomic<int> stem_pool{1};       // chain: stem and max pool as one kernel
   std::atomic<int> conv_tail{1};       // chain: next block's first 1x1 layer computed behind a closing layer

@@ -330,6 +330,33 @@ def test_weights_stationary_1x1_64_to_256(oracle):
     assert not any(chain.layer_info(i, 4)[0].startswith("pw1x1_ws") for i in range(len(net.layers)))
 
 
+def test_weights_stationary_1x1_256_and_512_inputs(oracle):
+    """1x1 layers with 256 or 512 input channels and whole slices of output channels at large batch (the
+    closing layers of the third and fourth ResNet stage) take a kernel whose waves keep the weights in
+    registers: with and without residual, residual scales above and below the accumulator's, type
+    combinations, pixel counts that leave a ragged last block, a shift of zero, clips inside the range."""
+    from concurrent.futures import ThreadPoolExecutor
+    rng = np.random.default_rng(25600)
+    # (sizes from which the library picks this kernel: blocks of 32 pixels x channel slices >= 1024)
+    for K, N, B, H, W, xt, yt, rt, shift, clip in ((256, 1024, 90, 14, 14, "u8", "u8", "u8", 10, None), (256, 1024, 531, 5, 13, "s8", "s8", "s8", 8, (-50, 90)),
+                                                    (512, 2048, 131, 7, 7, "u8", "u8", "u8", 11, None), (512, 512, 2055, 1, 8, "u8", "s8", None, 9, None),
+                                                    (256, 1024, 41, 19, 23, "s8", "u8", "s8", 0, (3, 200)), (512, 512, 271, 9, 7, "u8", "u8", "u8", 12, (0, 1)),
+                                                    (512, 1024, 2, 112, 37, "u8", "u8", None, 10, None), (256, 2048, 33, 31, 9, "u8", "u8", "u8", 9, None)):
+        for rep in range(2 if rt else 1):      # two draws of the residual's fractional length
+            x, L, res = wl.random_conv_case(rng, B, H, W, K, N, 1, 1, 1, 0, xt, yt, rt, shift=shift, clip=clip)
+            parts = np.array_split(np.arange(B), min(B, host_threads()))
+            with ThreadPoolExecutor(len(parts)) as ex:
+                outs = list(ex.map(lambda idx: oracle.conv2d_fixed(np.ascontiguousarray(x[idx]), L.w, L.bias, L, (1, 1), (0, 0),
+                                                                   None if res is None else np.ascontiguousarray(res[idx])), parts))
+            assert_same(gpu_layer(L, x, res), np.concatenate(outs), "pw wide %s" % str((K, N, B, H, W, xt, yt, rt, shift, L.fl_res)))
+    _, net = wl.config4(batch=1)
+    chain = f8.Chain(net)
+    names = [chain.layer_info(i, 256)[0] for i in range(len(net.layers))]
+    # the six closing layers of stage 3 and the three of stage 4
+    assert names.count("pw1x1_wide<256>") == 6 and names.count("pw1x1_wide<512>") == 3, names
+    assert not any(chain.layer_info(i, 4)[0].startswith("pw1x1_wide") for i in range(len(net.layers)))
+
+
 def test_1x1_layer_computed_behind_the_64_to_256_layer(oracle):
     """A 1x1 64 -> 256 layer followed by a 1x1 256 -> 64 layer that reads its output (the hand-over
     between two bottleneck blocks): at large batch one launch computes both, the second from each
