@@ -101,6 +101,17 @@ def single_layer_figures(torch, f8, wl, repeats):
             out["%s %s" % (key, r["layer"])] = {k: r[k] for k in
                                                 ("kernel", "us", "TOPS", "pct_mfma_peak", "alg_GBs", "pct_hbm_peak", "binds")}
         chain.close()
+    # a layer of a single tile, timed the same way: what one dependent launch costs on its own
+    import numpy as np
+    rng = np.random.default_rng(7)
+    nb = wl._NetBuilder("one_tile", rng, 8, 64, "u8", 5, (5, 9), (2, 6), False)
+    nb.conv("conv1x1", 0, 64, 1, 1, 0)
+    xt = torch.from_numpy(wl.draw_u8(rng, (1, 8, 8, 64))).to("cuda")
+    chain = f8.Chain(nb.net).prepare(1)
+    y = torch.empty((1,) + chain.out_shape, dtype=chain.out_dtype, device="cuda")
+    chain.run(xt, y)
+    out["one-tile layer (floor of a launch in this timing)"] = {"us": chain.profile(xt, y, repeats=repeats)[0] * 1e3}
+    chain.close()
     n = 1 << 30
     a = torch.empty(n, dtype=torch.uint8, device="cuda")
     b = torch.empty(n, dtype=torch.uint8, device="cuda")

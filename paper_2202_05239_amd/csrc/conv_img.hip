@@ -15,6 +15,8 @@
 // accumulator blocks (224 registers) per lane.
 #include "conv_img.h"
 
+#include <type_traits>
+
 namespace f8 {
 namespace {
 
@@ -39,15 +41,16 @@ __host__ __device__ inline int frag_channel(int r) { return 16 * ((r >> 2) & 1) 
 
 // Piece i (16 bytes) of the weights in fragment order: fragment (32-channel block nb, K slice t) is
 // 64 pieces, piece `lane` = the 16 bytes lane (l32, half) feeds to the matrix instruction: channel
-// 32 nb + frag_channel(l32), tap t / 8, input channels 32 (t % 8) + 16 half .. + 16.
-__global__ __launch_bounds__(256) void conv_img_weights_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wf) {
+// 32 nb + frag_channel(l32), tap t / (C / 32), input channels 32 (t % (C / 32)) + 16 half .. + 16.
+__global__ __launch_bounds__(256) void conv_img_weights_kernel(const int8_t *__restrict__ w, int8_t *__restrict__ wf, int C) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= (int)(CONV_IMG_W_BYTES / 16)) return;
-  const int lane = i & 63, t = (i >> 6) % IMG_KS, nb = (i >> 6) / IMG_KS;
+  if (i >= C * 9 * C / 16) return;
+  const int kpt = C / 32, ks = 9 * kpt;
+  const int lane = i & 63, t = (i >> 6) % ks, nb = (i >> 6) / ks;
   const int l32 = lane & 31, half = lane >> 5;
-  const int n = 32 * nb + frag_channel(l32), tap = t / IMG_KPT, cs = t % IMG_KPT;
+  const int n = 32 * nb + frag_channel(l32), tap = t / kpt, cs = t % kpt;
   *reinterpret_cast<v4i *>(wf + (size_t)i * 16) =
-      *reinterpret_cast<const v4i *>(w + ((size_t)n * 9 + tap) * IMG_C + 32 * cs + 16 * half);
+      *reinterpret_cast<const v4i *>(w + ((size_t)n * 9 + tap) * C + 32 * cs + 16 * half);
 }
 
 __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams p) {
@@ -199,38 +202,197 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
   }
 }
 
+
+// ---- 128 -> 128 channels, images up to 28 x 28 ---------------------------------------------------
+// The same scheme with two passes over the image: 784 output pixels are 25 blocks of 32 rows, more
+// accumulators than a workgroup has registers for.  The four waves are 2 (halves of the pass's
+// blocks) x 2 (halves of the channels): 7 x 2 accumulator blocks per wave in the first pass (blocks
+// 0..13 of the image), 6 x 2 in the second (blocks 14..25, the last one or two empty); the patch
+// stays where it is between the passes, and the weights are streamed once per pass.  The patch
+// cannot double as the staging tile here, so every wave passes its results through a small tile of
+// its own (32 pixels x its 64 channels) and stores 64-byte runs.
+constexpr int I2_C = 128;
+constexpr int I2_PW = 30;                           // patch rows and columns (image + border)
+constexpr int I2_PITCH = I2_C + 16;
+constexpr int I2_KPT = I2_C / 32;
+constexpr int I2_KS = 9 * I2_KPT;
+constexpr int I2_TPITCH = 64 + 16;                  // staging tile row pitch
+constexpr int I2_PATCH = (I2_PW + 2) * I2_PW * I2_PITCH;   // (two rows more: the reads issued behind the last slice land there)
+constexpr int I2_LDS = I2_PATCH + 4 * 32 * I2_TPITCH;
+constexpr int I2_MB0 = 7, I2_MB1 = 6;               // blocks per wave in the two passes
+
+__global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int HW = p.H * p.W;
+  const int image_bytes = HW * I2_C;
+  lds_u8 *patch = (lds_u8 *)lds;
+  uint8_t *tile = lds + I2_PATCH + wave * (32 * I2_TPITCH);
+
+  // this wave's weights: channel blocks 2 wn and 2 wn + 1
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t *>(p.wf) + (size_t)wn * (2 * I2_KS * 1024), 0, 2 * I2_KS * 1024, 0x00027000);
+  const int lane16 = lane * 16;
+
+  // Patch role: column tid / 8 of the patch (the last two of 32 idle), piece tid % 8 of its pixels.
+  const int pcol = tid >> 3, ppiece = tid & 7;
+  const bool col_in = (unsigned)(pcol - 1) < (unsigned)p.W;
+  const int zx = (int)p.x_xor;
+  const ScaledClip c1 = scaled_clip(p.lo, p.hi, p.shift);
+  const int sh = p.shift;
+  // Row-piece role of the staging tile: 4 pieces per row, 16 rows per instruction.
+  const int trow = lane >> 2, tpiece = lane & 3;
+
+  for (int img = blockIdx.x; img < p.B; img += gridDim.x) {
+    // ---- the image into LDS, stored xor 0x80 when unsigned (border: zero xor 0x80) ---------------
+    {
+      const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint8_t *>(p.x) + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
+#pragma unroll 1
+      for (int r0 = 0; r0 < I2_PW; r0 += 10) {
+        v4i px[10];
+#pragma unroll
+        for (int k = 0; k < 10; ++k) {
+          const int r = r0 + k;
+          // outside the image: an offset the descriptor rejects, which reads as zero
+          const bool in = col_in && (unsigned)(r - 1) < (unsigned)p.H;
+          const uint32_t off = in ? (uint32_t)(((r - 1) * p.W + (pcol - 1)) * I2_C + 16 * ppiece) : 0x80000000u;
+          px[k] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+        }
+        if (pcol < I2_PW) {
+#pragma unroll
+          for (int k = 0; k < 10; ++k)
+            *reinterpret_cast<v4i *>(lds + ((r0 + k) * I2_PW + pcol) * I2_PITCH + 16 * ppiece) =
+                v4i{px[k].x ^ zx, px[k].y ^ zx, px[k].z ^ zx, px[k].w ^ zx};
+        }
+      }
+    }
+    __syncthreads();                    // the patch is complete
+
+    const __amdgpu_buffer_rsrc_t yres =
+        __builtin_amdgcn_make_buffer_rsrc(p.y + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
+    // One pass: MBP blocks of 32 output pixels starting at block `first`, this wave's 64 channels.
+    auto run_pass = [&](auto mbp_tag, int first) {
+      constexpr int MBP = decltype(mbp_tag)::value;
+      lds_u8 *ar[MBP];
+#pragma unroll
+      for (int j = 0; j < MBP; ++j) {
+        const int m = 32 * (first + j) + l32;
+        const int oy = m < HW ? m / p.W : 0, ox = m < HW ? m - oy * p.W : 0;
+        ar[j] = patch + (oy * I2_PW + ox) * I2_PITCH + 16 * half;
+      }
+      v4i bq[I2_KPT][2];
+#pragma unroll
+      for (int cs = 0; cs < I2_KPT; ++cs)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) bq[cs][q] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, (q * I2_KS + cs) * 1024, 0);
+      v16i acc[2][MBP];
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const v4i a0 = *reinterpret_cast<const v4i *>(p.acc0 + 32 * (2 * wn + q) + 16 * half + 4 * g);
+#pragma unroll
+          for (int j = 0; j < MBP; ++j) {
+            acc[q][j][4 * g + 0] = a0.x; acc[q][j][4 * g + 1] = a0.y;
+            acc[q][j][4 * g + 2] = a0.z; acc[q][j][4 * g + 3] = a0.w;
+          }
+        }
+      v4i xf[2][MBP];
+#pragma unroll
+      for (int j = 0; j < MBP; ++j) xf[0][j] = *(lds_v4i *)(ar[j]);
+      constexpr int ROW_SLICES = 3 * I2_KPT;
+#pragma unroll 1
+      for (int r = 0; r < 3; ++r) {
+        const int wbase = r * ROW_SLICES * 1024;
+#pragma unroll
+        for (int sc = 0; sc < ROW_SLICES; ++sc) {
+          const int cs = sc % I2_KPT;
+          const int cur = sc & 1, nxt = cur ^ 1;
+          const int off = sc + 1 < ROW_SLICES ? ((sc + 1) / I2_KPT) * I2_PITCH + 32 * ((sc + 1) % I2_KPT) : I2_PW * I2_PITCH;
+#pragma unroll
+          for (int i = 0; i < 2 * MBP; ++i) {
+            const int q = i / MBP, j = i % MBP;
+            acc[q][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[cs][q], xf[cur][j], acc[q][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i < MBP) xf[nxt][i] = *(lds_v4i *)(ar[i] + off);
+            if (i == 2 * MBP - 2 && (sc < ROW_SLICES - I2_KPT || r < 2))
+              bq[cs][0] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (sc + I2_KPT) * 1024, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (sc < ROW_SLICES - I2_KPT || r < 2)
+            bq[cs][1] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (I2_KS + sc + I2_KPT) * 1024, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < MBP; ++j) ar[j] += I2_PW * I2_PITCH;
+      }
+      // epilogue, a block of 32 pixels at a time through the wave's own tile: clip at the accumulator's
+      // scale, shift-and-pack, then rows of 64 bytes to memory (rows past the image are offsets the
+      // descriptor rejects)
+#pragma unroll
+      for (int j = 0; j < MBP; ++j) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          settle_matrix_result(acc[q][j]);
+          int v[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
+          *reinterpret_cast<v4i *>(tile + l32 * I2_TPITCH + 32 * q + 16 * half) = shift_pack16(v, sh);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const int row = 16 * k + trow;
+          const v4i o = *reinterpret_cast<const v4i *>(tile + row * I2_TPITCH + 16 * tpiece);
+          __builtin_amdgcn_raw_buffer_store_b128(o, yres, (32 * (first + j) + row) * I2_C + 64 * wn + 16 * tpiece, 0, 0);
+        }
+      }
+    };
+    run_pass(std::integral_constant<int, I2_MB0>{}, wm * I2_MB0);
+    run_pass(std::integral_constant<int, I2_MB1>{}, 2 * I2_MB0 + wm * I2_MB1);
+    __syncthreads();                    // every wave is done with the patch before the next image overwrites it
+  }
+}
+
 }  // namespace
 
 bool conv_img_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int H, int W, int shift,
                          const void *x, const void *y) {
-  if (Cin != IMG_C || Cout != IMG_C || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
-  if (H < 1 || W < 1 || H > IMG_PW - 2 || W > IMG_PW - 2 || shift < 0) return false;
+  if (Cin != Cout || (Cin != IMG_C && Cin != I2_C) || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
+  const int most = (Cin == IMG_C ? IMG_PW : I2_PW) - 2;
+  if (H < 1 || W < 1 || H > most || W > most || shift < 0) return false;
   return ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
 }
 
-int launch_conv_img_weights(const int8_t *w, int8_t *wf, hipStream_t stream) {
-  if (!w || !wf || ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(wf)) & 15)) return (int)hipErrorInvalidValue;
-  const int pieces = (int)(CONV_IMG_W_BYTES / 16);
-  hipLaunchKernelGGL(conv_img_weights_kernel, dim3((pieces + 255) / 256), dim3(256), 0, stream, w, wf);
+int launch_conv_img_weights(const int8_t *w, int8_t *wf, int C, hipStream_t stream) {
+  if (!w || !wf || (C != IMG_C && C != I2_C) || ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(wf)) & 15))
+    return (int)hipErrorInvalidValue;
+  const int pieces = C * 9 * C / 16;
+  hipLaunchKernelGGL(conv_img_weights_kernel, dim3((pieces + 255) / 256), dim3(256), 0, stream, w, wf, C);
   return (int)hipGetLastError();
 }
 
 int launch_conv_img(const ConvImgParams &p, hipStream_t stream) {
   if (p.B <= 0) return 0;
-  if (!conv_img_applicable(IMG_C, IMG_C, 3, 3, 1, 1, 1, 1, p.H, p.W, p.shift, p.x, p.y) || p.lo > p.hi ||
+  if (!conv_img_applicable(p.C, p.C, 3, 3, 1, 1, 1, 1, p.H, p.W, p.shift, p.x, p.y) || p.lo > p.hi ||
       ((reinterpret_cast<uintptr_t>(p.wf) | reinterpret_cast<uintptr_t>(p.acc0)) & 15))
     return (int)hipErrorInvalidValue;
-  static unsigned long long done_mask = 0;                 // devices whose LDS limit has been raised
+  static unsigned long long done_mask[2] = {0, 0};         // devices whose LDS limit has been raised, per kernel
+  const bool wide = p.C == IMG_C;
+  const void *fn = wide ? reinterpret_cast<const void *>(conv_img_kernel) : reinterpret_cast<const void *>(conv_img128_kernel);
+  const int lds_bytes = wide ? IMG_LDS : I2_LDS;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
-  if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv_img_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, IMG_LDS);
+  if (dev < 0 || dev > 63 || !((done_mask[wide] >> dev) & 1ull)) {
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return (int)e;
-    if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
+    if (dev >= 0 && dev <= 63) done_mask[wide] |= 1ull << dev;
   }
   const int grid = p.B < 256 ? p.B : 256;                    // one workgroup per CU, an image at a time
-  hipLaunchKernelGGL(conv_img_kernel, dim3(grid), dim3(IMG_NT), IMG_LDS, stream, p);
+  if (wide) hipLaunchKernelGGL(conv_img_kernel, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
+  else hipLaunchKernelGGL(conv_img128_kernel, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
   return (int)hipGetLastError();
 }
 

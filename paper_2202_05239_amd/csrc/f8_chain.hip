@@ -320,7 +320,7 @@ struct f8_chain {
           ip.wf = reinterpret_cast<const int8_t *>(static_cast<uint8_t *>(workspace) + img_w_off[i]);
           ip.acc0 = acc0;
           ip.y = static_cast<uint8_t *>(dst);
-          ip.B = batch; ip.H = g.H; ip.W = g.W;
+          ip.B = batch; ip.H = g.H; ip.W = g.W; ip.C = L.Cin;
           ip.shift = L.q.fl_x + L.q.fl_w - L.q.fl_y; ip.lo = L.q.clip_lo; ip.hi = L.q.clip_hi;
           ip.x_xor = L.q.x_type == F8_U8 ? 0x80808080u : 0u;
           return launch_conv_img(ip, s) == 0 ? F8_OK : F8_ERR_DEVICE;
@@ -475,7 +475,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
         conv_img_applicable(L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, g.H, g.W,
                             L.q.fl_x + L.q.fl_w - L.q.fl_y, nullptr, nullptr)) {
       img_off = c->const_bytes;
-      c->const_bytes += round256(CONV_IMG_W_BYTES);
+      c->const_bytes += round256(conv_img_weight_bytes(L.Cin));
     }
     c->img_w_off.push_back(img_off);
     c->stem.push_back(sm);
@@ -621,7 +621,7 @@ f8_status f8_chain_prepare(f8_chain *c, void *workspace, int batch, void *stream
     const f8_status st = enqueue_fold(c->conv_weights(i, workspace), L.bias, acc0, c->conv_geom(i, 1), L.q, s);
     if (st != F8_OK) return st;
     if (c->img_w_off[i] != 0 &&
-        launch_conv_img_weights(L.w, reinterpret_cast<int8_t *>(static_cast<uint8_t *>(workspace) + c->img_w_off[i]), s) != 0)
+        launch_conv_img_weights(L.w, reinterpret_cast<int8_t *>(static_cast<uint8_t *>(workspace) + c->img_w_off[i]), L.Cin, s) != 0)
       return F8_ERR_DEVICE;
   }
   for (size_t i = 0; i < c->layers.size(); ++i) {
@@ -824,7 +824,7 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       Geom gk = c->narrow_rows((size_t)layer, batch) ? g : c->conv_geom(layer, batch);
       gk.B = batch;
       gk.P = g.P; gk.Q = g.Q;
-      name = c->img_role((size_t)layer) ? "conv3x3_img<256x256>" : conv_kernel_name(gk, L.q, L.res >= 0);
+      name = c->img_role((size_t)layer) ? (L.Cin == 256 ? "conv3x3_img<256x256>" : "conv3x3_img<128x128>") : conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       if (with_tail) {

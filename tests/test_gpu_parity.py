@@ -266,41 +266,52 @@ def test_weights_stationary_3x3_64(oracle):
     _, net = wl.config4(batch=1)
     chain = f8.Chain(net)
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 3
-    assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<128x128>") == 3
     assert [chain.layer_info(i, 2)[0] for i in range(len(net.layers))].count("conv3x3_ws<64x64>") == 0
+    # (in a chain the 128-channel layers go to the image-stationary kernel unless that is switched off)
+    f8.f8_tuning_set("conv_img", 0)
+    try:
+        chain = f8.Chain(net)
+        assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_ws<128x128>") == 3
+    finally:
+        f8.f8_tuning_set("conv_img", 1)
 
 
 def test_image_stationary_3x3_256(oracle):
-    """3x3 256 -> 256 stride-1 layers on images of at most 14 x 14 pixels take, in a chain, a kernel
+    """3x3 stride-1 layers with 256 -> 256 channels on images of at most 14 x 14 pixels, and with
+    128 -> 128 channels on images of at most 28 x 28, take, in a chain, a kernel
     that keeps one whole image in LDS and streams the weights (stored in fragment order when the
     workspace is prepared): image sizes with full, ragged and single blocks of pixels, batches
     below and above the number of workgroups, unsigned and signed inputs and outputs, clips inside
     the range; every image against the oracle, and against the general kernel."""
-    for k, (hw, batch, x_type, relu1, relu2) in enumerate(((14, 5, "u8", True, True), (14, 300, "s8", True, False),
-                                                            (13, 257, "u8", False, True), (7, 64, "u8", True, True),
-                                                            (3, 9, "s8", False, False), (1, 2, "u8", True, True))):
+    for k, (C, hw, batch, x_type, relu1, relu2) in enumerate(((256, 14, 5, "u8", True, True), (256, 14, 300, "s8", True, False),
+                                                               (256, 13, 257, "u8", False, True), (256, 7, 64, "u8", True, True),
+                                                               (256, 3, 9, "s8", False, False), (256, 1, 2, "u8", True, True),
+                                                               (128, 28, 5, "u8", True, True), (128, 28, 259, "s8", True, False),
+                                                               (128, 27, 33, "u8", False, True), (128, 21, 17, "u8", True, True),
+                                                               (128, 15, 70, "s8", False, False), (128, 2, 3, "u8", True, True))):
         rng = np.random.default_rng(1400 + k)
-        b = wl._NetBuilder("img%d" % k, rng, hw, 256, x_type, 5, (5, 9), (2, 6), True)
-        a = b.conv("first", 0, 256, 3, 1, 1, relu=relu1)
-        b.conv("second", a, 256, 3, 1, 1, relu=relu2)
+        b = wl._NetBuilder("img%d" % k, rng, hw, C, x_type, 5, (5, 9), (2, 6), True)
+        a = b.conv("first", 0, C, 3, 1, 1, relu=relu1)
+        b.conv("second", a, C, 3, 1, 1, relu=relu2)
         net = b.net
-        x = wl.draw_u8(rng, (batch, hw, hw, 256)) if x_type == "u8" else wl.draw_s8_normal(rng, (batch, hw, hw, 256), 5)
+        x = wl.draw_u8(rng, (batch, hw, hw, C)) if x_type == "u8" else wl.draw_s8_normal(rng, (batch, hw, hw, C), 5)
         names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(2)]
-        assert names == ["conv3x3_img<256x256>"] * 2, names
+        assert names == ["conv3x3_img<%dx%d>" % (C, C)] * 2, names
         out = check_network(oracle, x, net, list(range(batch)), "image-stationary 3x3, case %d" % k, lean_is_smaller=False)
         f8.f8_tuning_set("conv_img", 0)
         try:
             plain = f8.Chain(net).prepare(batch)
-            assert "conv3x3_img<256x256>" not in [plain.layer_info(i, batch)[0] for i in range(2)]
+            assert not any(plain.layer_info(i, batch)[0].startswith("conv3x3_img") for i in range(2))
             other = plain.run(torch.from_numpy(x).to(DEV))
             torch.cuda.synchronize()
             assert torch.equal(other, out), "general kernel, case %d" % k
         finally:
             f8.f8_tuning_set("conv_img", 1)
-    # the six stride-1 3x3 layers of the full-size network's third stage minus the strided first one
+    # the stride-1 3x3 layers of the full-size network's third (five) and second (three) stage
     _, net = wl.config4(batch=1)
     chain = f8.Chain(net)
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_img<256x256>") == 5
+    assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_img<128x128>") == 3
 
 
 def test_weights_stationary_1x1_64_to_256(oracle):
