@@ -203,41 +203,54 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
 }
 
 
-// ---- 128 -> 128 channels, images up to 28 x 28 ---------------------------------------------------
-// The same scheme with two passes over the image: 784 output pixels are 25 blocks of 32 rows, more
-// accumulators than a workgroup has registers for.  The four waves are 2 (halves of the pass's
-// blocks) x 2 (halves of the channels): 7 x 2 accumulator blocks per wave in the first pass (blocks
-// 0..13 of the image), 6 x 2 in the second (blocks 14..25, the last one or two empty); the patch
-// stays where it is between the passes, and the weights are streamed once per pass.  The patch
-// cannot double as the staging tile here, so every wave passes its results through a small tile of
-// its own (32 pixels x its 64 channels) and stores 64-byte runs.
-constexpr int I2_C = 128;
-constexpr int I2_PW = 30;                           // patch rows and columns (image + border)
-constexpr int I2_PITCH = I2_C + 16;
-constexpr int I2_KPT = I2_C / 32;
-constexpr int I2_KS = 9 * I2_KPT;
-constexpr int I2_TPITCH = 64 + 16;                  // staging tile row pitch
-constexpr int I2_PATCH = (I2_PW + 2) * I2_PW * I2_PITCH;   // (two rows more: the reads issued behind the last slice land there)
-constexpr int I2_LDS = I2_PATCH + 4 * 32 * I2_TPITCH;
-constexpr int I2_MB0 = 7, I2_MB1 = 6;               // blocks per wave in the two passes
+// ---- 128 -> 128 channels, images up to 28 pixels wide -----------------------------------------------
+// The same scheme on bands of up to 28 image rows, two passes per band: 28 x 28 output pixels are 25
+// blocks of 32 rows, more accumulators than a workgroup has registers for.  The four waves are 2
+// (halves of a pass's blocks) x 2 (halves of the channels); 7 x 2 accumulator blocks per wave in the
+// first pass (blocks 0..13 of the band), 6 x 2 in the second (blocks 14..25); the weights are
+// streamed once per pass.  The patch stays where it is between the passes.
+// (The same with 64 channels on bands of 28 x 56 pixels, every wave holding all weights in registers,
+// measured 45 us against the 35 us of the weights-stationary kernel on the 56 x 56 layers, and is
+// not built.)  It cannot double as the staging tile here, so
+// every wave passes its results through a small tile of its own (32 pixels x its 64 channels) and
+// stores 64-byte runs.
+template <int C> struct BandShape {
+  static_assert(C == 128, "one instantiation");
+  static constexpr int WM = 2, WN = 4 / WM;
+  static constexpr int PCOLS = 30;                      // patch columns (image + border)
+  static constexpr int BR = 28;                         // output rows per band
+  static constexpr int PROWS = BR + 2;
+  static constexpr int PITCH = C + 16;                  // bytes per patch pixel: 16 neighbouring pixels spread over all banks
+  static constexpr int KPT = C / 32;                    // K slices per tap
+  static constexpr int KS = 9 * KPT;
+  static constexpr int TPITCH = 64 + 16;                // staging tile row pitch
+  // (two patch rows more, where the reads issued behind the last slice land)
+  static constexpr int PATCH = (PROWS + 2) * PCOLS * PITCH;
+  static constexpr int LDS = PATCH + 4 * 32 * TPITCH;
+  static constexpr int MB0 = 7, MB1 = 6;                // blocks per wave in the two passes
+  static constexpr int PPP = C / 16;                    // 16-byte pieces per pixel
+};
 
-__global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgParams p) {
+template <int C>
+__global__ __launch_bounds__(IMG_NT, 1) void conv_img_band_kernel(const ConvImgParams p) {
+  using S = BandShape<C>;
+  constexpr int PITCH = S::PITCH, PCOLS = S::PCOLS, KPT = S::KPT, KS = S::KS, TPITCH = S::TPITCH;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int wm = wave & 1, wn = wave >> 1;
-  const int HW = p.H * p.W;
-  const int image_bytes = HW * I2_C;
+  const int wm = wave % S::WM, wn = wave / S::WM;
+  const int image_bytes = p.H * p.W * C;
+  const int bands = (p.H + S::BR - 1) / S::BR;
   lds_u8 *patch = (lds_u8 *)lds;
-  uint8_t *tile = lds + I2_PATCH + wave * (32 * I2_TPITCH);
+  uint8_t *tile = lds + S::PATCH + wave * (32 * TPITCH);
 
   // this wave's weights: channel blocks 2 wn and 2 wn + 1
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<int8_t *>(p.wf) + (size_t)wn * (2 * I2_KS * 1024), 0, 2 * I2_KS * 1024, 0x00027000);
+      const_cast<int8_t *>(p.wf) + (size_t)wn * (2 * KS * 1024), 0, 2 * KS * 1024, 0x00027000);
   const int lane16 = lane * 16;
 
-  // Patch role: column tid / 8 of the patch (the last two of 32 idle), piece tid % 8 of its pixels.
-  const int pcol = tid >> 3, ppiece = tid & 7;
+  // Patch role: column tid / PPP of the patch, piece tid % PPP of its pixels.
+  const int pcol = tid / S::PPP, ppiece = tid % S::PPP;
   const bool col_in = (unsigned)(pcol - 1) < (unsigned)p.W;
   const int zx = (int)p.x_xor;
   const ScaledClip c1 = scaled_clip(p.lo, p.hi, p.shift);
@@ -245,26 +258,28 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgPar
   // Row-piece role of the staging tile: 4 pieces per row, 16 rows per instruction.
   const int trow = lane >> 2, tpiece = lane & 3;
 
-  for (int img = blockIdx.x; img < p.B; img += gridDim.x) {
-    // ---- the image into LDS, stored xor 0x80 when unsigned (border: zero xor 0x80) ---------------
+  for (int u = blockIdx.x; u < p.B * bands; u += gridDim.x) {
+    const int img = u / bands, row0 = (u - img * bands) * S::BR;     // first output row of the band
+    const int HWu = min(S::BR, p.H - row0) * p.W;                    // its output pixels
+    // ---- the band's input rows into LDS, stored xor 0x80 when unsigned (border: zero xor 0x80) ----
     {
       const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
           const_cast<uint8_t *>(p.x) + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
-#pragma unroll 1
-      for (int r0 = 0; r0 < I2_PW; r0 += 10) {
-        v4i px[10];
+      constexpr int FB = S::PROWS;       // all rows requested at once
+      for (int r0 = 0; r0 < S::PROWS; r0 += FB) {
+        v4i px[FB];
 #pragma unroll
-        for (int k = 0; k < 10; ++k) {
-          const int r = r0 + k;
+        for (int k = 0; k < FB; ++k) {
+          const int iy = row0 - 1 + r0 + k;
           // outside the image: an offset the descriptor rejects, which reads as zero
-          const bool in = col_in && (unsigned)(r - 1) < (unsigned)p.H;
-          const uint32_t off = in ? (uint32_t)(((r - 1) * p.W + (pcol - 1)) * I2_C + 16 * ppiece) : 0x80000000u;
+          const bool in = col_in && (unsigned)iy < (unsigned)p.H;
+          const uint32_t off = in ? (uint32_t)((iy * p.W + (pcol - 1)) * C + 16 * ppiece) : 0x80000000u;
           px[k] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
         }
-        if (pcol < I2_PW) {
+        if (pcol < PCOLS) {
 #pragma unroll
-          for (int k = 0; k < 10; ++k)
-            *reinterpret_cast<v4i *>(lds + ((r0 + k) * I2_PW + pcol) * I2_PITCH + 16 * ppiece) =
+          for (int k = 0; k < FB; ++k)
+            *reinterpret_cast<v4i *>(lds + ((r0 + k) * PCOLS + pcol) * PITCH + 16 * ppiece) =
                 v4i{px[k].x ^ zx, px[k].y ^ zx, px[k].z ^ zx, px[k].w ^ zx};
         }
       }
@@ -280,14 +295,9 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgPar
 #pragma unroll
       for (int j = 0; j < MBP; ++j) {
         const int m = 32 * (first + j) + l32;
-        const int oy = m < HW ? m / p.W : 0, ox = m < HW ? m - oy * p.W : 0;
-        ar[j] = patch + (oy * I2_PW + ox) * I2_PITCH + 16 * half;
+        const int oy = m < HWu ? m / p.W : 0, ox = m < HWu ? m - oy * p.W : 0;
+        ar[j] = patch + (oy * PCOLS + ox) * PITCH + 16 * half;
       }
-      v4i bq[I2_KPT][2];
-#pragma unroll
-      for (int cs = 0; cs < I2_KPT; ++cs)
-#pragma unroll
-        for (int q = 0; q < 2; ++q) bq[cs][q] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, (q * I2_KS + cs) * 1024, 0);
       v16i acc[2][MBP];
 #pragma unroll
       for (int q = 0; q < 2; ++q)
@@ -303,34 +313,41 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgPar
       v4i xf[2][MBP];
 #pragma unroll
       for (int j = 0; j < MBP; ++j) xf[0][j] = *(lds_v4i *)(ar[j]);
-      constexpr int ROW_SLICES = 3 * I2_KPT;
+      {
+        v4i bq[KPT][2];
+#pragma unroll
+        for (int cs = 0; cs < KPT; ++cs)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) bq[cs][q] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, (q * KS + cs) * 1024, 0);
+        constexpr int ROW_SLICES = 3 * KPT;
 #pragma unroll 1
-      for (int r = 0; r < 3; ++r) {
-        const int wbase = r * ROW_SLICES * 1024;
+        for (int r = 0; r < 3; ++r) {
+          const int wbase = r * ROW_SLICES * 1024;
 #pragma unroll
-        for (int sc = 0; sc < ROW_SLICES; ++sc) {
-          const int cs = sc % I2_KPT;
-          const int cur = sc & 1, nxt = cur ^ 1;
-          const int off = sc + 1 < ROW_SLICES ? ((sc + 1) / I2_KPT) * I2_PITCH + 32 * ((sc + 1) % I2_KPT) : I2_PW * I2_PITCH;
+          for (int sc = 0; sc < ROW_SLICES; ++sc) {
+            const int cs = sc % KPT;
+            const int cur = sc & 1, nxt = cur ^ 1;
+            const int off = sc + 1 < ROW_SLICES ? ((sc + 1) / KPT) * PITCH + 32 * ((sc + 1) % KPT) : PCOLS * PITCH;
 #pragma unroll
-          for (int i = 0; i < 2 * MBP; ++i) {
-            const int q = i / MBP, j = i % MBP;
-            acc[q][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[cs][q], xf[cur][j], acc[q][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (i < MBP) xf[nxt][i] = *(lds_v4i *)(ar[i] + off);
-            if (i == 2 * MBP - 2 && (sc < ROW_SLICES - I2_KPT || r < 2))
-              bq[cs][0] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (sc + I2_KPT) * 1024, 0);
+            for (int i = 0; i < 2 * MBP; ++i) {
+              const int q = i / MBP, j = i % MBP;
+              acc[q][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[cs][q], xf[cur][j], acc[q][j], 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
+              if (i < MBP) xf[nxt][i] = *(lds_v4i *)(ar[i] + off);
+              if (i == 2 * MBP - 2 && (sc < ROW_SLICES - KPT || r < 2))
+                bq[cs][0] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (sc + KPT) * 1024, 0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (sc < ROW_SLICES - KPT || r < 2)
+              bq[cs][1] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (KS + sc + KPT) * 1024, 0);
             __builtin_amdgcn_sched_barrier(0);
           }
-          if (sc < ROW_SLICES - I2_KPT || r < 2)
-            bq[cs][1] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, wbase + (I2_KS + sc + I2_KPT) * 1024, 0);
-          __builtin_amdgcn_sched_barrier(0);
-        }
 #pragma unroll
-        for (int j = 0; j < MBP; ++j) ar[j] += I2_PW * I2_PITCH;
+          for (int j = 0; j < MBP; ++j) ar[j] += PCOLS * PITCH;
+        }
       }
       // epilogue, a block of 32 pixels at a time through the wave's own tile: clip at the accumulator's
-      // scale, shift-and-pack, then rows of 64 bytes to memory (rows past the image are offsets the
+      // scale, shift-and-pack, then rows of 64 bytes to memory (rows past the band get an offset the
       // descriptor rejects)
 #pragma unroll
       for (int j = 0; j < MBP; ++j) {
@@ -340,19 +357,20 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgPar
           int v[16];
 #pragma unroll
           for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
-          *reinterpret_cast<v4i *>(tile + l32 * I2_TPITCH + 32 * q + 16 * half) = shift_pack16(v, sh);
+          *reinterpret_cast<v4i *>(tile + l32 * TPITCH + 32 * q + 16 * half) = shift_pack16(v, sh);
         }
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-          const int row = 16 * k + trow;
-          const v4i o = *reinterpret_cast<const v4i *>(tile + row * I2_TPITCH + 16 * tpiece);
-          __builtin_amdgcn_raw_buffer_store_b128(o, yres, (32 * (first + j) + row) * I2_C + 64 * wn + 16 * tpiece, 0, 0);
+          const int row = 16 * k + trow, m = 32 * (first + j) + row;
+          const v4i o = *reinterpret_cast<const v4i *>(tile + row * TPITCH + 16 * tpiece);
+          const uint32_t off = m < HWu ? (uint32_t)((row0 * p.W + m) * C + 64 * wn + 16 * tpiece) : 0x80000000u;
+          __builtin_amdgcn_raw_buffer_store_b128(o, yres, off, 0, 0);
         }
       }
     };
-    run_pass(std::integral_constant<int, I2_MB0>{}, wm * I2_MB0);
-    run_pass(std::integral_constant<int, I2_MB1>{}, 2 * I2_MB0 + wm * I2_MB1);
-    __syncthreads();                    // every wave is done with the patch before the next image overwrites it
+    run_pass(std::integral_constant<int, S::MB0>{}, wm * S::MB0);
+    run_pass(std::integral_constant<int, S::MB1>{}, S::WM * S::MB0 + wm * S::MB1);
+    __syncthreads();                    // every wave is done with the patch before the next band overwrites it
   }
 }
 
@@ -360,14 +378,18 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img128_kernel(const ConvImgPar
 
 bool conv_img_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int H, int W, int shift,
                          const void *x, const void *y) {
-  if (Cin != Cout || (Cin != IMG_C && Cin != I2_C) || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
-  const int most = (Cin == IMG_C ? IMG_PW : I2_PW) - 2;
-  if (H < 1 || W < 1 || H > most || W > most || shift < 0) return false;
+  if (Cin != Cout || (Cin != IMG_C && Cin != 128) || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
+  if (H < 1 || W < 1 || shift < 0) return false;
+  // 256 channels: a whole image of at most 14 x 14; otherwise bands of 28 rows of an image of any height
+  if (Cin == IMG_C ? (H > IMG_PW - 2 || W > IMG_PW - 2) : W > BandShape<128>::PCOLS - 2) return false;
+  if ((long long)H * W * Cin >= (1LL << 31)) return false;
   return ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
 }
 
+int conv_img_units(int C, int B, int H) { return C == IMG_C ? B : B * ((H + BandShape<128>::BR - 1) / BandShape<128>::BR); }
+
 int launch_conv_img_weights(const int8_t *w, int8_t *wf, int C, hipStream_t stream) {
-  if (!w || !wf || (C != IMG_C && C != I2_C) || ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(wf)) & 15))
+  if (!w || !wf || (C != IMG_C && C != 128) || ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(wf)) & 15))
     return (int)hipErrorInvalidValue;
   const int pieces = C * 9 * C / 16;
   hipLaunchKernelGGL(conv_img_weights_kernel, dim3((pieces + 255) / 256), dim3(256), 0, stream, w, wf, C);
@@ -380,19 +402,22 @@ int launch_conv_img(const ConvImgParams &p, hipStream_t stream) {
       ((reinterpret_cast<uintptr_t>(p.wf) | reinterpret_cast<uintptr_t>(p.acc0)) & 15))
     return (int)hipErrorInvalidValue;
   static unsigned long long done_mask[2] = {0, 0};         // devices whose LDS limit has been raised, per kernel
-  const bool wide = p.C == IMG_C;
-  const void *fn = wide ? reinterpret_cast<const void *>(conv_img_kernel) : reinterpret_cast<const void *>(conv_img128_kernel);
-  const int lds_bytes = wide ? IMG_LDS : I2_LDS;
+  const int which = p.C == IMG_C ? 0 : 1;
+  const void *fn = which == 0 ? reinterpret_cast<const void *>(conv_img_kernel)
+                              : reinterpret_cast<const void *>(conv_img_band_kernel<128>);
+  const int lds_bytes = which == 0 ? IMG_LDS : BandShape<128>::LDS;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
-  if (dev < 0 || dev > 63 || !((done_mask[wide] >> dev) & 1ull)) {
+  if (dev < 0 || dev > 63 || !((done_mask[which] >> dev) & 1ull)) {
     const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return (int)e;
-    if (dev >= 0 && dev <= 63) done_mask[wide] |= 1ull << dev;
+    if (dev >= 0 && dev <= 63) done_mask[which] |= 1ull << dev;
   }
-  const int grid = p.B < 256 ? p.B : 256;                    // one workgroup per CU, an image at a time
-  if (wide) hipLaunchKernelGGL(conv_img_kernel, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
-  else hipLaunchKernelGGL(conv_img128_kernel, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
+  const long long units = conv_img_units(p.C, p.B, p.H);
+  if (units > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+  const int grid = units < 256 ? (int)units : 256;           // one workgroup per CU, an image (or band) at a time
+  if (which == 0) hipLaunchKernelGGL(conv_img_kernel, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
+  else hipLaunchKernelGGL(conv_img_band_kernel<128>, dim3(grid), dim3(IMG_NT), lds_bytes, stream, p);
   return (int)hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ const TuningName kTuningNames[] = {
     {"pw_ws", "F8_PW_WS", &Tuning::pw_ws},                       {"pw_small", "F8_PW_SMALL", &Tuning::pw_small},
     {"xcd_remap", "F8_XCD_REMAP", &Tuning::xcd_remap},           {"stem_pool", "F8_STEM_POOL", &Tuning::stem_pool},
     {"conv_tail", "F8_CONV_TAIL", &Tuning::conv_tail},         {"conv_img", "F8_CONV_IMG", &Tuning::conv_img},
-    {"pw_wide", "F8_PW_WIDE", &Tuning::pw_wide},
+    {"pw_wide", "F8_PW_WIDE", &Tuning::pw_wide},                 {"conv_img_min", "F8_CONV_IMG_MIN", &Tuning::conv_img_min},
 };
 }  // namespace
 

@@ -93,7 +93,11 @@ struct f8_chain {
   // in the constants region (0: not such a layer).
   std::vector<size_t> img_w_off;       // per layer
   bool conv_img = true;
-  bool img_role(size_t i) const { return conv_img && img_w_off[i] != 0 && !(use_fusion() && fused[i].role != 0); }
+  int conv_img_min = 96;
+  bool img_role(size_t i, int batch) const {
+    return conv_img && img_w_off[i] != 0 && !(use_fusion() && fused[i].role != 0) &&
+           conv_img_units(layers[i].Cin, batch, geom[i].H) >= conv_img_min;
+  }
   bool tail_in_fused_block(size_t i) const {
     const size_t a = tail[i] == 1 ? i : (size_t)tail_peer[i], b = tail[i] == 1 ? (size_t)tail_peer[i] : i;
     return use_fusion() && (fused[a].role != 0 || fused[b].role != 0);
@@ -313,7 +317,7 @@ struct f8_chain {
     switch (L.op) {
       case F8_OP_CONV: {
         const int32_t *acc0 = reinterpret_cast<const int32_t *>(static_cast<uint8_t *>(workspace) + acc0_off[i]);
-        if (img_role(i) && conv_img_applicable(L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, g.H, g.W,
+        if (img_role(i, batch) && conv_img_applicable(L.Cin, L.Cout, L.R, L.S, L.stride_h, L.stride_w, L.pad_h, L.pad_w, g.H, g.W,
                                                L.q.fl_x + L.q.fl_w - L.q.fl_y, src, dst)) {
           ConvImgParams ip;
           ip.x = static_cast<const uint8_t *>(src);
@@ -488,6 +492,7 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
   c->tensors[c->last_tensor].external = true;
   c->stem_pool = tuning().stem_pool.load() != 0;
   c->conv_img = tuning().conv_img.load() != 0;
+  c->conv_img_min = tuning().conv_img_min.load();
   // a stem whose only reader is a 3x3 stride-2 pad-1 max pool: both in one kernel
   for (size_t i = 0; i + 1 < c->layers.size(); ++i) {
     const f8_layer_desc &L = c->layers[i], &M = c->layers[i + 1];
@@ -824,7 +829,9 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       Geom gk = c->narrow_rows((size_t)layer, batch) ? g : c->conv_geom(layer, batch);
       gk.B = batch;
       gk.P = g.P; gk.Q = g.Q;
-      name = c->img_role((size_t)layer) ? (L.Cin == 256 ? "conv3x3_img<256x256>" : "conv3x3_img<128x128>") : conv_kernel_name(gk, L.q, L.res >= 0);
+      name = c->img_role((size_t)layer, batch)
+                 ? (L.Cin == 256 ? "conv3x3_img<256x256>" : "conv3x3_img<128x128>")
+                 : conv_kernel_name(gk, L.q, L.res >= 0);
       ops = 2.0 * M * g.R * g.S * g.Cin * g.Cout;
       bytes += (double)g.R * g.S * g.Cin * g.Cout + 4.0 * g.Cout;
       if (with_tail) {

@@ -30,7 +30,8 @@ struct Tuning {
   std::atomic<int> xcd_remap{1};       // XCD-aware tile order
   std::atomic<int> stem_pool{1};       // chain: stem and max pool as one kernel
   std::atomic<int> conv_tail{1};       // chain: next block's first 1x1 layer computed behind a closing layer
-  std::atomic<int> conv_img{1};        // chain: image-stationary 3x3 kernel (256 channels, images up to 14 x 14)
+  std::atomic<int> conv_img{1};        // chain: image-stationary 3x3 kernels (128 and 256 channels)
+  std::atomic<int> conv_img_min{96};   // ... from this many images (or bands of 28 rows) on: one workgroup each
 };
 Tuning &tuning();
 

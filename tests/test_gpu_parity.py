@@ -278,7 +278,7 @@ def test_weights_stationary_3x3_64(oracle):
 
 def test_image_stationary_3x3_256(oracle):
     """3x3 stride-1 layers with 256 -> 256 channels on images of at most 14 x 14 pixels, and with
-    128 -> 128 channels on images of at most 28 x 28, take, in a chain, a kernel
+    128 -> 128 channels on images at most 28 wide, take, in a chain with enough images to fill the CUs, a kernel
     that keeps one whole image in LDS and streams the weights (stored in fragment order when the
     workspace is prepared): image sizes with full, ragged and single blocks of pixels, batches
     below and above the number of workgroups, unsigned and signed inputs and outputs, clips inside
@@ -295,9 +295,14 @@ def test_image_stationary_3x3_256(oracle):
         b.conv("second", a, C, 3, 1, 1, relu=relu2)
         net = b.net
         x = wl.draw_u8(rng, (batch, hw, hw, C)) if x_type == "u8" else wl.draw_s8_normal(rng, (batch, hw, hw, C), 5)
-        names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(2)]
-        assert names == ["conv3x3_img<%dx%d>" % (C, C)] * 2, names
-        out = check_network(oracle, x, net, list(range(batch)), "image-stationary 3x3, case %d" % k, lean_is_smaller=False)
+        f8.f8_tuning_set("conv_img_min", 1)      # (also for fewer images than the kernel is normally chosen for)
+        try:
+            names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(2)]
+            assert names == ["conv3x3_img<%dx%d>" % (C, C)] * 2, names
+            out = check_network(oracle, x, net, list(range(batch)), "image-stationary 3x3, case %d" % k, lean_is_smaller=False)
+        finally:
+            f8.f8_tuning_set("conv_img_min", 96)
+        assert not any(f8.Chain(net).layer_info(i, 1)[0].startswith("conv3x3_img") for i in range(2))
         f8.f8_tuning_set("conv_img", 0)
         try:
             plain = f8.Chain(net).prepare(batch)
@@ -312,6 +317,7 @@ def test_image_stationary_3x3_256(oracle):
     chain = f8.Chain(net)
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_img<256x256>") == 5
     assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("conv3x3_img<128x128>") == 3
+    assert not any(chain.layer_info(i, 32)[0].startswith("conv3x3_img") for i in range(len(net.layers)))
 
 
 def test_weights_stationary_1x1_64_to_256(oracle):
