@@ -371,7 +371,8 @@ f8_status f8_mfma_i8_yardstick_operands(int32_t *sink, int iters, uint32_t seed,
  * through them).  Names and defaults: "conv_variant" (-1 = automatic; >= 0 forces that tile
  * variant of the LDS-direct dense kernel), "conv_ws", "conv_ws_min" (768: smallest layer, in blocks
  * of 128 pixels, that takes the weights-stationary 3x3 kernel), "pw_ws", "pw_small", "xcd_remap",
- * "pw_wide", "stem_pool", "conv_tail", "conv_img" (1 = on), "conv_img_min" (96: fewest images, or
+ * "pw_wide", "pw_mid" (1: the 1x1 128 -> 512 kernel only together with the 512 -> 128 layer behind it, 2: also
+ * alone), "stem_pool", "conv_tail", "conv_img" (1 = on), "conv_img_min" (96: fewest images, or
  * bands of 28 image rows, for which a chain takes the image-stationary 3x3 kernels).  The environment variables F8_<NAME IN CAPITALS> give the
  * initial values; they are read once, when the library first looks at a switch, never on the
  * launch path.  f8_tuning_set returns 0, or -1 for an unknown name; the chain switches

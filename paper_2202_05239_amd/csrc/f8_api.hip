@@ -17,6 +17,7 @@ const TuningName kTuningNames[] = {
     {"xcd_remap", "F8_XCD_REMAP", &Tuning::xcd_remap},           {"stem_pool", "F8_STEM_POOL", &Tuning::stem_pool},
     {"conv_tail", "F8_CONV_TAIL", &Tuning::conv_tail},         {"conv_img", "F8_CONV_IMG", &Tuning::conv_img},
     {"pw_wide", "F8_PW_WIDE", &Tuning::pw_wide},                 {"conv_img_min", "F8_CONV_IMG_MIN", &Tuning::conv_img_min},
+    {"pw_mid", "F8_PW_MID", &Tuning::pw_mid},
 };
 }  // namespace
 
@@ -113,6 +114,17 @@ static bool use_pw_ws(const void *x, const int8_t *w, const void *y, const void 
   return pw_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
 }
 
+// The 1x1 128 -> 512 layers (the closing layers of the second ResNet stage): with the 512 -> 128 layer behind
+// them in the same launch, or (switch at 2) on their own.
+static bool use_pw_mid(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
+                       const f8_quant &q, const void *y2, bool with_tail) {
+  const int level = tuning().pw_mid.load(std::memory_order_relaxed);
+  if (level < (with_tail ? 1 : 2) || y2 || q.y_type == F8_S32 || (res && q.res_type == F8_S32)) return false;
+  // it pays once every workgroup walks over several pairs of blocks
+  if ((long long)g.B * g.H * g.W < 65536) return false;
+  return pw_mid_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, q.fl_x + q.fl_w - q.fl_y, x, w, y, res);
+}
+
 // And the 1x1 layers with 256 or 512 input channels and at least as many output channels per workgroup
 // as its four waves hold weights for (the closing layers of the third and fourth ResNet stage).
 static bool use_pw_wide(const void *x, const int8_t *w, const void *y, const void *res, const Geom &g,
@@ -147,6 +159,29 @@ f8_status enqueue_conv(const void *x, const int8_t *w, const int32_t *acc0, cons
     return launch_pw_small(sp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
   }
   const bool pw_ws = use_pw_ws(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0;
+  const bool pw_mid = use_pw_mid(x, w, y, res, g, q, (q2 && y2) ? y2 : nullptr, tail != nullptr) && (reinterpret_cast<uintptr_t>(acc0) & 15) == 0;
+  if (pw_mid && (!tail || (tail->Cout == 128 && tail->q.y_type != F8_S32))) {
+    PwMidParams pp;
+    pp.t_w = nullptr; pp.t_acc0 = nullptr; pp.t_y = nullptr;
+    pp.t_shift = pp.t_lo = pp.t_hi = 0; pp.t_xor = 0;
+    if (tail) {
+      pp.t_w = tail->w; pp.t_acc0 = tail->acc0; pp.t_y = static_cast<uint8_t *>(tail->y);
+      pp.t_shift = tail->q.fl_x + tail->q.fl_w - tail->q.fl_y;
+      pp.t_lo = tail->q.clip_lo; pp.t_hi = tail->q.clip_hi;
+      pp.t_xor = tail->q.x_type == F8_U8 ? 0x80808080u : 0u;
+    }
+    pp.x = static_cast<const uint8_t *>(x);
+    pp.w = w;
+    pp.acc0 = acc0;
+    pp.res = static_cast<const uint8_t *>(res);
+    pp.y = static_cast<uint8_t *>(y);
+    pp.M = (long long)g.B * g.H * g.W;
+    pp.shift = q.fl_x + q.fl_w - q.fl_y; pp.lo = q.clip_lo; pp.hi = q.clip_hi;
+    pp.res_signed = q.res_type == F8_S8;
+    pp.res_d = res ? q.fl_x + q.fl_w - q.fl_res : 0;
+    pp.x_xor = q.x_type == F8_U8 ? 0x80808080u : 0u;
+    return launch_pw_mid(pp, stream) == 0 ? F8_OK : F8_ERR_DEVICE;
+  }
   if (tail && !(pw_ws && (tail->Cout == 64 || tail->Cout == 128) && tail->q.y_type != F8_S32)) return F8_ERR_UNSUPPORTED;
   if (pw_ws) {
     PwWsParams pp;
@@ -253,6 +288,7 @@ bool conv_reads_narrow_rows(const Geom &g, const f8_quant &q, bool has_res) {
 }
 
 bool conv_tail_ok(const Geom &g, const f8_quant &q, int Cout2) {
+  if (g.Cin == 128) return Cout2 == 128 && use_pw_mid(nullptr, nullptr, nullptr, nullptr, g, q, nullptr, true);
   return (Cout2 == 64 || Cout2 == 128) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr);
 }
 
@@ -266,6 +302,7 @@ const char *conv_kernel_name(const Geom &g, const f8_quant &q, bool has_res) {
     return names[g.Cin == 16 ? 0 : (g.Cin == 24 ? 1 : 2)][g.Cout == 96 ? 0 : (g.Cout == 144 ? 1 : 2)];
   }
   if (!(has_res && q.res_type == F8_S32) && use_pw_ws(nullptr, nullptr, nullptr, nullptr, g, q, nullptr)) return "pw1x1_ws<64x256>";
+  if (!(has_res && q.res_type == F8_S32) && use_pw_mid(nullptr, nullptr, nullptr, nullptr, g, q, nullptr, false)) return "pw1x1_mid<128x512>";
   if (!(has_res && q.res_type == F8_S32) && use_pw_wide(nullptr, nullptr, nullptr, nullptr, g, q, nullptr))
     return g.Cin == 256 ? "pw1x1_wide<256>" : "pw1x1_wide<512>";
   if (use_conv_ws(nullptr, nullptr, nullptr, has_res ? &g : nullptr, g, q, nullptr)) return g.Cin == 64 ? "conv3x3_ws<64x64>" : "conv3x3_ws<128x128>";

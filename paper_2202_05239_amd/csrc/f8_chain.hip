@@ -508,8 +508,8 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     c->stem[i + 1].pool = 2;
   }
   c->conv_tail = tuning().conv_tail.load() != 0;      // tuning aid
-  // a 1x1 64 -> 256 layer and a 1x1 layer of 64 or 128 channels that reads it (the hand-over between two
-  // bottleneck blocks): the second can run on each block of the first one's output while it is in LDS.
+  // a 1x1 64 -> 256 layer and a 1x1 layer of 64 or 128 channels that reads it, or a 1x1 128 -> 512 layer and
+  // a 1x1 layer of 128 channels that reads it (the hand-over between two bottleneck blocks): the second can run on each block of the first one's output while it is in LDS.
   // It is the next layer, or the one after it when the layer between them takes no part in a pair (the
   // shortcut projection of a new stage).  Every tensor involved lives in the arena (aligned); weights
   // must be 16-byte aligned.
@@ -517,12 +517,13 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
     const f8_layer_desc &L = c->layers[i];
     if (c->tail[i] != 0 || c->stem[i].pool != 0 || c->stem[i].on) continue;
     if (L.op != F8_OP_CONV || L.dst2 > 0) continue;
-    if (L.Cin != 64 || L.Cout != 256 || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h != 0 || L.pad_w != 0) continue;
+    const bool head64 = L.Cin == 64 && L.Cout == 256, head128 = L.Cin == 128 && L.Cout == 512;
+    if (!(head64 || head128) || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h != 0 || L.pad_w != 0) continue;
     if (L.q.y_type == F8_S32 || (L.res >= 0 && L.q.res_type == F8_S32) || L.q.fl_x + L.q.fl_w - L.q.fl_y < 0) continue;
     for (size_t j = i + 1; j <= i + 2 && j < c->layers.size(); ++j) {
       const f8_layer_desc &T = c->layers[j];
       if (c->tail[j] != 0 || c->stem[j].on || c->stem[j].pool != 0) break;
-      const bool fits = T.op == F8_OP_CONV && T.src == L.dst && T.dst2 <= 0 && T.res < 0 && (T.Cout == 64 || T.Cout == 128) &&
+      const bool fits = T.op == F8_OP_CONV && T.src == L.dst && T.dst2 <= 0 && T.res < 0 && (T.Cout == 128 || (head64 && T.Cout == 64)) &&
                         T.R == 1 && T.S == 1 && T.stride_h == 1 && T.stride_w == 1 && T.pad_h == 0 && T.pad_w == 0 &&
                         T.q.y_type != F8_S32 && T.q.fl_x + T.q.fl_w - T.q.fl_y >= 0 &&
                         ((reinterpret_cast<uintptr_t>(L.w) | reinterpret_cast<uintptr_t>(T.w)) & 15) == 0;
@@ -837,7 +838,7 @@ f8_status f8_chain_layer_info(const f8_chain *c, int layer, int batch, char *ker
       if (with_tail) {
         // plus the 1x1 layer behind it: its output and weights; its input never leaves the chip
         const f8_layer_desc &T = c->layers[c->tail_peer[layer]];
-        name = T.Cout == 64 ? "pw1x1_ws<64x256>+1x1<64>" : "pw1x1_ws<64x256>+1x1<128>";
+        name = L.Cin == 128 ? "pw1x1_mid<128x512>+1x1<128>" : (T.Cout == 64 ? "pw1x1_ws<64x256>+1x1<64>" : "pw1x1_ws<64x256>+1x1<128>");
         ops += 2.0 * M * (double)T.Cin * T.Cout;
         bytes += M * T.Cout + (double)T.Cin * T.Cout + 4.0 * T.Cout;
       }

@@ -12,6 +12,7 @@
 #include "conv_ws.h"
 #include "pw_ws.h"
 #include "pw_wide.h"
+#include "pw_mid.h"
 #include "pw_small.h"
 #include "dwconv_pool.h"
 
@@ -31,6 +32,7 @@ struct Tuning {
   std::atomic<int> stem_pool{1};       // chain: stem and max pool as one kernel
   std::atomic<int> conv_tail{1};       // chain: next block's first 1x1 layer computed behind a closing layer
   std::atomic<int> conv_img{1};        // chain: image-stationary 3x3 kernels (128 and 256 channels)
+  std::atomic<int> pw_mid{1};          // 1x1 128 -> 512 kernel: 1 = when the 512 -> 128 layer behind it runs in the same launch, 2 = always
   std::atomic<int> conv_img_min{96};   // ... from this many images (or bands of 28 rows) on: one workgroup each
 };
 Tuning &tuning();

@@ -416,6 +416,63 @@ def test_1x1_layer_computed_behind_the_64_to_256_layer(oracle):
             assert torch.equal(part, out[i0:i0 + 8]), "two launches, case %d" % k
 
 
+def test_1x1_layer_computed_behind_the_128_to_512_layer(oracle):
+    """A 1x1 128 -> 512 layer followed by a 1x1 512 -> 128 layer that reads its output (the hand-over
+    between two bottleneck blocks of the second stage): at large batch one launch computes both, the
+    second from each block of the first one's output while it is on chip; both tensors are still
+    written.  Every tensor against the oracle; the one-launch path against the two-launch path;
+    small batches keep two launches."""
+    cases = ((32, 64, True, True, True, False),      # unsigned in between, residual
+             (23, 130, False, True, False, False),   # signed tensor in between, no residual, ragged last pair of blocks
+             (19, 190, True, False, True, True),     # signed output, another layer between the two
+             (37, 49, False, False, True, False))    # signed everywhere, ragged
+    for k, (hw, batch, relu1, relu2, with_res, between) in enumerate(cases):
+        rng = np.random.default_rng(1900 + k)
+        b = wl._NetBuilder("tail128_%d" % k, rng, hw, 32, "u8", 6, (5, 9), (2, 6), True)
+        r = b.conv("short", 0, 512, 1, 1, 0, relu=(k % 2 == 0))
+        m = b.conv("mid", 0, 128, 1, 1, 0)
+        h = b.conv("front", m, 512, 1, 1, 0, relu=relu1, res=r if with_res else -1)
+        if between:      # (32 channels: this reader cannot itself be the layer computed behind the front one)
+            e = b.conv("other_reader", h, 32, 1, 1, 0, relu=False)
+            t = b.conv("behind", h, 128, 1, 1, 0, relu=relu2)
+        else:
+            t = b.conv("behind", h, 128, 1, 1, 0, relu=relu2)
+            e = b.conv("other_reader", h, 32, 1, 1, 0, relu=False)
+        b.conv("join", t, 32, 1, 1, 0, res=e)
+        net = b.net
+        x = wl.draw_u8(rng, (batch, hw, hw, 32))
+        names = [f8.Chain(net).layer_info(i, batch)[0] for i in range(len(net.layers))]
+        assert names[2] == "pw1x1_mid<128x512>+1x1<128>" and names[4 if between else 3] == "(fused)", names
+        assert "(fused)" not in [f8.Chain(net).layer_info(i, 8)[0] for i in range(len(net.layers))]
+        imgs = sorted(set([0, 1, batch // 2, batch - 2, batch - 1]))
+        out = check_network(oracle, x, net, imgs, "1x1 behind 128->512, case %d" % k, lean_is_smaller=False)
+        # the two-launch path: the same chain below the batch where one launch pays
+        small = f8.Chain(net).prepare(8)
+        xt = torch.from_numpy(x).to(DEV)
+        for i0 in (0, batch - 8):
+            part = small.run(xt[i0:i0 + 8].contiguous())
+            torch.cuda.synchronize()
+            assert torch.equal(part, out[i0:i0 + 8]), "two launches, case %d" % k
+    # without the layer behind (switch at 2): the 128 -> 512 layer alone, through the single-layer call
+    from concurrent.futures import ThreadPoolExecutor
+    f8.f8_tuning_set("pw_mid", 2)
+    try:
+        rng = np.random.default_rng(1999)
+        for B, H, W, xt_, yt, rt, shift, clip in ((70, 31, 31, "u8", "u8", "u8", 9, None), (1027, 8, 8, "s8", "s8", "s8", 7, (-50, 90)),
+                                                  (65537, 1, 1, "u8", "s8", None, 0, (3, 100))):
+            x, L, res = wl.random_conv_case(rng, B, H, W, 128, 512, 1, 1, 1, 0, xt_, yt, rt, shift=shift, clip=clip)
+            parts = np.array_split(np.arange(B), min(B, host_threads()))
+            with ThreadPoolExecutor(len(parts)) as ex:
+                outs = list(ex.map(lambda idx: oracle.conv2d_fixed(np.ascontiguousarray(x[idx]), L.w, L.bias, L, (1, 1), (0, 0),
+                                                                   None if res is None else np.ascontiguousarray(res[idx])), parts))
+            assert_same(gpu_layer(L, x, res), np.concatenate(outs), "pw mid alone %s" % str((B, H, W, xt_, yt, rt, shift)))
+    finally:
+        f8.f8_tuning_set("pw_mid", 1)
+    _, net = wl.config4(batch=1)
+    chain = f8.Chain(net)
+    assert [chain.layer_info(i, 256)[0] for i in range(len(net.layers))].count("pw1x1_mid<128x512>+1x1<128>") == 3
+
+
 def test_weights_stationary_1x1_few_input_channels(oracle):
     """1x1 layers with 16, 24 or 32 input and 96, 144 or 192 output channels at large batch (MobileNetV2's
     first expand layers; also 32 -> 16, its first projection) take a streaming kernel of their own: every shape, input / output types,
