@@ -11,9 +11,10 @@
 // rows are fed in the order that leaves a lane with 16 consecutive channels of its pixel, so each lane
 // adds its accumulators to one 16-byte piece of the residual, requantises and writes the piece back in
 // place; finished rows leave as 16-byte pieces, 128 bytes contiguous per row.
-// The layer behind: its weights (64 KiB) sit in LDS for the life of the workgroup; once the four
-// tiles of a block are complete (one barrier) they are its activation operand, K = 512 = 16 slices,
-// and every wave computes 32 of its 128 channels for its block, requantises and stores them.  Both
+// The layer behind: every wave also keeps the weights of 32 of its 128 channels in registers (16
+// fragments); once the four tiles of a block are complete (one barrier) they are its activation
+// operand, K = 512 = 16 slices, and the wave computes those 32 channels for its block, requantises
+// and stores them.  Both
 // tensors are still written, but the second layer's 512 bytes per pixel are never read back.
 #include "pw_mid.h"
 
@@ -26,8 +27,8 @@ typedef __attribute__((address_space(3))) const int32_t lds_i32;
 typedef __attribute__((address_space(3))) const uint8_t lds_u8;
 
 // The same LDS address, made opaque to the optimiser: reads through it stay where they are written
-// (start values and the second layer's weights never change, so they would otherwise be hoisted out of
-// the loop and held in registers).
+// (start values never change, so they would otherwise be hoisted out of the loop and held in
+// registers).
 __device__ __forceinline__ lds_i32 *here(const int32_t *shared_array) {
   lds_i32 *q = (lds_i32 *)shared_array;
   asm volatile("" : "+v"(q));
@@ -41,17 +42,15 @@ __device__ __forceinline__ lds_u8 *here(const uint8_t *shared_array) {
 
 // Row r = 8 g + 4 h + j of a 32 x 32 matrix result lies in lane half h, register 4 g + j.  With channel
 // 16 h + 4 g + j as row r of the weight operand, registers 0..15 of a lane are the channels
-// 16 h .. 16 h + 15 of its pixel: one 16-byte piece of the row.  frag_row is the inverse map.
+// 16 h .. 16 h + 15 of its pixel: one 16-byte piece of the row.
 __device__ __forceinline__ int frag_channel(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
-__device__ __forceinline__ int frag_row(int c) { return 8 * ((c >> 2) & 3) + 4 * (c >> 4) + (c & 3); }
 
 constexpr int PM_NT = 512;
 constexpr int PM_K = 128, PM_N = 512, PM_TN = 128;
 constexpr int PM_PITCH = 128 + 16;                       // tile row pitch: 16 rows' pieces spread over all banks
 constexpr int PM_TILE = 32 * PM_PITCH;
-// LDS: second layer's weights | two stages of activations (64 pixels each) | eight tiles | start values
-constexpr int PM_W2 = 0;
-constexpr int PM_X = PM_W2 + PM_TN * PM_N;
+// LDS: two stages of activations (64 pixels each) | eight tiles | start values
+constexpr int PM_X = 0;
 constexpr int PM_TILES = PM_X + 2 * 64 * PM_K;
 constexpr int PM_START = PM_TILES + 8 * PM_TILE;
 constexpr int PM_LDS = PM_START + (PM_N + PM_TN) * 4;
@@ -62,7 +61,6 @@ template <int RK, bool RLEFT, bool TAIL>
 __global__ __launch_bounds__(PM_NT, 1) void pw_mid_kernel(const PwMidParams p) {
   constexpr bool HAS_RES = RK != 0;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  uint8_t *w2 = lds + PM_W2;
   uint8_t *xring = lds + PM_X;
   int32_t *start = reinterpret_cast<int32_t *>(lds + PM_START);
   int32_t *start2 = start + PM_N;
@@ -79,14 +77,13 @@ __global__ __launch_bounds__(PM_NT, 1) void pw_mid_kernel(const PwMidParams p) {
     for (int ks = 0; ks < 4; ++ks)
       fa[nb][ks] = *reinterpret_cast<const v4i *>(p.w + (size_t)(128 * cg + 32 * nb + frag_channel(l32)) * PM_K + 32 * ks + 16 * half);
   start[tid] = p.acc0[tid];
+  // the second layer's weights for this wave's 32 of its channels: 16 fragments, in registers as well
+  v4i wt[TAIL ? 16 : 1];
   if (TAIL) {
     if (tid < PM_TN) start2[tid] = p.t_acc0[tid];
-    // the second layer's weights: rows of 512 bytes in fragment order, their 16-byte pieces permuted by the row
 #pragma unroll
-    for (int k = 0; k < PM_TN * PM_N / 16 / PM_NT; ++k) {
-      const int i = tid + k * PM_NT, n2 = i >> 5, r = (n2 & ~31) + frag_row(n2 & 31), pc = i & 31;
-      *reinterpret_cast<v4i *>(w2 + r * PM_N + 16 * (pc ^ (r & 15))) = *reinterpret_cast<const v4i *>(p.t_w + (size_t)i * 16);
-    }
+    for (int ks = 0; ks < 16; ++ks)
+      wt[ks] = *reinterpret_cast<const v4i *>(p.t_w + (size_t)(32 * cg + frag_channel(l32)) * PM_N + 32 * ks + 16 * half);
   }
 
   const long long npair = (p.M + 63) >> 6;
@@ -214,7 +211,6 @@ __global__ __launch_bounds__(PM_NT, 1) void pw_mid_kernel(const PwMidParams p) {
       // this wave: channels 32 cg .. 32 cg + 31 of the layer behind, for its block; two accumulators
       // over alternate slices, so that consecutive matrix instructions do not wait for each other
       lds_i32 *st2 = here(start2);
-      lds_u8 *w2h = here(w2) + (32 * cg + l32) * PM_N;
       lds_u8 *yt = here(lds + PM_TILES + 4 * pb * PM_TILE) + l32 * PM_PITCH + 16 * half;
       v16i acc2[2];
 #pragma unroll
@@ -224,11 +220,8 @@ __global__ __launch_bounds__(PM_NT, 1) void pw_mid_kernel(const PwMidParams p) {
         acc2[1][4 * g] = 0; acc2[1][4 * g + 1] = 0; acc2[1][4 * g + 2] = 0; acc2[1][4 * g + 3] = 0;
       }
       // fragment reads run two slices ahead of the matrix instructions
-      v4i yb[3], wa[3];
-      auto read_slice = [&](int ks) {
-        yb[ks % 3] = *(lds_v4i *)(yt + (ks >> 2) * PM_TILE + 32 * (ks & 3));
-        wa[ks % 3] = *(lds_v4i *)(w2h + 16 * ((2 * ks + half) ^ (l32 & 15)));
-      };
+      v4i yb[3];
+      auto read_slice = [&](int ks) { yb[ks % 3] = *(lds_v4i *)(yt + (ks >> 2) * PM_TILE + 32 * (ks & 3)); };
       read_slice(0);
       read_slice(1);
 #pragma unroll
@@ -236,7 +229,7 @@ __global__ __launch_bounds__(PM_NT, 1) void pw_mid_kernel(const PwMidParams p) {
         if (ks + 2 < 16) read_slice(ks + 2);
         const v4i y = yb[ks % 3];
         const v4i ys = v4i{y.x ^ tx, y.y ^ tx, y.z ^ tx, y.w ^ tx};
-        acc2[ks & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[ks % 3], ys, acc2[ks & 1], 0, 0, 0);
+        acc2[ks & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[ks], ys, acc2[ks & 1], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
       settle_matrix_result(acc2[0]);
