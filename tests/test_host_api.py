@@ -158,9 +158,9 @@ def test_chain_planner_host_side():
 
 
 def test_chain_pairs_a_1x1_layer_with_the_layer_in_front_host_side():
-    """The 1x1 64 -> 256 layers of the first ResNet stage also compute the 1x1 layer that reads their
-    output (the next block's first layer; at the stage boundary it sits behind the shortcut projection):
-    which layers are paired, at which batch, and that the planner never lets the extra output share
+    """The 1x1 64 -> 256 layers of the first ResNet stage and the 1x1 128 -> 512 layers of the second also
+    compute the 1x1 layer that reads their output (the next block's first layer; at the boundary between
+    the first two stages it sits behind the shortcut projection): which layers are paired, at which batch, and that the planner never lets the extra output share
     memory with anything the launch reads or with the launch's own output (no GPU needed: names and
     addresses only)."""
     L = f8.lib()
@@ -175,11 +175,14 @@ def test_chain_pairs_a_1x1_layer_with_the_layer_in_front_host_side():
 
     names = [name(i, 256) for i in range(len(net.layers))]
     by_name = {S.name: i for i, S in enumerate(net.layers)}
-    pairs = {"s1b1.conv_c": "s1b2.conv_a", "s1b2.conv_c": "s1b3.conv_a", "s1b3.conv_c": "s2b1.conv_a"}
+    pairs = {"s1b1.conv_c": "s1b2.conv_a", "s1b2.conv_c": "s1b3.conv_a", "s1b3.conv_c": "s2b1.conv_a",
+             "s2b1.conv_c": "s2b2.conv_a", "s2b2.conv_c": "s2b3.conv_a", "s2b3.conv_c": "s2b4.conv_a"}
     for front, behind in pairs.items():
         width = net.layers[by_name[behind]].Cout
-        assert names[by_name[front]] == "pw1x1_ws<64x256>+1x1<%d>" % width
+        kernel = "pw1x1_ws<64x256>" if front.startswith("s1") else "pw1x1_mid<128x512>"
+        assert names[by_name[front]] == "%s+1x1<%d>" % (kernel, width)
         assert names[by_name[behind]] == "(fused)"
+    assert "+1x1" not in names[by_name["s2b4.conv_c"]]             # the third stage's first layer is 256 wide: on its own
     assert names[by_name["s2b1.ds"]] != "(fused)"                  # the layer between the last pair runs on its own
     assert names.count("(fused)") == len(pairs) + 1                # + the max pool inside the stem kernel
     assert not any("+1x1" in name(i, 8) for i in range(len(net.layers)))       # small batches: two launches
