@@ -40,11 +40,10 @@ template <int C> struct WsShape {
   static constexpr int OPITCH = C + OPITCH_PAD;
 };
 
-__device__ __forceinline__ int med3(int v, int lo, int hi) {
-  int r;
-  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
-  return r;
-}
+// Row r of a 32-channel weight fragment holds channel frag_channel(r) of its block: the matrix
+// instruction then leaves a lane with 16 consecutive channels of one pixel (16 half .. 16 half + 15),
+// which the epilogue packs into one 16-byte piece.
+__device__ __forceinline__ int frag_channel(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
 
 template <int C>
 __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p) {
@@ -121,7 +120,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   v4i nextbuf[MAXCH];
   fetch_patch(t, nextbuf);
 
-  // weights: fa[slice] = channel 32 wn + l32, bytes 32 slice + 16 half .. + 16 of its 9 C.  They reach
+  // weights: fa[slice] = channel 32 wn + frag_channel(l32), bytes 32 slice + 16 half .. + 16 of its 9 C.  They reach
   // the registers through LDS (the patch buffers are not in use yet), all 64 channels at once or 16 of 128 at a time: the
   // global loads are then contiguous (a lane reading its own fragments straight from memory would
   // touch a different cache line than every other lane, 9 C bytes apart, while every workgroup of the
@@ -150,7 +149,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
       }
       if (j + 1 < C / RPC) fetch_rows(j + 1);
       __syncthreads();
-      const int r = 32 * wn + l32;                          // this lane's channel
+      const int r = 32 * wn + frag_channel(l32);            // this lane's channel
       if (r / RPC == j) {
 #pragma unroll
         for (int sl = 0; sl < KS; ++sl)
@@ -198,15 +197,14 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
         a0[mf][sx] = base + cx * C + 16 * (half ^ ((cx >> S::KEY_SHIFT) & (S::PIECES - 1)));
       }
     }
-    v16i acc[MF];
+    // acc[mf][e] is channel 32 wn + 16 half + e of pixel 32 mf + l32.  The accumulator start values of
+    // these 16 channels are the addend of a tile's first matrix instructions: no accumulator is
+    // initialised by moves.
+    v16i acc[MF], startv;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      // acc[mf][4 g + j] is channel 32 wn + 8 g + 4 half + j
-      const v4i s0 = *reinterpret_cast<const v4i *>(start + 32 * wn + 8 * g + 4 * half);
-#pragma unroll
-      for (int mf = 0; mf < MF; ++mf) {
-        acc[mf][4 * g] = s0.x; acc[mf][4 * g + 1] = s0.y; acc[mf][4 * g + 2] = s0.z; acc[mf][4 * g + 3] = s0.w;
-      }
+      const v4i s0 = *reinterpret_cast<const v4i *>(start + 32 * wn + 16 * half + 4 * g);
+      startv[4 * g] = s0.x; startv[4 * g + 1] = s0.y; startv[4 * g + 2] = s0.z; startv[4 * g + 3] = s0.w;
     }
     // K slices: 9 taps x C / 32; the fragments of slice i + AHEAD are requested before the matrix
     // instructions of slice i are issued, so that much LDS latency is covered
@@ -228,7 +226,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
       }
 #pragma unroll
       for (int mf = 0; mf < MF; ++mf)
-        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice], fb[slice % (AHEAD + 1)][mf], acc[mf], 0, 0, 0);
+        acc[mf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[slice], fb[slice % (AHEAD + 1)][mf], slice == 0 ? startv : acc[mf], 0, 0, 0);
     }
 
     // requantise into the staging tile
@@ -236,15 +234,11 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf) {
       settle_matrix_result(acc[mf]);
+      // clip at the accumulator's scale, then one shift-and-pack instruction per value: 16 bytes per store
+      int v[16];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        // clip at the accumulator's scale, then one shift-and-pack instruction per value
-        int v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = clamp_med3(acc[mf][4 * g + j], sc.lo, sc.hi);
-        *reinterpret_cast<uint32_t *>(stage + ((32 * MF) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 8 * g + 4 * half) =
-            shift_pack4(v[0], v[1], v[2], v[3], p.shift);
-      }
+      for (int e = 0; e < 16; ++e) v[e] = clamp_med3(acc[mf][e], sc.lo, sc.hi);
+      *reinterpret_cast<v4i *>(stage + ((32 * MF) * wm + 32 * mf + l32) * OPITCH + 32 * wn + 16 * half) = shift_pack16(v, p.shift);
     }
     if (tn < t_end) store_patch(which ^ 1, nextbuf);
     if (tn + 1 < t_end) fetch_patch(tn + 1, nextbuf);      // lands during the next tile

@@ -34,9 +34,11 @@ int launch_gpool(const DwParams &p, bool vec4, hipStream_t stream);
 int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 
 // Stem re-layout for convolutions with C <= 4 input channels: explicit zero border and
-// channels padded to 4 (input), window rows padded to Sp taps of 4 channels (weights).
+// channels padded to 4 (input), window rows padded to Sp taps of 4 channels (weights).  Every dword
+// written is xor-ed with value_xor (0x80808080 turns an unsigned image, its border included, into the
+// signed form the matrix instructions take).
 int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp, int Wp, int ph, int pw,
-                     hipStream_t stream);
+                     hipStream_t stream, uint32_t value_xor = 0);
 int launch_repack_weights(const int8_t *w, void *wp, int N, int R, int S, int C, int Sp, hipStream_t stream);
 
 // Channel padding: rows of C bytes -> rows of Cp bytes (Cp % 4 == 0, Cp >= C), zeros in C..Cp-1.

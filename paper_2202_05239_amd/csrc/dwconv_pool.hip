@@ -435,7 +435,7 @@ __global__ __launch_bounds__(NT) void gpool_kernel(const DwParams p, const long 
 // pixel (one dword).  Turns a clipped-window, odd-channel convolution into one whose
 // windows are never clipped and whose taps are whole dwords.
 __global__ __launch_bounds__(NT) void pad_input_kernel(const uint8_t *x, uint32_t *xp, int B, int H, int W, int C,
-                                                       int Hp, int Wp, int ph, int pw, long long total) {
+                                                       int Hp, int Wp, int ph, int pw, long long total, uint32_t value_xor) {
   const long long gid = (long long)blockIdx.x * NT + threadIdx.x;
   if (gid >= total) return;
   const int j = (int)(gid % Wp);
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(NT) void pad_input_kernel(const uint8_t *x, uint32_
     const uint8_t *src = x + (((size_t)b * H + ih) * W + iw) * C;
     for (int c = 0; c < C; ++c) v |= (uint32_t)src[c] << (8 * c);
   }
-  xp[gid] = v;
+  xp[gid] = v ^ value_xor;
 }
 
 // The same re-layout for C = 3 (the RGB stem), four output pixels (one 16-byte store) per thread.
@@ -460,7 +460,7 @@ struct PadTiling {
 };
 
 __global__ __launch_bounds__(NT) void pad_input3_kernel(const uint8_t *x, v4i *xp, int H, int W, int Hp, int Wp, int ph,
-                                                        int pw, const PadTiling tl, uint32_t total, long long x_bytes) {
+                                                        int pw, const PadTiling tl, uint32_t total, long long x_bytes, uint32_t value_xor) {
   const uint32_t gid = blockIdx.x * NT + threadIdx.x;
   if (gid >= total) return;
   const uint32_t t = tl.fd_g.div(gid);
@@ -487,7 +487,8 @@ __global__ __launch_bounds__(NT) void pad_input3_kernel(const uint8_t *x, v4i *x
 #pragma unroll
     for (int k = 0; k < 4; ++k) out[k] = (unsigned)(iw0 + k) < (unsigned)W ? (int)px[k] : 0;
   }
-  xp[gid] = out;
+  const int vx = (int)value_xor;
+  xp[gid] = v4i{out.x ^ vx, out.y ^ vx, out.z ^ vx, out.w ^ vx};
 }
 
 // w [N][R][S][C] -> wp [N][R][Sp][4], zeros in taps S..Sp-1 and channels C..3.
@@ -629,7 +630,7 @@ int launch_maxpool(const PoolParams &p, bool vec4, hipStream_t stream) {
 }
 
 int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp, int Wp, int ph, int pw,
-                     hipStream_t stream) {
+                     hipStream_t stream, uint32_t value_xor) {
   const long long total = (long long)B * Hp * Wp;
   if (total <= 0) return 0;
   const long long x_bytes = (long long)B * H * W * C;
@@ -640,11 +641,11 @@ int launch_pad_input(const void *x, void *xp, int B, int H, int W, int C, int Hp
     tl.fd_hp = FastDiv((uint32_t)Hp);
     const uint32_t threads = (uint32_t)(total / 4);
     hipLaunchKernelGGL(pad_input3_kernel, dim3((threads + NT - 1) / NT), dim3(NT), 0, stream,
-                       static_cast<const uint8_t *>(x), static_cast<v4i *>(xp), H, W, Hp, Wp, ph, pw, tl, threads, x_bytes);
+                       static_cast<const uint8_t *>(x), static_cast<v4i *>(xp), H, W, Hp, Wp, ph, pw, tl, threads, x_bytes, value_xor);
     return (int)hipGetLastError();
   }
   hipLaunchKernelGGL(pad_input_kernel, dim3(blocks_for(total)), dim3(NT), 0, stream, static_cast<const uint8_t *>(x),
-                     static_cast<uint32_t *>(xp), B, H, W, C, Hp, Wp, ph, pw, total);
+                     static_cast<uint32_t *>(xp), B, H, W, C, Hp, Wp, ph, pw, total, value_xor);
   return (int)hipGetLastError();
 }
 

@@ -291,7 +291,8 @@ struct f8_chain {
     if (pool_role(i) == 1) {
       const void *src = tensor_ptr(L.src, x, out, workspace, batch);
       void *xp = arena(workspace) + stem[i].x_off_per_image * (size_t)batch;
-      if (launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s) != 0)
+      if (launch_pad_input(src, xp, batch, g.H, g.W, g.Cin, stem[i].Hp, stem[i].Wp, g.ph, g.pw, s,
+                           L.q.x_type == F8_U8 ? 0x80808080u : 0u) != 0)
         return F8_ERR_DEVICE;
       StemPoolParams sp;
       sp.xp = static_cast<const uint8_t *>(xp);
@@ -301,7 +302,6 @@ struct f8_chain {
       sp.B = batch; sp.Hp = stem[i].Hp; sp.Wp = stem[i].Wp;
       sp.P = g.P; sp.Q = g.Q; sp.PP = geom[i + 1].P; sp.QP = geom[i + 1].Q;
       sp.shift = L.q.fl_x + L.q.fl_w - L.q.fl_y; sp.lo = L.q.clip_lo; sp.hi = L.q.clip_hi;
-      sp.x_xor = L.q.x_type == F8_U8 ? 0x80808080u : 0u;
       sp.ntiles = 0;
       return launch_stem_pool(sp, s) == 0 ? F8_OK : F8_ERR_DEVICE;
     }
@@ -461,7 +461,9 @@ f8_status f8_chain_create(const f8_layer_desc *layers, int n_layers, int in_h, i
         sm.on = true;
         sm.Sp = (L.S + 3) / 4 * 4;
         sm.Hp = (g.P - 1) * g.sh + g.R;
-        sm.Wp = ((g.Q - 1) * g.sw + sm.Sp + 3) / 4 * 4;     // whole 16-byte groups of pixels per row
+        // whole 16-byte groups of pixels per row, and two pixels no window reaches at the end of a row (the
+        // fused stem fetches some rows 8 bytes off the 16-byte grid)
+        sm.Wp = ((g.Q - 1) * g.sw + sm.Sp + 2 + 3) / 4 * 4;
         sm.x_bytes_per_image = (size_t)sm.Hp * sm.Wp * 4;
         sm.w_off = c->const_bytes;
         c->const_bytes += round256((size_t)L.Cout * g.R * sm.Sp * 4);
