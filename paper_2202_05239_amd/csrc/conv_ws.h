@@ -21,7 +21,7 @@ struct ConvWsParams {
 
 // Geometry and operand checks (C -> C channels with C = 64 or 128, 16-byte aligned tensors, an image
 // width the LDS patch has room for).
-bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int W, int shift,
+bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int H, int W, int shift,
                         const void *x, const void *w, const void *y);
 // Output pixels per tile for C channels.
 int conv_ws_tile_pixels(int C);

@@ -1,18 +1,21 @@
 // Weights-stationary 3x3 convolution, 64 -> 64 or 128 -> 128 channels, stride 1, pad 1 (the 3x3 layers of
 // the first two ResNet stages), with the shift / clip epilogue of F8Net Eq. 2 / Eq. 9.
 //
-// With only 64 output channels a tile of the implicit GEMM reuses each activation fragment twice, so
-// the general kernel spends its time moving operands.  Here the 64 x 576 weights stay in registers
-// for the life of a workgroup (each of the four waves holds 32 output channels: 18 fragments), and
-// the activations are not expanded per tap: a workgroup takes 128 consecutive output pixels of one
-// image (raster order), keeps the input rows under them (plus one above and below) in LDS, and
-// reads every tap's fragment straight from that patch.  Rows are stored 64 W bytes apart plus one
-// pixel of zeros, which serves as the right border of one row and the left border of the next, so
-// no tap needs a bounds check.  Inside a pixel the four 16-byte pieces are stored permuted by bits 2-3 of
-// the pixel's column (piece ^ ((column >> 2) & 3)): 16 lanes reading the same piece of 16 neighbouring
-// pixels then touch 16 different bank groups instead of 4.  The workgroup walks over tiles; the patch of the tile after the
-// next is in flight meanwhile.  The requantised tile is staged in LDS and written with 16-byte
-// stores (128 pixels x 64 bytes are contiguous in NHWC).
+// With so few output channels a tile of the implicit GEMM reuses each activation fragment once or
+// twice, so the general kernel spends its time moving operands.  Here the weights stay in registers
+// for the life of a workgroup, and the activations are not expanded per tap: a workgroup takes a run
+// of consecutive output pixels of one image (raster order), keeps the input rows under them (plus
+// one above and below) in LDS, and reads every tap's fragment straight from that patch.  Rows are
+// stored C W bytes apart plus one pixel of zeros, which serves as the right border of one row and the
+// left border of the next, so no tap needs a bounds check.  Inside a pixel the 16-byte pieces are
+// stored permuted by the pixel's column, so that 16 lanes reading the same piece of 16 neighbouring
+// pixels touch 16 different bank groups instead of 4.  The workgroup walks over tiles, the next
+// patch in flight meanwhile.  The requantised pixels are staged in LDS and written with 16-byte
+// stores (consecutive pixels are contiguous in NHWC).
+//
+// Two kernels: for 128 channels each of the four waves holds 32 output channels (36 fragments) and all
+// waves work on the same 64 pixels; for 64 channels every wave holds all of them and takes its own 64
+// of a tile's 256 pixels (see there).
 #include "conv_ws.h"
 
 namespace f8 {
@@ -23,19 +26,19 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int WS_NT = 256;
 constexpr int OPITCH_PAD = 16;      // staging pitch per pixel = C + 16
 
-// Per channel count: how the four waves split a tile, and the tile size.
-//   C = 64:  2 waves along the pixels x 2 along the channels, four 32-pixel blocks per wave: 256 pixels per tile;
-//   C = 128: all 4 waves along the channels (32 each), two blocks per wave: 64 pixels per tile.
+// The 128-channel kernel: all 4 waves along the channels (32 each), two 32-pixel blocks per wave, 64 pixels
+// per tile.
 template <int C> struct WsShape {
+  static_assert(C == 128, "the 64-channel layers have a kernel of their own");
   static constexpr int WN = C / 32, WM = 4 / WN;
-  static constexpr int MF = C == 64 ? 4 : 2;    // 32-pixel blocks per wave
-  static constexpr int MAXCH = C == 64 ? 8 : 6; // 16-byte patch pieces per thread
-  static constexpr int WROWS = C == 64 ? 64 : 16;   // weight rows that pass through LDS together at set-up
+  static constexpr int MF = 2;                  // 32-pixel blocks per wave
+  static constexpr int MAXCH = 6;               // 16-byte patch pieces per thread
+  static constexpr int WROWS = 16;              // weight rows that pass through LDS together at set-up
   static constexpr int TILE = 32 * MF * WM;
   static constexpr int KPT = C / 32;            // K slices per tap
   static constexpr int KS = 9 * KPT;            // K slices in all
   static constexpr int PIECES = C / 16;         // 16-byte pieces per pixel
-  static constexpr int KEY_SHIFT = C == 64 ? 2 : 1;   // piece ^= (column >> KEY_SHIFT) & (PIECES - 1)
+  static constexpr int KEY_SHIFT = 1;           // piece ^= (column >> KEY_SHIFT) & (PIECES - 1)
   static constexpr int AHEAD = 2;               // K slices the fragment reads run ahead
   static constexpr int OPITCH = C + OPITCH_PAD;
 };
@@ -257,6 +260,206 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
   }
 }
 
+
+// ---- 64 -> 64 channels ---------------------------------------------------------------------------
+// Every wave holds all 64 x 576 weights (36 fragments) and takes 64 of the tile's 256 pixels: a pixel
+// fragment read from the patch then feeds two matrix instructions, which halves the LDS traffic that
+// bounds the kernel above.  The registers this takes are freed by letting the load unit copy the patch
+// into LDS directly (no staging registers, no address table): unsigned activations are xor-ed when a
+// fragment is read instead of when the patch is stored.  Rows of the patch outside the image are
+// fetched with an offset the buffer descriptor rejects, which writes zeros; the border pixel of every
+// row is never written at all.  Each wave stages and stores its own 64 pixels, so one barrier per tile
+// (the hand-over of the patch buffers) is left.
+// The same LDS address, made opaque to the optimiser: reads through it stay where they are written
+// (the start values never change, so they would otherwise be hoisted out of the tile loop and held in
+// registers the weights need).
+typedef __attribute__((address_space(3))) const int32_t lds_i32;
+typedef __attribute__((address_space(3))) const v4i lds_cv4i;
+__device__ __forceinline__ lds_i32 *here(const int32_t *shared_array) {
+  lds_i32 *q = (lds_i32 *)shared_array;
+  asm volatile("" : "+v"(q));
+  return q;
+}
+
+constexpr int W64_TILE = 256, W64_C = 64, W64_KS = 18, W64_OPITCH = W64_C + OPITCH_PAD;
+typedef __attribute__((address_space(3))) void lds_void;
+
+__global__ __launch_bounds__(WS_NT, 2) void conv_ws64_kernel(const ConvWsParams p) {
+  constexpr int C = W64_C, KS = W64_KS, OPITCH = W64_OPITCH;
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  __shared__ __attribute__((aligned(16))) int32_t start[C];
+  const int patch_bytes = C + p.nrows * p.pitch;            // leading zero pixel, then the rows
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int stage_at = 2 * patch_bytes + wave * (64 * OPITCH);      // this wave's 64 pixels of the result
+  const int HW = p.H * p.W;
+
+  const int per = p.ntiles / (int)gridDim.x, rem = p.ntiles % (int)gridDim.x;
+  int t = (int)blockIdx.x * per + min((int)blockIdx.x, rem);
+  const int t_end = t + per + ((int)blockIdx.x < rem ? 1 : 0);
+  if (t >= t_end) return;
+
+  const int zx = (int)p.x_xor;
+  auto tile_coords = [&](int tt, int &b, int &m0, int &row0) {
+    const uint32_t bi = p.fd_tpi.div((uint32_t)tt);
+    b = (int)bi;
+    m0 = W64_TILE * (int)((uint32_t)tt - bi * p.fd_tpi.d);
+    row0 = (int)p.fd_w.div((uint32_t)m0) - 1;               // first patch row: one above the tile's first
+  };
+  // The patch of tile tt into buffer `which`: the rows behind the leading pixel are one linear range of
+  // 16-byte pieces; piece L is piece L % 4 of pixel (L / 4) % (W + 1) of row L / (4 (W + 1)), the
+  // last pixel of a row being the border.  Wave w issues the instructions 4 k + w, 64 pieces each (at
+  // most 8 per wave: the launcher checks it).  What this lane fetches with instruction k never changes:
+  // its byte offset from the patch's first row (low 24 bits) and its row (bits 24-30); bit 31 marks
+  // lanes that fetch nothing (border pixels, pieces past the end).
+  const int row_pieces = 4 * (p.W + 1), pieces = p.nrows * row_pieces;
+  const int image_bytes = HW * C;
+  int what[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int L = (4 * k + wave) * 64 + lane;
+    const int row = (int)p.fd_rowchunks.div((uint32_t)L), r4 = L - row * row_pieces;
+    const int col = r4 >> 2, part = (r4 & 3) ^ ((col >> 2) & 3);
+    what[k] = (L < pieces && col < p.W) ? (((row * p.W + col) * C + 16 * part) | (row << 24)) : (int)0x80000000;
+  }
+  auto fetch_patch = [&](int tt, int which) {
+    int b, m0, row0;
+    tile_coords(tt, b, m0, row0);
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(p.x) + (size_t)b * (size_t)image_bytes, 0, image_bytes, 0x00027000);
+    const int base = row0 * p.W * C;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if ((4 * k + wave) * 64 < pieces) {                   // uniform
+        const int y = row0 + ((what[k] >> 24) & 127);
+        // rows outside the image: an offset the descriptor rejects, which writes zeros
+        const uint32_t off = (unsigned)y < (unsigned)p.H ? (uint32_t)(base + (what[k] & 0xffffff)) : 0x80000000u;
+        if (what[k] >= 0)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_void *)(lds + which * patch_bytes + C + (4 * k + wave) * 1024), 16, off, 0, 0, 0);
+      }
+    }
+  };
+
+  // the first tile's input rows are requested before anything else: they come from HBM, the weights from L2
+  fetch_patch(t, 0);
+
+  // weights: fa[nb][slice] = channel 32 nb + frag_channel(l32), bytes 32 slice + 16 half .. + 16 of its
+  // 576, through LDS so that the global loads are contiguous (rows 576 + 16 bytes apart there).  They
+  // pass through the end of the LDS allocation, behind the first patch buffer.
+  v4i fa[2][KS];
+  {
+    constexpr int ROWB = 9 * C, WPITCH = ROWB + 16, PPR = ROWB / 16;
+    constexpr int PPT = C * PPR / WS_NT;                     // 9 pieces per thread
+    uint8_t *wl = lds + 2 * patch_bytes + W64_TILE * OPITCH - C * WPITCH;
+    v4i wbuf[PPT];
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) wbuf[k] = *reinterpret_cast<const v4i *>(p.w + (size_t)(tid + k * WS_NT) * 16);
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      const int i = tid + k * WS_NT, row = i / PPR, col = i - row * PPR;
+      *reinterpret_cast<v4i *>(wl + row * WPITCH + 16 * col) = wbuf[k];
+    }
+    if (tid < C) start[tid] = p.acc0[tid];
+    __syncthreads();
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int sl = 0; sl < KS; ++sl)
+        fa[nb][sl] = *reinterpret_cast<const v4i *>(wl + (32 * nb + frag_channel(l32)) * WPITCH + 32 * sl + 16 * half);
+    __syncthreads();
+  }
+  // the leading pixel and the border pixel behind every row of both patch buffers: zero for good
+  for (int i = tid; i < 2 * (1 + p.nrows) * 4; i += WS_NT) {
+    const int which_buf = i / ((1 + p.nrows) * 4), j = i - which_buf * ((1 + p.nrows) * 4);
+    const int px = j >> 2, part = j & 3;                    // px 0: the leading pixel; px r + 1: behind row r
+    const int off = px == 0 ? 0 : C + (px - 1) * p.pitch + p.W * C;
+    *reinterpret_cast<v4i *>(lds + which_buf * patch_bytes + off + 16 * part) = v4i{0, 0, 0, 0};
+  }
+  const ScaledClip sc = scaled_clip(p.lo, p.hi, p.shift);
+  int which = 0;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's part of the first patch
+
+  for (; t < t_end; ++t) {
+    int b, m0, row0;
+    tile_coords(t, b, m0, row0);
+    // Every wave has waited for its part of this tile's patch, and is past the previous tile's last
+    // fragment read: behind the barrier the patch is complete and the other buffer is free for the
+    // next tile's patch, which then has a whole tile's time to arrive.
+    __syncthreads();
+    if (t + 1 < t_end) fetch_patch(t + 1, which ^ 1);
+
+    // the wave's 64 pixels in two passes of 32, so that the accumulators take 32 registers
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf) {
+      // where the windows of this lane's pixel start in the patch, per window column (see above)
+      int a0[3];
+      {
+        int m = m0 + 64 * wave + 32 * mf + l32;
+        if (m >= HW) m = m0;
+        const int y = (int)p.fd_w.div((uint32_t)m), xq = m - y * p.W;
+        const int base = which * patch_bytes + C + (y - row0 - 1) * p.pitch;
+#pragma unroll
+        for (int sx = 0; sx < 3; ++sx) {
+          const int cx = xq - 1 + sx;                                 // -1 and W are the border pixels
+          a0[sx] = base + cx * C + 16 * (half ^ ((cx >> 2) & 3));
+        }
+      }
+      // acc[nb][e] is channel 32 nb + 16 half + e of pixel 64 wave + 32 mf + l32.  The start values are
+      // the addend of the pass's first matrix instructions (no accumulator is initialised by moves); they
+      // are read here, for every pass, so that they occupy no registers during the K loop.
+      v16i acc[2], sv[2];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const v4i s0 = *reinterpret_cast<lds_cv4i *>(here(start) + 32 * nb + 16 * half + 4 * g);
+          sv[nb][4 * g] = s0.x; sv[nb][4 * g + 1] = s0.y; sv[nb][4 * g + 2] = s0.z; sv[nb][4 * g + 3] = s0.w;
+        }
+      auto frag = [&](int slice) {
+        const int tap = slice / 2, k32 = slice % 2;
+        return *reinterpret_cast<const v4i *>(&lds[(a0[tap % 3] ^ (32 * k32)) + (tap / 3) * p.pitch]);
+      };
+      constexpr int AHEAD = 3;
+      v4i fb[AHEAD + 1];
+#pragma unroll
+      for (int i = 0; i < AHEAD; ++i) fb[i] = frag(i);
+#pragma unroll
+      for (int slice = 0; slice < KS; ++slice) {
+        if (slice + AHEAD < KS) fb[(slice + AHEAD) % (AHEAD + 1)] = frag(slice + AHEAD);
+        // (unsigned activations become signed here, next to their use: applied where the fragment is read,
+        // the xor would wait for the read it belongs to and undo the run-ahead)
+        const v4i raw = fb[slice % (AHEAD + 1)];
+        const v4i f = v4i{raw.x ^ zx, raw.y ^ zx, raw.z ^ zx, raw.w ^ zx};
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[nb][slice], f, slice == 0 ? sv[nb] : acc[nb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // requantise into this wave's staging rows: 16 bytes per lane and block
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        settle_matrix_result(acc[nb]);
+        int v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = clamp_med3(acc[nb][e], sc.lo, sc.hi);
+        *reinterpret_cast<v4i *>(lds + stage_at + (32 * mf + l32) * OPITCH + 32 * nb + 16 * half) = shift_pack16(v, p.shift);
+      }
+    }
+    // The wait for the next patch goes here, before this tile's stores are issued (loads and stores share
+    // one counter): the patch was requested a whole pass over the weights ago.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // 64 pixels x 64 bytes, contiguous in the output: 16 bytes per store, 1 KiB per instruction
+    uint8_t *yt = p.y + ((size_t)b * HW + m0 + 64 * wave) * C;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = lane + 64 * k, px = c >> 2, part = c & 3;
+      const v4i v = *reinterpret_cast<const v4i *>(lds + stage_at + px * OPITCH + 16 * part);
+      if (m0 + 64 * wave + px < HW) *reinterpret_cast<v4i *>(yt + (size_t)c * 16) = v;
+    }
+    which ^= 1;
+  }
+}
+
 constexpr size_t WS_LDS_MAX = 80 * 1024 - 1024;
 
 template <int C> int ws_nrows(int W) { return (W - 1 + WsShape<C>::TILE - 1) / W + 1 + 2; }     // rows a tile can touch, plus one above and below
@@ -299,17 +502,61 @@ int launch_ws(ConvWsParams p, hipStream_t stream) {
   return (int)hipGetLastError();
 }
 
+
+size_t ws64_lds_bytes(int W) {
+  const size_t nrows = (size_t)((W - 1 + W64_TILE - 1) / W + 1 + 2);
+  const size_t tiles = 2 * (W64_C + nrows * (W + 1) * W64_C) + (size_t)W64_TILE * W64_OPITCH;
+  const size_t weights = (size_t)W64_C * (9 * W64_C + 16);
+  return tiles > weights ? tiles : weights;
+}
+// (the weights pass through the end of the allocation while the first patch arrives in the first buffer)
+bool ws64_fits(int W) {
+  if (W < 8 || W > 64) return false;
+  const size_t nrows = (size_t)((W - 1 + W64_TILE - 1) / W + 1 + 2);
+  const size_t patch = W64_C + nrows * (W + 1) * W64_C, weights = (size_t)W64_C * (9 * W64_C + 16);
+  if (nrows * (W + 1) * 4 > 8 * 256) return false;          // at most 8 fetch instructions per wave and patch
+  return ws64_lds_bytes(W) <= WS_LDS_MAX && 2 * patch + (size_t)W64_TILE * W64_OPITCH >= patch + weights;
+}
+
+int launch_ws64(ConvWsParams p, hipStream_t stream) {
+  if (!ws64_fits(p.W) || (long long)p.H * p.W * W64_C > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+  const int HW = p.H * p.W;
+  p.tiles_per_image = (HW + W64_TILE - 1) / W64_TILE;
+  const long long ntiles = (long long)p.B * p.tiles_per_image;
+  if (ntiles > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+  p.ntiles = (int)ntiles;
+  p.nrows = (p.W - 1 + W64_TILE - 1) / p.W + 1 + 2;    // rows 256 consecutive pixels can touch, plus one above and below
+  p.pitch = (p.W + 1) * W64_C;
+  p.nchunks = p.nrows * (p.W + 1) * 4;
+  p.fd_tpi = FastDiv((uint32_t)p.tiles_per_image);
+  p.fd_w = FastDiv((uint32_t)p.W);
+  p.fd_rowchunks = FastDiv((uint32_t)(4 * (p.W + 1)));
+  const size_t smem = ws64_lds_bytes(p.W);
+  static unsigned long long done_mask = 0;       // raising the dynamic LDS limit is per device and idempotent
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+  if (dev < 0 || dev > 63 || !((done_mask >> dev) & 1ull)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv_ws64_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_MAX);
+    if (e != hipSuccess) return (int)e;
+    if (dev >= 0 && dev <= 63) done_mask |= 1ull << dev;
+  }
+  const int grid = (int)(ntiles < 512 ? ntiles : 512);       // two workgroups per CU walk over the tiles
+  hipLaunchKernelGGL(conv_ws64_kernel, dim3(grid), dim3(WS_NT), smem, stream, p);
+  return (int)hipGetLastError();
+}
+
 }  // namespace
 
-int conv_ws_tile_pixels(int C) { return C == 64 ? WsShape<64>::TILE : WsShape<128>::TILE; }
+int conv_ws_tile_pixels(int C) { return C == 64 ? W64_TILE : WsShape<128>::TILE; }
 
-bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int W, int shift,
+bool conv_ws_applicable(int Cin, int Cout, int R, int S, int sh, int sw, int ph, int pw, int H, int W, int shift,
                         const void *x, const void *w, const void *y) {
   if (Cin != Cout || (Cin != 64 && Cin != 128) || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1) return false;
   if (shift < 0) return false;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(y);
   if (bits & 15) return false;
-  return Cin == 64 ? ws_fits<64>(W) : ws_fits<128>(W);
+  return Cin == 64 ? ws64_fits(W) && (long long)H * W * W64_C <= 0x7fffffffLL : ws_fits<128>(W);
 }
 
 int launch_conv_ws(ConvWsParams p, hipStream_t stream) {
@@ -318,7 +565,7 @@ int launch_conv_ws(ConvWsParams p, hipStream_t stream) {
       ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w) | reinterpret_cast<uintptr_t>(p.y) |
         reinterpret_cast<uintptr_t>(p.acc0)) & 15))
     return (int)hipErrorInvalidValue;
-  return p.C == 64 ? launch_ws<64>(p, stream) : launch_ws<128>(p, stream);
+  return p.C == 64 ? launch_ws64(p, stream) : launch_ws<128>(p, stream);
 }
 
 }  // namespace f8

@@ -102,7 +102,7 @@ static bool use_conv_ws(const void *x, const int8_t *w, const void *y, const voi
   // 20-30 % ahead once every workgroup walks over several tiles
   const int granule = g.Cin == 64 ? 128 : 64;       // pixels
   if ((long long)g.B * ((g.H * g.W + granule - 1) / granule) < tuning().conv_ws_min.load(std::memory_order_relaxed)) return false;
-  return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
+  return conv_ws_applicable(g.Cin, g.Cout, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.H, g.W, q.fl_x + q.fl_w - q.fl_y, x, w, y);
 }
 
 // So do the 1x1 64 -> 256 layers (weights in registers, every wave streams pixels on its own).
