@@ -294,3 +294,14 @@ def test_second_output_format_host_side():
     bad = make_descs(net)
     bad[i].q2.y_type = f8.F8_S32
     assert L.f8_chain_create(bad, len(net.layers), 64, 64, 3, f8.F8_S8, ctypes.byref(h)) == 5
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU: bench.py with --gpus above 1 exits with a message and a non-zero
+    status before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
