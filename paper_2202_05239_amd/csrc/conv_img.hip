@@ -170,35 +170,27 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
 #pragma unroll
       for (int j = 0; j < IMG_MB; ++j) ar[j] += IMG_PW * IMG_PITCH;
     }
-    __syncthreads();                    // every wave is done with the patch: it becomes the staging tile
-
-    // ---- epilogue: clip at the accumulator's scale, shift-and-pack, rows of 256 bytes in LDS ----
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-      for (int j = 0; j < IMG_MB; ++j) {
-        settle_matrix_result(acc[q][j]);
-        int v[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
-        const v4i pk = shift_pack16(v, sh);
-        const int m = 32 * j + l32;
-        if (m < HW) *reinterpret_cast<v4i *>(lds + m * IMG_PITCH + 32 * (2 * wave + q) + 16 * half) = pk;
-      }
-    __syncthreads();
+    // ---- epilogue: clip at the accumulator's scale, shift-and-pack; a lane's 16 channels are a 16-byte
+    // piece of an output row and go straight to memory (the wave's two channel blocks make runs of 64
+    // bytes per pixel); pixels past the image get an offset the descriptor rejects ----
     {
-      // the image's output is contiguous: piece i of it is piece i % 16 of staged row i / 16;
-      // pieces past the end have offsets the descriptor rejects
       const __amdgpu_buffer_rsrc_t yres =
           __builtin_amdgcn_make_buffer_rsrc(p.y + (size_t)img * image_bytes, 0, image_bytes, 0x00027000);
 #pragma unroll
-      for (int k = 0; k < IMG_MB * 32 * 16 / IMG_NT; ++k) {
-        const int i = tid + k * IMG_NT;
-        const v4i v = *reinterpret_cast<const v4i *>(lds + (i >> 4) * IMG_PITCH + 16 * (i & 15));
-        __builtin_amdgcn_raw_buffer_store_b128(v, yres, i * 16, 0, 0);
+      for (int j = 0; j < IMG_MB; ++j) {
+        const int m = 32 * j + l32;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          settle_matrix_result(acc[q][j]);
+          int v[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
+          const uint32_t off = m < HW ? (uint32_t)(m * IMG_C + 32 * (2 * wave + q) + 16 * half) : 0x80000000u;
+          __builtin_amdgcn_raw_buffer_store_b128(shift_pack16(v, sh), yres, off, 0, 0);
+        }
       }
     }
-    __syncthreads();                    // the staging tile is read out before the next image overwrites it
+    __syncthreads();                    // every wave is done with the patch before the next image overwrites it
   }
 }
 
@@ -211,9 +203,7 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_kernel(const ConvImgParams
 // streamed once per pass.  The patch stays where it is between the passes.
 // (The same with 64 channels on bands of 28 x 56 pixels, every wave holding all weights in registers,
 // measured 45 us against the 35 us of the weights-stationary kernel on the 56 x 56 layers, and is
-// not built.)  It cannot double as the staging tile here, so
-// every wave passes its results through a small tile of its own (32 pixels x its 64 channels) and
-// stores 64-byte runs.
+// not built.)  Results go straight from the registers to memory, as 16-byte pieces of output rows.
 template <int C> struct BandShape {
   static_assert(C == 128, "one instantiation");
   static constexpr int WM = 2, WN = 4 / WM;
@@ -223,10 +213,9 @@ template <int C> struct BandShape {
   static constexpr int PITCH = C + 16;                  // bytes per patch pixel: 16 neighbouring pixels spread over all banks
   static constexpr int KPT = C / 32;                    // K slices per tap
   static constexpr int KS = 9 * KPT;
-  static constexpr int TPITCH = 64 + 16;                // staging tile row pitch
   // (two patch rows more, where the reads issued behind the last slice land)
   static constexpr int PATCH = (PROWS + 2) * PCOLS * PITCH;
-  static constexpr int LDS = PATCH + 4 * 32 * TPITCH;
+  static constexpr int LDS = PATCH;
   static constexpr int MB0 = 7, MB1 = 6;                // blocks per wave in the two passes
   static constexpr int PPP = C / 16;                    // 16-byte pieces per pixel
 };
@@ -234,7 +223,7 @@ template <int C> struct BandShape {
 template <int C>
 __global__ __launch_bounds__(IMG_NT, 1) void conv_img_band_kernel(const ConvImgParams p) {
   using S = BandShape<C>;
-  constexpr int PITCH = S::PITCH, PCOLS = S::PCOLS, KPT = S::KPT, KS = S::KS, TPITCH = S::TPITCH;
+  constexpr int PITCH = S::PITCH, PCOLS = S::PCOLS, KPT = S::KPT, KS = S::KS;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
@@ -242,7 +231,6 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_band_kernel(const ConvImgP
   const int image_bytes = p.H * p.W * C;
   const int bands = (p.H + S::BR - 1) / S::BR;
   lds_u8 *patch = (lds_u8 *)lds;
-  uint8_t *tile = lds + S::PATCH + wave * (32 * TPITCH);
 
   // this wave's weights: channel blocks 2 wn and 2 wn + 1
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
@@ -255,8 +243,6 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_band_kernel(const ConvImgP
   const int zx = (int)p.x_xor;
   const ScaledClip c1 = scaled_clip(p.lo, p.hi, p.shift);
   const int sh = p.shift;
-  // Row-piece role of the staging tile: 4 pieces per row, 16 rows per instruction.
-  const int trow = lane >> 2, tpiece = lane & 3;
 
   for (int u = blockIdx.x; u < p.B * bands; u += gridDim.x) {
     const int img = u / bands, row0 = (u - img * bands) * S::BR;     // first output row of the band
@@ -346,25 +332,20 @@ __global__ __launch_bounds__(IMG_NT, 1) void conv_img_band_kernel(const ConvImgP
           for (int j = 0; j < MBP; ++j) ar[j] += PCOLS * PITCH;
         }
       }
-      // epilogue, a block of 32 pixels at a time through the wave's own tile: clip at the accumulator's
-      // scale, shift-and-pack, then rows of 64 bytes to memory (rows past the band get an offset the
-      // descriptor rejects)
+      // epilogue: clip at the accumulator's scale, shift-and-pack; a lane's 16 channels are a 16-byte piece
+      // of an output row and go straight to memory (pixels past the band get an offset the descriptor
+      // rejects)
 #pragma unroll
       for (int j = 0; j < MBP; ++j) {
+        const int m = 32 * (first + j) + l32;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
           settle_matrix_result(acc[q][j]);
           int v[16];
 #pragma unroll
           for (int i = 0; i < 16; ++i) v[i] = clamp_med3(acc[q][j][i], c1.lo, c1.hi);
-          *reinterpret_cast<v4i *>(tile + l32 * TPITCH + 32 * q + 16 * half) = shift_pack16(v, sh);
-        }
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          const int row = 16 * k + trow, m = 32 * (first + j) + row;
-          const v4i o = *reinterpret_cast<const v4i *>(tile + row * TPITCH + 16 * tpiece);
-          const uint32_t off = m < HWu ? (uint32_t)((row0 * p.W + m) * C + 64 * wn + 16 * tpiece) : 0x80000000u;
-          __builtin_amdgcn_raw_buffer_store_b128(o, yres, off, 0, 0);
+          const uint32_t off = m < HWu ? (uint32_t)((row0 * p.W + m) * C + 64 * wn + 32 * q + 16 * half) : 0x80000000u;
+          __builtin_amdgcn_raw_buffer_store_b128(shift_pack16(v, sh), yres, off, 0, 0);
         }
       }
     };

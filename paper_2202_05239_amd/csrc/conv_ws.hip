@@ -268,7 +268,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws_kernel(const ConvWsParams p)
 // into LDS directly (no staging registers, no address table): unsigned activations are xor-ed when a
 // fragment is read instead of when the patch is stored.  Rows of the patch outside the image are
 // fetched with an offset the buffer descriptor rejects, which writes zeros; the border pixel of every
-// row is never written at all.  Each wave stages and stores its own 64 pixels, so one barrier per tile
+// row is never written at all.  A lane's 16 channels of a pixel go straight to memory, so one barrier per tile
 // (the hand-over of the patch buffers) is left.
 // The same LDS address, made opaque to the optimiser: reads through it stay where they are written
 // (the start values never change, so they would otherwise be hoisted out of the tile loop and held in
@@ -281,17 +281,19 @@ __device__ __forceinline__ lds_i32 *here(const int32_t *shared_array) {
   return q;
 }
 
-constexpr int W64_TILE = 256, W64_C = 64, W64_KS = 18, W64_OPITCH = W64_C + OPITCH_PAD;
+constexpr int W64_TILE = 256, W64_C = 64, W64_KS = 18;
+// LDS behind the two patch buffers: at set-up the 64 x 592 bytes of weights pass through the end of the
+// allocation (the second buffer and this much behind it) while the first patch arrives in the first buffer
+constexpr int W64_SPARE = 20 * 1024;
 typedef __attribute__((address_space(3))) void lds_void;
 
 __global__ __launch_bounds__(WS_NT, 2) void conv_ws64_kernel(const ConvWsParams p) {
-  constexpr int C = W64_C, KS = W64_KS, OPITCH = W64_OPITCH;
+  constexpr int C = W64_C, KS = W64_KS;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   __shared__ __attribute__((aligned(16))) int32_t start[C];
   const int patch_bytes = C + p.nrows * p.pitch;            // leading zero pixel, then the rows
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int stage_at = 2 * patch_bytes + wave * (64 * OPITCH);      // this wave's 64 pixels of the result
   const int HW = p.H * p.W;
 
   const int per = p.ntiles / (int)gridDim.x, rem = p.ntiles % (int)gridDim.x;
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws64_kernel(const ConvWsParams 
   {
     constexpr int ROWB = 9 * C, WPITCH = ROWB + 16, PPR = ROWB / 16;
     constexpr int PPT = C * PPR / WS_NT;                     // 9 pieces per thread
-    uint8_t *wl = lds + 2 * patch_bytes + W64_TILE * OPITCH - C * WPITCH;
+    uint8_t *wl = lds + 2 * patch_bytes + W64_SPARE - C * WPITCH;
     v4i wbuf[PPT];
 #pragma unroll
     for (int k = 0; k < PPT; ++k) wbuf[k] = *reinterpret_cast<const v4i *>(p.w + (size_t)(tid + k * WS_NT) * 16);
@@ -389,6 +391,7 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws64_kernel(const ConvWsParams 
     if (t + 1 < t_end) fetch_patch(t + 1, which ^ 1);
 
     // the wave's 64 pixels in two passes of 32, so that the accumulators take 32 registers
+    v4i pk[2][2];
 #pragma unroll
     for (int mf = 0; mf < 2; ++mf) {
       // where the windows of this lane's pixel start in the patch, per window column (see above)
@@ -435,26 +438,27 @@ __global__ __launch_bounds__(WS_NT, 2) void conv_ws64_kernel(const ConvWsParams 
           acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[nb][slice], f, slice == 0 ? sv[nb] : acc[nb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // requantise into this wave's staging rows: 16 bytes per lane and block
+      // requantise: 16 bytes per lane and block, kept until both passes are done
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         settle_matrix_result(acc[nb]);
         int v[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) v[e] = clamp_med3(acc[nb][e], sc.lo, sc.hi);
-        *reinterpret_cast<v4i *>(lds + stage_at + (32 * mf + l32) * OPITCH + 32 * nb + 16 * half) = shift_pack16(v, p.shift);
+        pk[mf][nb] = shift_pack16(v, p.shift);
       }
     }
     // The wait for the next patch goes here, before this tile's stores are issued (loads and stores share
     // one counter): the patch was requested a whole pass over the weights ago.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // 64 pixels x 64 bytes, contiguous in the output: 16 bytes per store, 1 KiB per instruction
-    uint8_t *yt = p.y + ((size_t)b * HW + m0 + 64 * wave) * C;
+    // a lane's 16 channels are a 16-byte piece of an output row: straight to memory
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int c = lane + 64 * k, px = c >> 2, part = c & 3;
-      const v4i v = *reinterpret_cast<const v4i *>(lds + stage_at + px * OPITCH + 16 * part);
-      if (m0 + 64 * wave + px < HW) *reinterpret_cast<v4i *>(yt + (size_t)c * 16) = v;
+    for (int mf = 0; mf < 2; ++mf) {
+      const int m = m0 + 64 * wave + 32 * mf + l32;
+      uint8_t *yt = p.y + ((size_t)b * HW + m) * C + 16 * half;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        if (m < HW) *reinterpret_cast<v4i *>(yt + 32 * nb) = pk[mf][nb];
     }
     which ^= 1;
   }
@@ -505,7 +509,7 @@ int launch_ws(ConvWsParams p, hipStream_t stream) {
 
 size_t ws64_lds_bytes(int W) {
   const size_t nrows = (size_t)((W - 1 + W64_TILE - 1) / W + 1 + 2);
-  const size_t tiles = 2 * (W64_C + nrows * (W + 1) * W64_C) + (size_t)W64_TILE * W64_OPITCH;
+  const size_t tiles = 2 * (W64_C + nrows * (W + 1) * W64_C) + (size_t)W64_SPARE;
   const size_t weights = (size_t)W64_C * (9 * W64_C + 16);
   return tiles > weights ? tiles : weights;
 }
@@ -515,7 +519,7 @@ bool ws64_fits(int W) {
   const size_t nrows = (size_t)((W - 1 + W64_TILE - 1) / W + 1 + 2);
   const size_t patch = W64_C + nrows * (W + 1) * W64_C, weights = (size_t)W64_C * (9 * W64_C + 16);
   if (nrows * (W + 1) * 4 > 8 * 256) return false;          // at most 8 fetch instructions per wave and patch
-  return ws64_lds_bytes(W) <= WS_LDS_MAX && 2 * patch + (size_t)W64_TILE * W64_OPITCH >= patch + weights;
+  return ws64_lds_bytes(W) <= WS_LDS_MAX && 2 * patch + (size_t)W64_SPARE >= patch + weights;
 }
 
 int launch_ws64(ConvWsParams p, hipStream_t stream) {
